@@ -1,0 +1,210 @@
+"""fp64 CPU oracle of one Orth-Dion / stripped-Dion optimizer step.
+
+TEST INFRASTRUCTURE ONLY.  This file is the slow, plain reference the HIP path
+is judged against.  Only the tests, the smoke check and the benchmark's
+CPU-baseline leg may import it; the product path never does, and it shares no
+code with the HIP sources.
+
+What it computes (paper Alg. 1, "Orth-Dion / Stripped Dion (one step)", and the
+two listings of App. B.1), in the notation of the library interface
+(paper name -> name here):  buffer M_t -> B,  residual R_t -> M,  U_t -> P,
+W_t -> R,  right factor V -> Q,  eta -> lr.
+
+    B      = M + G                     Alg. 1 line 1  (buffer = gradient + residual)
+    P_raw  = B Q_prev                  Alg. 1 line 2  (one subspace-iteration step)
+    P      = orth(P_raw)               Alg. 1 line 2  (left factor via QR)
+    R      = B^T P                     Alg. 1 line 3
+    Q      = orth(R)  |  ColNorm(R)    Alg. 1 line 4  (Orth-Dion | Dion, Sec. 2 table)
+    X_new  = X - lr P Q^T              Alg. 1 lines 5-6
+    M_new  = a B - b P R^T             Alg. 1 line 7 and the reading below
+    Q_prev = Q                         Alg. 1 line 8  (warm start)
+
+Readings of points the paper leaves open:
+  * orth(A) is the Q factor of the thin QR factorisation A = Q T whose triangular
+    factor has a positive diagonal.  The paper only says "QR"; for full column
+    rank this factor is unique, which is what makes P Q^T well defined (a
+    different orthonormal basis of the same span gives a different update).
+  * error feedback: the library's default is M_new = B - (1 - mu) P R^T
+    ("dion" form: a = 1, b = 1 - mu).  Alg. 1 line 7 prints
+    beta (B - P (P^T B)) ("paper" form: a = b = beta, with beta passed as mu).
+    Both are a B - b P R^T and coincide at mu = 0 / beta = 1.
+  * ColNorm divides each column of R by its Euclidean length (abstract and
+    Sec. 3: unit-length columns, Gram diagonal 1); no epsilon is added.
+  * bf16 parameters: the new parameter is the fp64 result rounded to bfloat16
+    with round-to-nearest-even; the paper does not discuss rounding.
+
+Every product is a plain numpy matmul in float64; the QR is Householder
+reflections written out below.  Nothing is blocked, fused or reordered.
+"""
+from __future__ import annotations
+
+from typing import Dict, Optional, Tuple
+
+import numpy as np
+
+__all__ = ["thin_qr_positive", "col_norm", "ef_coefficients", "OrthDionOracle",
+           "bf16_bits_to_f64", "f64_to_bf16_bits", "rel_fro"]
+
+
+# ---------------------------------------------------------------- storage helpers
+
+def bf16_bits_to_f64(bits: np.ndarray) -> np.ndarray:
+    """Exact value of bfloat16 bit patterns (uint16) as float64."""
+    u = np.asarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+    return u.view(np.float32).astype(np.float64)
+
+
+def f64_to_bf16_bits(x: np.ndarray) -> np.ndarray:
+    """Round float64 to bfloat16, round-to-nearest-even, directly from the fp64 value
+    (no intermediate fp32 rounding).  Finite inputs in bf16's normal range only."""
+    x = np.asarray(x, dtype=np.float64)
+    mant, expo = np.frexp(x)                     # x = mant * 2^expo, 0.5 <= |mant| < 1
+    # bf16 keeps 8 significant bits: quantum is 2^(expo - 8); subnormals: 2^-133
+    q = np.ldexp(1.0, np.maximum(expo - 8, -133))
+    y = np.rint(x / q) * q                       # rint = round half to even
+    y32 = y.astype(np.float32)                   # exact: y has <= 8 significant bits
+    return (y32.view(np.uint32) >> np.uint32(16)).astype(np.uint16)
+
+
+def rel_fro(a: np.ndarray, b: np.ndarray) -> float:
+    """||a - b||_F / ||b||_F in float64 (b is the reference)."""
+    a = np.asarray(a, dtype=np.float64)
+    b = np.asarray(b, dtype=np.float64)
+    den = float(np.linalg.norm(b))
+    num = float(np.linalg.norm(a - b))
+    return num / den if den > 0.0 else num
+
+
+# ---------------------------------------------------------------- orth / ColNorm
+
+def thin_qr_positive(a: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """Thin QR of ``a`` (rows >= cols) by Householder reflections: ``a = q @ t`` with
+    ``q`` having orthonormal columns and ``t`` upper triangular with ``diag(t) > 0``.
+
+    This is the ``orth`` of Alg. 1 lines 2 and 4 under the positive-diagonal reading.
+    """
+    a = np.array(a, dtype=np.float64, copy=True)
+    rows, cols = a.shape
+    if rows < cols:
+        raise ValueError("thin QR needs rows >= cols")
+    vs = []
+    for j in range(cols):
+        x = a[j:, j]
+        normx = np.sqrt(np.dot(x, x))
+        v = x.copy()
+        if normx > 0.0:
+            alpha = -normx if x[0] >= 0.0 else normx     # reflect x onto alpha * e_1
+            v[0] -= alpha
+            vnorm = np.sqrt(np.dot(v, v))
+            if vnorm > 0.0:
+                v /= vnorm
+                a[j:, j:] -= 2.0 * np.outer(v, v @ a[j:, j:])
+        else:
+            v[:] = 0.0
+        vs.append(v)
+    t = np.triu(a[:cols, :cols])
+    q = np.zeros((rows, cols), dtype=np.float64)
+    q[:cols, :cols] = np.eye(cols)
+    for j in range(cols - 1, -1, -1):                    # q = H_0 H_1 ... H_{c-1} [I; 0]
+        v = vs[j]
+        q[j:, :] -= 2.0 * np.outer(v, v @ q[j:, :])
+    sign = np.where(np.diag(t) < 0.0, -1.0, 1.0)
+    return q * sign[None, :], t * sign[:, None]
+
+
+def col_norm(r: np.ndarray) -> np.ndarray:
+    """ColNorm of the Dion variant: every column rescaled to unit Euclidean length.
+    A zero column is left as zeros."""
+    r = np.asarray(r, dtype=np.float64)
+    lengths = np.sqrt(np.sum(r * r, axis=0))
+    safe = np.where(lengths > 0.0, lengths, 1.0)
+    return r / safe[None, :]
+
+
+def ef_coefficients(mu: float, ef: str) -> Tuple[float, float]:
+    """(a, b) of ``M_new = a B - b P R^T``: "dion" -> (1, 1 - mu); "paper" -> (mu, mu)
+    (Alg. 1 line 7 with beta = mu)."""
+    if ef == "dion":
+        return 1.0, 1.0 - float(mu)
+    if ef == "paper":
+        return float(mu), float(mu)
+    raise ValueError("ef must be 'dion' or 'paper'")
+
+
+# ---------------------------------------------------------------- the step
+
+class OrthDionOracle:
+    """One matrix, stepped in float64.  Each sub-step is its own method so that a
+    test can plant a mistake in exactly one of them and check that the pins notice."""
+
+    def __init__(self, mu: float = 0.95, lr: float = 0.01, variant: str = "qr",
+                 ef: str = "dion", x_bf16: bool = False):
+        if variant not in ("qr", "colnorm"):
+            raise ValueError("variant must be 'qr' or 'colnorm'")
+        self.mu, self.lr, self.variant, self.ef, self.x_bf16 = float(mu), float(lr), variant, ef, bool(x_bf16)
+        ef_coefficients(mu, ef)
+
+    # Alg. 1 line 1
+    def buffer(self, m_prev: np.ndarray, g: np.ndarray) -> np.ndarray:
+        return m_prev + g
+
+    # Alg. 1 line 2 (product)
+    def project(self, b: np.ndarray, q_prev: np.ndarray) -> np.ndarray:
+        return b @ q_prev
+
+    # Alg. 1 lines 2 and 4 (orth)
+    def orth(self, a: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+        return thin_qr_positive(a)
+
+    # Alg. 1 line 3
+    def back_project(self, b: np.ndarray, p: np.ndarray) -> np.ndarray:
+        return b.T @ p
+
+    # Alg. 1 line 4
+    def right_factor(self, r: np.ndarray) -> Tuple[np.ndarray, Optional[np.ndarray]]:
+        if self.variant == "qr":
+            return self.orth(r)
+        return col_norm(r), None
+
+    # Alg. 1 lines 5-6
+    def update(self, x: np.ndarray, p: np.ndarray, q: np.ndarray) -> np.ndarray:
+        return x - self.lr * (p @ q.T)
+
+    # Alg. 1 line 7 / default form
+    def error_feedback(self, b: np.ndarray, p: np.ndarray, r: np.ndarray) -> np.ndarray:
+        a_coef, b_coef = ef_coefficients(self.mu, self.ef)
+        return a_coef * b - b_coef * (p @ r.T)
+
+    def step(self, x, g, m_prev, q_prev) -> Dict[str, np.ndarray]:
+        """Inputs: X and G as float arrays or uint16 bf16 bit patterns; M, Q float.
+        Returns every intermediate; ``X`` is the fp64 result, ``X_bits`` its bf16
+        rounding when the parameter is stored in bf16."""
+        x = bf16_bits_to_f64(x) if np.asarray(x).dtype == np.uint16 else np.asarray(x, dtype=np.float64)
+        g = bf16_bits_to_f64(g) if np.asarray(g).dtype == np.uint16 else np.asarray(g, dtype=np.float64)
+        m_prev = np.asarray(m_prev, dtype=np.float64)
+        q_prev = np.asarray(q_prev, dtype=np.float64)
+        b = self.buffer(m_prev, g)
+        p_raw = self.project(b, q_prev)
+        p, t_p = self.orth(p_raw)
+        r = self.back_project(b, p)
+        q, t_q = self.right_factor(r)
+        x_new = self.update(x, p, q)
+        m_new = self.error_feedback(b, p, r)
+        out = {"B": b, "P_raw": p_raw, "P": p, "T_P": t_p, "R": r, "Q": q, "T_Q": t_q,
+               "X": x_new, "M": m_new, "D": p @ q.T}
+        if self.x_bf16:
+            out["X_bits"] = f64_to_bf16_bits(x_new)
+        return out
+
+    def run(self, x, grads, m0, q0):
+        """Free-running trajectory: ``grads`` is an iterable of gradients.  With bf16
+        parameters the stored (rounded) X is what the next step reads; M and Q stay in
+        float64.  Returns the list of per-step outputs."""
+        outs = []
+        x_cur, m_cur, q_cur = x, m0, q0
+        for g in grads:
+            o = self.step(x_cur, g, m_cur, q_cur)
+            outs.append(o)
+            x_cur = o["X_bits"] if self.x_bf16 else o["X"]
+            m_cur, q_cur = o["M"], o["Q"]
+        return outs
