@@ -1,0 +1,140 @@
+/*
+ * orthdion.h - C ABI of the MI355X-native Orth-Dion optimizer step.
+ *
+ * One call of orthdion_step performs, for every matrix of the set, one step of the
+ * paper's Alg. 1 ("Orth-Dion / Stripped Dion (one step)"; the two variants are also
+ * listed in App. B.1).  In this interface's letters (paper's letters in brackets):
+ *
+ *   B      = M + G                   [M_t = G_t + R_t]            Alg. 1 line 1
+ *   P      = orth(B Q)               [U_t = orth(M_t V_{t-1})]    Alg. 1 line 2
+ *   R      = B^T P                   [W_t = M_t^T U_t]            Alg. 1 line 3
+ *   Q      = orth(R) | ColNorm(R)    [V_t]   Orth-Dion | Dion     Alg. 1 line 4, Sec. 2 table
+ *   X      = X - lr P Q^T            [X_{t+1} = X_t - eta D_t]    Alg. 1 lines 5-6
+ *   M      = a B - b P R^T           [R_{t+1}]                    Alg. 1 line 7 (see orthdion_ef)
+ *   Q is kept for the next step      [warm start]                 Alg. 1 line 8
+ *
+ * orth(A) is the Q factor of the thin QR factorisation of A whose triangular factor has a
+ * positive diagonal.  ColNorm rescales every column to unit Euclidean length.
+ *
+ * Memory: every matrix is row-major.  X, G, M are m x n with leading dimensions ldx, ldg,
+ * ldm (in elements); Q is n x r, densely packed (leading dimension r).  X and G are fp32 or
+ * bf16 as configured; M and Q are always fp32.  All buffers named "device" are device
+ * (HBM) pointers owned by the caller; pointer *arrays* are host arrays.  The library never
+ * allocates or frees device memory and never synchronises the device or a stream, except
+ * orthdion_get_info, which waits for the stream it is given.
+ *
+ * Errors: every function returns ORTHDION_OK (0) or a negative orthdion_status; nothing
+ * throws or aborts.  Numerical breakdown found on the device (a rank-deficient or
+ * non-finite factor, outside the method's domain: Lemma 4.3 assumes full rank) does not
+ * fail the call; it is reported per matrix by orthdion_get_info and leaves that matrix's
+ * outputs unspecified.
+ */
+#ifndef ORTHDION_H
+#define ORTHDION_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct orthdion_ctx* orthdion_handle;   /* opaque; host memory only */
+
+typedef enum {
+  ORTHDION_OK = 0,
+  ORTHDION_E_INVALID_ARG = -1,        /* enum out of range, nmat < 1, non-finite mu / lr ...   */
+  ORTHDION_E_NULL_PTR = -2,
+  ORTHDION_E_BAD_SHAPE = -3,          /* see orthdion_matdesc                                   */
+  ORTHDION_E_WORKSPACE_TOO_SMALL = -4,
+  ORTHDION_E_MISALIGNED = -5,         /* a device pointer is not 16-byte aligned                */
+  ORTHDION_E_HIP = -6,                /* a HIP call failed; hipGetLastError has the cause       */
+  ORTHDION_E_NO_STEP = -7             /* orthdion_get_info before any orthdion_step             */
+} orthdion_status;
+
+typedef enum { ORTHDION_F32 = 0, ORTHDION_BF16 = 1 } orthdion_dtype;
+
+/* Alg. 1 line 4: QR orthogonalisation (Orth-Dion, the paper's method) or Dion's column
+ * normalisation. */
+typedef enum { ORTHDION_QR = 0, ORTHDION_COLNORM = 1 } orthdion_variant;
+
+/* Error-feedback form, both M = a B - b P R^T:
+ *   ORTHDION_EF_DION   a = 1,  b = 1 - mu   (momentum form; the default)
+ *   ORTHDION_EF_PAPER  a = mu, b = mu       (Alg. 1 line 7 with beta = mu)
+ * They coincide at mu = 0 / beta = 1. */
+typedef enum { ORTHDION_EF_DION = 0, ORTHDION_EF_PAPER = 1 } orthdion_ef;
+
+/* Arithmetic of the large contractions (B Q, B^T P, P R^T, P Q^T).  Accumulation is always
+ * fp32; the orthogonalisations always use split-bf16 operands (>= 16 significant bits).
+ *   ORTHDION_PREC_AUTO   FAST when X and G are both bf16, otherwise EXACT
+ *   ORTHDION_PREC_FAST   fp16 matrix-core operands under a power-of-two scale (11 bits)
+ *   ORTHDION_PREC_EXACT  three-way split bf16 operands, six products (24 bits) */
+typedef enum { ORTHDION_PREC_AUTO = 0, ORTHDION_PREC_FAST = 1, ORTHDION_PREC_EXACT = 2 } orthdion_precision;
+
+/* One parameter matrix.  Requirements (else ORTHDION_E_BAD_SHAPE):
+ *   m, n, r multiples of 8 (the paper's adaptive-rank policy, App. B.2, rounds ranks to
+ *   multiples of 8);  8 <= r <= min(m, n);  ldx, ldg, ldm >= n and multiples of 8;
+ *   m, n < 2^24. */
+typedef struct {
+  int64_t m, n;
+  int32_t r;
+  int64_t ldx, ldg, ldm;
+} orthdion_matdesc;
+
+typedef struct {
+  orthdion_dtype x_dtype, g_dtype;
+  orthdion_variant variant;
+  orthdion_ef ef;
+  orthdion_precision precision;
+  float mu;     /* momentum / error-feedback coefficient, 0 <= mu <= 1                  */
+  float lr;     /* step size eta; any scale factor or schedule is folded in by the caller */
+} orthdion_config;
+
+/* Builds a handle for a fixed set of nmat matrices (host-side planning only; the handle
+ * holds shapes and hyper-parameters, no numerical state: the optimizer state is the
+ * caller's X, M, Q buffers).  `mats` and `cfg` are copied. */
+int orthdion_create(orthdion_handle* out, const orthdion_matdesc* mats, int32_t nmat,
+                    const orthdion_config* cfg);
+
+/* Bytes of device scratch orthdion_step needs; the caller allocates it (256-byte aligned).
+ * Its contents are meaningless between steps except for the debug layout below. */
+size_t orthdion_workspace_bytes(orthdion_handle h);
+
+int orthdion_set_lr(orthdion_handle h, float lr);
+int orthdion_set_mu(orthdion_handle h, float mu);
+int orthdion_set_variant(orthdion_handle h, orthdion_variant v);
+
+/* One optimizer step over the whole matrix set, enqueued on `stream` (a hipStream_t passed
+ * as void*, 0 = the null stream); returns without waiting.
+ *   X  host array of nmat device pointers, x_dtype, updated in place
+ *   G  host array of nmat device pointers, g_dtype, read only
+ *   M  host array of nmat device pointers, fp32, updated in place
+ *   Q  host array of nmat device pointers, fp32 n x r; on entry the previous right factor
+ *      (any full-column-rank n x r matrix for the first step), on exit the new one
+ * Buffers must not overlap each other or the workspace.  Steps of one handle must be
+ * enqueued on one stream at a time (they share the workspace). */
+int orthdion_step(orthdion_handle h, void* const* X, const void* const* G, float* const* M,
+                  float* const* Q, void* workspace, size_t workspace_bytes, void* stream);
+
+/* Waits for `stream`, then copies the per-matrix breakdown words of the last step to
+ * info_host[nmat]: 0 = fine; k > 0 = the left factor B Q lost rank (or went non-finite) at
+ * column k; k < 0 = the same for the right factor (QR) or a zero column (ColNorm) at
+ * column -k. */
+int orthdion_get_info(orthdion_handle h, int32_t* info_host, void* stream);
+
+/* Debug / test hook: byte offsets inside the workspace of what the last step left for
+ * matrix `index`: P (m x r fp32), R (n x r fp32), and the two triangular factors of each
+ * CholeskyQR2 orthogonalisation (r x r fp32 each; orth(.)'s triangular factor is
+ * t2 * t1).  Any output pointer may be NULL. */
+int orthdion_workspace_layout(orthdion_handle h, int32_t index, size_t* off_p, size_t* off_r,
+                              size_t* off_tp1, size_t* off_tp2, size_t* off_tq1, size_t* off_tq2);
+
+const char* orthdion_strerror(int status);
+
+int orthdion_destroy(orthdion_handle h);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* ORTHDION_H */

@@ -1,0 +1,337 @@
+// Host side of the Orth-Dion C ABI: argument checks, shape classes, workspace planning and
+// the kernel sequence of one step.  No device memory is allocated here; everything lives
+// in the caller's workspace.
+#include "../../include/orthdion.h"
+
+#include <cmath>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "od_kernels.h"
+
+namespace {
+
+using od::ClassDims;
+using od::MatPtrs;
+using od::WsArr;
+
+constexpr size_t kAlign = 256;
+
+size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
+
+// A batch: up to kMaxBatchHost matrices of identical shape and leading dimensions.
+struct Batch {
+  ClassDims d;
+  std::vector<int> members;          // indices into the caller's arrays
+  // per-matrix float arrays (offset of matrix 0 in bytes, stride in elements)
+  size_t off_pa, off_pb, off_ra, off_rb, off_part, off_gram, off_tp1, off_tp2, off_tq1, off_tq2, off_w,
+      off_tmp, off_colsq;
+  int64_t st_p, st_r, st_part, st_rr, st_colsq;
+  int splits_proj, splits_back, splits_gram_p, splits_gram_q, slabs;
+  int slot_base;                     // first row of this batch in the scal / info tables
+};
+
+int pick_splits(int64_t tiles, int nb, int64_t k, int kt_min) {
+  int64_t want = (512 + tiles * nb - 1) / (tiles * nb);
+  int64_t cap = k / kt_min;
+  if (cap < 1) cap = 1;
+  if (want > cap) want = cap;
+  if (want > 32) want = 32;
+  if (want < 1) want = 1;
+  return (int)want;
+}
+
+}  // namespace
+
+struct orthdion_ctx {
+  std::vector<orthdion_matdesc> mats;
+  orthdion_config cfg;
+  std::vector<Batch> batches;
+  std::vector<int> batch_of, slot_of;     // per matrix
+  size_t off_scal, off_info, ws_bytes;
+  void* last_ws;
+};
+
+static od::Prec resolve_prec(const orthdion_config& c) {
+  if (c.precision == ORTHDION_PREC_FAST) return od::PREC_F16;
+  if (c.precision == ORTHDION_PREC_EXACT) return od::PREC_BF3;
+  return (c.x_dtype == ORTHDION_BF16 && c.g_dtype == ORTHDION_BF16) ? od::PREC_F16 : od::PREC_BF3;
+}
+
+static int check_config(const orthdion_config* c) {
+  if (c->x_dtype != ORTHDION_F32 && c->x_dtype != ORTHDION_BF16) return ORTHDION_E_INVALID_ARG;
+  if (c->g_dtype != ORTHDION_F32 && c->g_dtype != ORTHDION_BF16) return ORTHDION_E_INVALID_ARG;
+  if (c->variant != ORTHDION_QR && c->variant != ORTHDION_COLNORM) return ORTHDION_E_INVALID_ARG;
+  if (c->ef != ORTHDION_EF_DION && c->ef != ORTHDION_EF_PAPER) return ORTHDION_E_INVALID_ARG;
+  if (c->precision != ORTHDION_PREC_AUTO && c->precision != ORTHDION_PREC_FAST && c->precision != ORTHDION_PREC_EXACT)
+    return ORTHDION_E_INVALID_ARG;
+  if (!std::isfinite(c->mu) || c->mu < 0.f || c->mu > 1.f) return ORTHDION_E_INVALID_ARG;
+  if (!std::isfinite(c->lr)) return ORTHDION_E_INVALID_ARG;
+  return ORTHDION_OK;
+}
+
+static int check_shape(const orthdion_matdesc& m) {
+  if (m.m < 8 || m.n < 8 || m.r < 8) return ORTHDION_E_BAD_SHAPE;
+  if (m.m % 8 || m.n % 8 || m.r % 8) return ORTHDION_E_BAD_SHAPE;
+  if (m.m >= (1 << 24) || m.n >= (1 << 24)) return ORTHDION_E_BAD_SHAPE;
+  if (m.r > m.m || m.r > m.n) return ORTHDION_E_BAD_SHAPE;
+  if (m.ldx < m.n || m.ldg < m.n || m.ldm < m.n) return ORTHDION_E_BAD_SHAPE;
+  if (m.ldx % 8 || m.ldg % 8 || m.ldm % 8) return ORTHDION_E_BAD_SHAPE;
+  return ORTHDION_OK;
+}
+
+extern "C" int orthdion_create(orthdion_handle* out, const orthdion_matdesc* mats, int32_t nmat,
+                               const orthdion_config* cfg) {
+  if (!out) return ORTHDION_E_NULL_PTR;
+  *out = nullptr;
+  if (!mats || !cfg) return ORTHDION_E_NULL_PTR;
+  if (nmat < 1 || nmat > (1 << 20)) return ORTHDION_E_INVALID_ARG;
+  int rc = check_config(cfg);
+  if (rc != ORTHDION_OK) return rc;
+  for (int i = 0; i < nmat; ++i)
+    if ((rc = check_shape(mats[i])) != ORTHDION_OK) return rc;
+
+  orthdion_ctx* h = new (std::nothrow) orthdion_ctx();
+  if (!h) return ORTHDION_E_INVALID_ARG;
+  h->mats.assign(mats, mats + nmat);
+  h->cfg = *cfg;
+  h->last_ws = nullptr;
+  h->batch_of.assign(nmat, -1);
+  h->slot_of.assign(nmat, -1);
+
+  // shape classes, in order of first appearance, cut into batches
+  for (int i = 0; i < nmat; ++i) {
+    const orthdion_matdesc& a = mats[i];
+    int found = -1;
+    for (size_t b = 0; b < h->batches.size(); ++b) {
+      const ClassDims& d = h->batches[b].d;
+      if (d.m == a.m && d.n == a.n && d.r == a.r && d.ldx == a.ldx && d.ldg == a.ldg && d.ldm == a.ldm &&
+          (int)h->batches[b].members.size() < od::kMaxBatchHost)
+        found = (int)b;
+    }
+    if (found < 0) {
+      Batch nb = {};
+      nb.d.m = (int)a.m; nb.d.n = (int)a.n; nb.d.r = a.r;
+      nb.d.ldx = a.ldx; nb.d.ldg = a.ldg; nb.d.ldm = a.ldm;
+      nb.d.x_bf16 = cfg->x_dtype == ORTHDION_BF16;
+      nb.d.g_bf16 = cfg->g_dtype == ORTHDION_BF16;
+      h->batches.push_back(nb);
+      found = (int)h->batches.size() - 1;
+    }
+    h->batch_of[i] = found;
+    h->slot_of[i] = (int)h->batches[found].members.size();
+    h->batches[found].members.push_back(i);
+  }
+
+  // workspace plan
+  size_t off = 0;
+  h->off_scal = off; off = align_up(off + (size_t)nmat * od::kScalPerMat * sizeof(float));
+  h->off_info = off; off = align_up(off + (size_t)nmat * od::kInfoPerMat * sizeof(int));
+  int slot_base = 0;
+  for (Batch& b : h->batches) {
+    ClassDims& d = b.d;
+    d.nb = (int)b.members.size();
+    b.slot_base = slot_base;
+    slot_base += d.nb;
+    const int64_t m = d.m, n = d.n, r = d.r;
+    const int nt = r <= 64 ? 64 : (r <= 128 ? 128 : 256);
+    const int64_t tiles_r = (r + nt - 1) / nt;
+    b.splits_proj = pick_splits(((m + 127) / 128) * tiles_r, d.nb, n, 128);
+    b.splits_back = pick_splits(((n + 127) / 128) * tiles_r, d.nb, m, 128);
+    const int64_t gt = ((r + 127) / 128) * ((r + 127) / 128);
+    b.splits_gram_p = pick_splits(gt, d.nb, m, 128);
+    b.splits_gram_q = pick_splits(gt, d.nb, n, 128);
+    b.slabs = (int)((n + 511) / 512);
+    if (b.slabs > 64) b.slabs = 64;
+    int64_t part = (int64_t)b.splits_proj * m * r;
+    if ((int64_t)b.splits_back * n * r > part) part = (int64_t)b.splits_back * n * r;
+    if ((int64_t)b.splits_gram_p * r * r > part) part = (int64_t)b.splits_gram_p * r * r;
+    if ((int64_t)b.splits_gram_q * r * r > part) part = (int64_t)b.splits_gram_q * r * r;
+    if ((int64_t)b.slabs * r > part) part = (int64_t)b.slabs * r;
+    // strides rounded so that every matrix slice stays 256-byte aligned
+    auto rnd = [](int64_t e) { return (e + 63) / 64 * 64; };
+    b.st_p = rnd(m * r); b.st_r = rnd(n * r); b.st_part = rnd(part); b.st_rr = rnd(r * r); b.st_colsq = rnd(r);
+    auto take = [&](int64_t stride) { size_t o = off; off = align_up(off + (size_t)stride * d.nb * sizeof(float)); return o; };
+    b.off_pa = take(b.st_p); b.off_pb = take(b.st_p);
+    b.off_ra = take(b.st_r); b.off_rb = take(b.st_r);
+    b.off_part = take(b.st_part);
+    b.off_gram = take(b.st_rr);
+    b.off_tp1 = take(b.st_rr); b.off_tp2 = take(b.st_rr); b.off_tq1 = take(b.st_rr); b.off_tq2 = take(b.st_rr);
+    b.off_w = take(b.st_rr); b.off_tmp = take(b.st_rr);
+    b.off_colsq = take(b.st_colsq);
+  }
+  h->ws_bytes = off;
+  *out = h;
+  return ORTHDION_OK;
+}
+
+extern "C" size_t orthdion_workspace_bytes(orthdion_handle h) { return h ? h->ws_bytes : 0; }
+
+extern "C" int orthdion_set_lr(orthdion_handle h, float lr) {
+  if (!h) return ORTHDION_E_NULL_PTR;
+  if (!std::isfinite(lr)) return ORTHDION_E_INVALID_ARG;
+  h->cfg.lr = lr;
+  return ORTHDION_OK;
+}
+
+extern "C" int orthdion_set_mu(orthdion_handle h, float mu) {
+  if (!h) return ORTHDION_E_NULL_PTR;
+  if (!std::isfinite(mu) || mu < 0.f || mu > 1.f) return ORTHDION_E_INVALID_ARG;
+  h->cfg.mu = mu;
+  return ORTHDION_OK;
+}
+
+extern "C" int orthdion_set_variant(orthdion_handle h, orthdion_variant v) {
+  if (!h) return ORTHDION_E_NULL_PTR;
+  if (v != ORTHDION_QR && v != ORTHDION_COLNORM) return ORTHDION_E_INVALID_ARG;
+  h->cfg.variant = v;
+  return ORTHDION_OK;
+}
+
+#define OD_TRY(expr)                                  \
+  do {                                                \
+    if ((expr) != hipSuccess) return ORTHDION_E_HIP;  \
+  } while (0)
+
+// CholeskyQR2 of `a0` (rows x r): pass 1 a0 -> a1, pass 2 a1 -> (a0 | callers' Q).
+static int cholqr2(const Batch& b, char* ws, int rows, size_t off_a0, size_t off_a1, int64_t st_a, int splits,
+                   size_t off_t1, size_t off_t2, int info_slot, const MatPtrs* q_out, bool want_r_scale, float* scal,
+                   int* info, int exact, hipStream_t st) {
+  const int nb = b.d.nb, r = b.d.r;
+  WsArr a0{reinterpret_cast<float*>(ws + off_a0), st_a}, a1{reinterpret_cast<float*>(ws + off_a1), st_a};
+  WsArr part{reinterpret_cast<float*>(ws + b.off_part), b.st_part};
+  WsArr gram{reinterpret_cast<float*>(ws + b.off_gram), b.st_rr};
+  WsArr w{reinterpret_cast<float*>(ws + b.off_w), b.st_rr}, tmp{reinterpret_cast<float*>(ws + b.off_tmp), b.st_rr};
+  WsArr t1{reinterpret_cast<float*>(ws + off_t1), b.st_rr}, t2{reinterpret_cast<float*>(ws + off_t2), b.st_rr};
+  OD_TRY(od::launch_gram(nb, rows, r, a0, part, splits, exact, st));
+  OD_TRY(od::launch_reduce(nb, part, splits, (int64_t)r * r, gram, st));
+  if (want_r_scale) OD_TRY(od::launch_scale_from_trace(nb, rows, r, gram, scal, st));
+  OD_TRY(od::launch_cholinv(nb, r, gram, t1, w, tmp, info, info_slot, exact, st));
+  OD_TRY(od::launch_apply(nb, rows, r, a0, w, a1, nullptr, exact, st));
+  OD_TRY(od::launch_gram(nb, rows, r, a1, part, splits, exact, st));
+  OD_TRY(od::launch_reduce(nb, part, splits, (int64_t)r * r, gram, st));
+  OD_TRY(od::launch_cholinv(nb, r, gram, t2, w, tmp, info, info_slot, exact, st));
+  OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, exact, st));
+  return ORTHDION_OK;
+}
+
+extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* const* G, float* const* M,
+                             float* const* Q, void* workspace, size_t workspace_bytes, void* stream) {
+  if (!h || !X || !G || !M || !Q || !workspace) return ORTHDION_E_NULL_PTR;
+  if (workspace_bytes < h->ws_bytes) return ORTHDION_E_WORKSPACE_TOO_SMALL;
+  if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return ORTHDION_E_MISALIGNED;
+  const int nmat = (int)h->mats.size();
+  for (int i = 0; i < nmat; ++i) {
+    if (!X[i] || !G[i] || !M[i] || !Q[i]) return ORTHDION_E_NULL_PTR;
+    if (reinterpret_cast<uintptr_t>(X[i]) % 16 || reinterpret_cast<uintptr_t>(G[i]) % 16 ||
+        reinterpret_cast<uintptr_t>(M[i]) % 16 || reinterpret_cast<uintptr_t>(Q[i]) % 16)
+      return ORTHDION_E_MISALIGNED;
+  }
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  char* ws = reinterpret_cast<char*>(workspace);
+  const od::Prec prec = resolve_prec(h->cfg);
+  const int exact = prec == od::PREC_BF3 ? 1 : 0;
+  float a_coef, b_coef;
+  if (h->cfg.ef == ORTHDION_EF_DION) { a_coef = 1.f; b_coef = 1.f - h->cfg.mu; }
+  else { a_coef = h->cfg.mu; b_coef = h->cfg.mu; }
+
+  int* info_all = reinterpret_cast<int*>(ws + h->off_info);
+  float* scal_all = reinterpret_cast<float*>(ws + h->off_scal);
+  OD_TRY(od::launch_fill_int(info_all, (int64_t)nmat * od::kInfoPerMat, 0, st));
+  h->last_ws = workspace;
+
+  for (const Batch& b : h->batches) {
+    const ClassDims& d = b.d;
+    MatPtrs ptrs;
+    std::memset(&ptrs, 0, sizeof(ptrs));
+    for (int s = 0; s < d.nb; ++s) {
+      int i = b.members[s];
+      ptrs.X[s] = X[i]; ptrs.G[s] = G[i]; ptrs.M[s] = M[i]; ptrs.Q[s] = Q[i];
+    }
+    float* scal = scal_all + (size_t)b.slot_base * od::kScalPerMat;
+    int* info = info_all + (size_t)b.slot_base * od::kInfoPerMat;
+    WsArr pa{reinterpret_cast<float*>(ws + b.off_pa), b.st_p};
+    WsArr ra{reinterpret_cast<float*>(ws + b.off_ra), b.st_r};
+    WsArr part{reinterpret_cast<float*>(ws + b.off_part), b.st_part};
+    WsArr colsq{reinterpret_cast<float*>(ws + b.off_colsq), b.st_colsq};
+
+    // Alg. 1 lines 1-2: P_raw = (M + G) Q, then P = orth(P_raw)
+    if (prec == od::PREC_F16) OD_TRY(od::launch_stats(d, ptrs, scal, st));
+    OD_TRY(od::launch_proj(d, ptrs, prec, scal, part, b.splits_proj, st));
+    OD_TRY(od::launch_reduce(d.nb, part, b.splits_proj, (int64_t)d.m * d.r, pa, st));
+    int rc = cholqr2(b, ws, d.m, b.off_pa, b.off_pb, b.st_p, b.splits_gram_p, b.off_tp1, b.off_tp2, 0, nullptr,
+                     false, scal, info, exact, st);
+    if (rc != ORTHDION_OK) return rc;
+    // line 3: R = (M + G)^T P
+    OD_TRY(od::launch_back(d, ptrs, prec, scal, pa, part, b.splits_back, st));
+    OD_TRY(od::launch_reduce(d.nb, part, b.splits_back, (int64_t)d.n * d.r, ra, st));
+    // line 4: Q = orth(R) or ColNorm(R), written to the callers' Q (Q_prev is no longer needed)
+    if (h->cfg.variant == ORTHDION_QR) {
+      rc = cholqr2(b, ws, d.n, b.off_ra, b.off_rb, b.st_r, b.splits_gram_q, b.off_tq1, b.off_tq2, 1, &ptrs, true,
+                   scal, info, exact, st);
+      if (rc != ORTHDION_OK) return rc;
+    } else {
+      OD_TRY(od::launch_colnorm(d.nb, d.n, d.r, ra, ptrs, part, b.slabs, colsq, scal, info, st));
+    }
+    // lines 5-7: parameter update and error feedback in one pass
+    OD_TRY(od::launch_efx(d, ptrs, prec, scal, pa, ra, a_coef, b_coef, h->cfg.lr, st));
+  }
+  return ORTHDION_OK;
+}
+
+extern "C" int orthdion_get_info(orthdion_handle h, int32_t* info_host, void* stream) {
+  if (!h || !info_host) return ORTHDION_E_NULL_PTR;
+  if (!h->last_ws) return ORTHDION_E_NO_STEP;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const int nmat = (int)h->mats.size();
+  std::vector<int> raw((size_t)nmat * od::kInfoPerMat);
+  const char* ws = reinterpret_cast<const char*>(h->last_ws);
+  OD_TRY(hipMemcpyAsync(raw.data(), ws + h->off_info, raw.size() * sizeof(int), hipMemcpyDeviceToHost, st));
+  OD_TRY(hipStreamSynchronize(st));
+  for (int i = 0; i < nmat; ++i) {
+    const Batch& b = h->batches[h->batch_of[i]];
+    const int* w = raw.data() + (size_t)(b.slot_base + h->slot_of[i]) * od::kInfoPerMat;
+    int v = 0;
+    if (w[0] != 0) v = w[0];
+    else if (w[1] != 0) v = -w[1];
+    else if (w[2] != 0) v = -w[2];
+    info_host[i] = v;
+  }
+  return ORTHDION_OK;
+}
+
+extern "C" int orthdion_workspace_layout(orthdion_handle h, int32_t index, size_t* off_p, size_t* off_r,
+                                         size_t* off_tp1, size_t* off_tp2, size_t* off_tq1, size_t* off_tq2) {
+  if (!h) return ORTHDION_E_NULL_PTR;
+  if (index < 0 || index >= (int)h->mats.size()) return ORTHDION_E_INVALID_ARG;
+  const Batch& b = h->batches[h->batch_of[index]];
+  const size_t s = (size_t)h->slot_of[index];
+  if (off_p) *off_p = b.off_pa + s * b.st_p * sizeof(float);
+  if (off_r) *off_r = b.off_ra + s * b.st_r * sizeof(float);
+  if (off_tp1) *off_tp1 = b.off_tp1 + s * b.st_rr * sizeof(float);
+  if (off_tp2) *off_tp2 = b.off_tp2 + s * b.st_rr * sizeof(float);
+  if (off_tq1) *off_tq1 = b.off_tq1 + s * b.st_rr * sizeof(float);
+  if (off_tq2) *off_tq2 = b.off_tq2 + s * b.st_rr * sizeof(float);
+  return ORTHDION_OK;
+}
+
+extern "C" const char* orthdion_strerror(int status) {
+  switch (status) {
+    case ORTHDION_OK: return "ok";
+    case ORTHDION_E_INVALID_ARG: return "invalid argument";
+    case ORTHDION_E_NULL_PTR: return "null pointer";
+    case ORTHDION_E_BAD_SHAPE: return "unsupported shape: m, n, r, ld must be multiples of 8 with 8 <= r <= min(m, n) and ld >= n";
+    case ORTHDION_E_WORKSPACE_TOO_SMALL: return "workspace too small";
+    case ORTHDION_E_MISALIGNED: return "device pointer not sufficiently aligned";
+    case ORTHDION_E_HIP: return "HIP call failed";
+    case ORTHDION_E_NO_STEP: return "no step has been enqueued on this handle";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int orthdion_destroy(orthdion_handle h) {
+  if (!h) return ORTHDION_E_NULL_PTR;
+  delete h;
+  return ORTHDION_OK;
+}

@@ -1,0 +1,201 @@
+// LDS-tiled matrix-core contraction for gfx950: one workgroup computes an MT x NT tile of
+// C = A * B^T-like products over a K range, with both operands staged through LDS as
+// [row][k] tiles of 16-byte k-groups (8 half-precision values), double buffered.
+//
+// Operand tiles come from "loaders" that read global memory in whichever direction is
+// contiguous and always write the same LDS layout:
+//   LoadKC  memory is [operand row][k]  (k contiguous): one 8-element vector load per item.
+//   LoadKS  memory is [k][operand row]  (operand row contiguous): eight 4-element loads
+//           (8 consecutive k, 4 consecutive operand rows) transposed in registers.
+// The loads of step i+1 are issued before the matrix-core work of step i and converted
+// and written to the other LDS buffer after it, so one barrier per step suffices.
+#pragma once
+
+#include "od_common.h"
+
+namespace od {
+
+template <int MT_, int NT_, int KT_, int WM_, int WN_>
+struct Tile {
+  static constexpr int MT = MT_, NT = NT_, KT = KT_, WM = WM_, WN = WN_;
+  static constexpr int THREADS = kWave * WM * WN;
+  static constexpr int WTM = MT / WM, WTN = NT / WN;      // per-wave tile
+  static constexpr int FM = WTM / 32, FN = WTN / 32;      // 32x32 accumulator tiles per wave
+  static constexpr int KG = KT / 8;                       // 16-byte k-groups per row
+  static constexpr int PITCH = KT * 2 + 16;               // bytes per LDS row (padded)
+  static constexpr int PLANE_A = MT * PITCH, PLANE_B = NT * PITCH;
+  static_assert(MT % (32 * WM) == 0 && NT % (32 * WN) == 0 && KT % 16 == 0, "tile shape");
+  template <class Num>
+  static constexpr int lds_bytes() { return 2 * Num::PARTS * (PLANE_A + PLANE_B); }
+};
+
+template <class Src, int ROWS, int KT, int PITCH, int THREADS>
+struct LoadKC {
+  static constexpr int KG = KT / 8, ITEMS = ROWS * KG, PER = (ITEMS + THREADS - 1) / THREADS;
+  typename Src::Raw8 raw[PER];
+  OD_DEV void load(const Src& s, int row0, int k0, int tid) {
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      int item = tid + p * THREADS;
+      if (ITEMS % THREADS == 0 || item < ITEMS) raw[p] = s.load8(row0 + item / KG, k0 + (item % KG) * 8);
+    }
+  }
+  template <class Num>
+  OD_DEV void store(char* lds, int plane, float scale, int tid) const {
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      int item = tid + p * THREADS;
+      if (ITEMS % THREADS == 0 || item < ITEMS) {
+        float x[8];
+        Src::unpack8(raw[p], x);
+        u32x4 w[Num::PARTS];
+        Num::pack(x, scale, w);
+        char* dst = lds + (item / KG) * PITCH + (item % KG) * 16;
+#pragma unroll
+        for (int s = 0; s < Num::PARTS; ++s) *reinterpret_cast<u32x4*>(dst + s * plane) = w[s];
+      }
+    }
+  }
+};
+
+template <class Src, int ROWS, int KT, int PITCH, int THREADS>
+struct LoadKS {
+  static constexpr int RQ = ROWS / 4, KG = KT / 8, ITEMS = RQ * KG, PER = (ITEMS + THREADS - 1) / THREADS;
+  typename Src::Raw4 raw[PER][8];
+  OD_DEV void load(const Src& s, int row0, int k0, int tid) {
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      int item = tid + p * THREADS;
+      if (ITEMS % THREADS == 0 || item < ITEMS) {
+        int rq = item % RQ, kg = item / RQ;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) raw[p][kk] = s.load4(k0 + kg * 8 + kk, row0 + rq * 4);
+      }
+    }
+  }
+  template <class Num>
+  OD_DEV void store(char* lds, int plane, float scale, int tid) const {
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      int item = tid + p * THREADS;
+      if (ITEMS % THREADS == 0 || item < ITEMS) {
+        int rq = item % RQ, kg = item / RQ;
+        float x[8][4];
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) Src::unpack4(raw[p][kk], x[kk]);
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+          float col[8];
+#pragma unroll
+          for (int kk = 0; kk < 8; ++kk) col[kk] = x[kk][j];
+          u32x4 w[Num::PARTS];
+          Num::pack(col, scale, w);
+          char* dst = lds + (rq * 4 + j) * PITCH + kg * 16;
+#pragma unroll
+          for (int s = 0; s < Num::PARTS; ++s) *reinterpret_cast<u32x4*>(dst + s * plane) = w[s];
+        }
+      }
+    }
+  }
+};
+
+// Loader selection by direction tag.
+struct KC {};
+struct KS {};
+template <class Dir, class Src, int ROWS, int KT, int PITCH, int THREADS>
+struct LoaderFor;
+template <class Src, int ROWS, int KT, int PITCH, int THREADS>
+struct LoaderFor<KC, Src, ROWS, KT, PITCH, THREADS> { typedef LoadKC<Src, ROWS, KT, PITCH, THREADS> type; };
+template <class Src, int ROWS, int KT, int PITCH, int THREADS>
+struct LoaderFor<KS, Src, ROWS, KT, PITCH, THREADS> { typedef LoadKS<Src, ROWS, KT, PITCH, THREADS> type; };
+
+// One KT-deep step of matrix-core work from the LDS tiles.
+template <class T, class Num>
+OD_DEV void mma_step(const char* ldsA, const char* ldsB, f32x16 (&acc)[T::FM][T::FN], int wm, int wn, int lane) {
+#pragma unroll
+  for (int kk = 0; kk < T::KT / 16; ++kk) {
+    const int kg = 2 * kk + (lane >> 5);
+    u32x4 af[Num::PARTS][T::FM], bf[Num::PARTS][T::FN];
+#pragma unroll
+    for (int s = 0; s < Num::PARTS; ++s) {
+#pragma unroll
+      for (int fm = 0; fm < T::FM; ++fm)
+        af[s][fm] = *reinterpret_cast<const u32x4*>(ldsA + s * T::PLANE_A + (wm * T::WTM + fm * 32 + (lane & 31)) * T::PITCH + kg * 16);
+#pragma unroll
+      for (int fn = 0; fn < T::FN; ++fn)
+        bf[s][fn] = *reinterpret_cast<const u32x4*>(ldsB + s * T::PLANE_B + (wn * T::WTN + fn * 32 + (lane & 31)) * T::PITCH + kg * 16);
+    }
+#pragma unroll
+    for (int fm = 0; fm < T::FM; ++fm)
+#pragma unroll
+      for (int fn = 0; fn < T::FN; ++fn)
+#pragma unroll
+        for (int i = Num::PARTS - 1; i >= 0; --i)
+#pragma unroll
+          for (int j = Num::PARTS - 1 - i; j >= 0; --j)
+            acc[fm][fn] = mfma_32x32x16<Num::F16>(af[i][fm], bf[j][fn], acc[fm][fn]);
+  }
+}
+
+// The main loop: acc += sum over k in [kbeg, kend) of A(m0.., k) * B(n0.., k).
+// `lds` must hold T::lds_bytes<Num>() bytes.  Ends with all waves past their last LDS read.
+template <class T, class Num, class DirA, class SrcA, class DirB, class SrcB>
+OD_DEV void gemm_mainloop(const SrcA& a, const SrcB& b, int m0, int n0, int kbeg, int kend,
+                          float scaleA, float scaleB, char* lds, f32x16 (&acc)[T::FM][T::FN]) {
+  typedef typename LoaderFor<DirA, SrcA, T::MT, T::KT, T::PITCH, T::THREADS>::type LA;
+  typedef typename LoaderFor<DirB, SrcB, T::NT, T::KT, T::PITCH, T::THREADS>::type LB;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / T::WN, wn = wave % T::WN;
+  constexpr int BUF = Num::PARTS * (T::PLANE_A + T::PLANE_B);
+  constexpr int OFF_B = Num::PARTS * T::PLANE_A;
+  LA la;
+  LB lb;
+  if (kbeg >= kend) return;
+  la.load(a, m0, kbeg, tid);
+  lb.load(b, n0, kbeg, tid);
+  la.template store<Num>(lds, T::PLANE_A, scaleA, tid);
+  lb.template store<Num>(lds + OFF_B, T::PLANE_B, scaleB, tid);
+  __syncthreads();
+  int buf = 0;
+  for (int k = kbeg; k < kend; k += T::KT) {
+    const bool more = (k + T::KT) < kend;
+    if (more) {
+      la.load(a, m0, k + T::KT, tid);
+      lb.load(b, n0, k + T::KT, tid);
+    }
+    mma_step<T, Num>(lds + buf * BUF, lds + buf * BUF + OFF_B, acc, wm, wn, lane);
+    if (more) {
+      la.template store<Num>(lds + (buf ^ 1) * BUF, T::PLANE_A, scaleA, tid);
+      lb.template store<Num>(lds + (buf ^ 1) * BUF + OFF_B, T::PLANE_B, scaleB, tid);
+    }
+    __syncthreads();
+    buf ^= 1;
+  }
+}
+
+template <class T>
+OD_DEV void zero_acc(f32x16 (&acc)[T::FM][T::FN]) {
+#pragma unroll
+  for (int fm = 0; fm < T::FM; ++fm)
+#pragma unroll
+    for (int fn = 0; fn < T::FN; ++fn)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[fm][fn][v] = 0.f;
+}
+
+// Visit every accumulator element of this lane: f(row, col, value) in tile coordinates
+// offset by (m0, n0).
+template <class T, class F>
+OD_DEV void for_each_acc(const f32x16 (&acc)[T::FM][T::FN], int m0, int n0, F&& f) {
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / T::WN, wn = wave % T::WN;
+#pragma unroll
+  for (int fm = 0; fm < T::FM; ++fm)
+#pragma unroll
+    for (int fn = 0; fn < T::FN; ++fn)
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        f(m0 + wm * T::WTM + fm * 32 + acc_row(v, lane), n0 + wn * T::WTN + fn * 32 + acc_col(lane), acc[fm][fn][v]);
+}
+
+}  // namespace od

@@ -1,0 +1,82 @@
+// Host-callable launchers of the HIP kernels of the Orth-Dion step (defined in
+// od_kernels.hip).  Every launcher only enqueues work on `stream`; none synchronises
+// or allocates.  A launch covers the matrices of one shape class (same m, n, r),
+// `nb` of them, at most od::kMaxBatch.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace od {
+
+constexpr int kMaxBatchHost = 32;
+
+// Caller-owned buffers of the matrices of one shape class.
+struct MatPtrs {
+  void* X[kMaxBatchHost];
+  const void* G[kMaxBatchHost];
+  float* M[kMaxBatchHost];
+  float* Q[kMaxBatchHost];
+};
+
+enum Prec : int { PREC_F16 = 0, PREC_BF3 = 1 };   // operand format of the big contractions
+
+struct ClassDims {
+  int m, n, r, nb;
+  int64_t ldx, ldg, ldm;
+  int x_bf16, g_bf16;
+};
+
+// A workspace array with one slice per matrix of the class.
+struct WsArr {
+  float* base;
+  int64_t stride;      // elements between consecutive matrices
+};
+
+// scal layout per matrix (floats): [0] scale of B, [1] scale of R, [2..7] spare
+constexpr int kScalPerMat = 8;
+// info layout per matrix (ints): [0] left-factor breakdown column, [1] right-factor
+// breakdown column (1-based, 0 = none), [2] zero-column flag of ColNorm, [3] spare
+constexpr int kInfoPerMat = 4;
+
+hipError_t launch_stats(const ClassDims& d, const MatPtrs& ptrs, float* scal, hipStream_t st);
+
+// P_raw partials: part[split][m][r] = (M+G)[:, k-range] * Q[k-range, :]
+hipError_t launch_proj(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal,
+                       WsArr part, int splits, hipStream_t st);
+// R partials: part[split][n][r] = (M+G)[k-range, :]^T * P[k-range, :]
+hipError_t launch_back(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal,
+                       WsArr p, WsArr part, int splits, hipStream_t st);
+// out[i] = sum_s part[s * count + i], i < count, per matrix
+hipError_t launch_reduce(int nb, WsArr part, int splits, int64_t count, WsArr out, hipStream_t st);
+
+// Gram partials: part[split][r][r] = A[k-range, :]^T A[k-range, :], A is rows x r (ld r)
+hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits, int exact, hipStream_t st);
+// out = A * W, A rows x r, W r x r upper triangular (both ld r); the result goes to the
+// callers' Q buffers when q_ptrs is given, else to the workspace array `out`.
+hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs,
+                        int exact, hipStream_t st);
+
+// Cholesky factor and its inverse of an SPD r x r matrix (ld r): gram = T^T T, W = T^-1,
+// both upper triangular with zeros below the diagonal.  `gram` is destroyed; `tmp` is
+// r x r scratch.  A non-positive or non-finite pivot writes its 1-based column to
+// info[mat * kInfoPerMat + info_slot] (first failure wins) and the factorisation goes on
+// with that pivot replaced by 1.
+hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp, int* info,
+                          int info_slot, int exact, hipStream_t st);
+
+// scal[mat][1] = power-of-two scale for R from trace(gram) = ||R||_F^2 (rows n, cols r)
+hipError_t launch_scale_from_trace(int nb, int n, int r, WsArr gram, float* scal, hipStream_t st);
+
+// ColNorm: Q[:, c] = R[:, c] / ||R[:, c]||; also writes the scale of R.  `part` holds
+// slabs x r partial sums per matrix, `colsq` r reciprocal lengths per matrix.
+hipError_t launch_colnorm(int nb, int n, int r, WsArr rr, const MatPtrs& ptrs, WsArr part, int slabs, WsArr colsq,
+                          float* scal, int* info, hipStream_t st);
+
+// M_new = a (M+G) - b P R^T ;  X_new = X - lr P Q^T   (one pass over M, G, X)
+hipError_t launch_efx(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p,
+                      WsArr rr, float a_coef, float b_coef, float lr, hipStream_t st);
+
+hipError_t launch_fill_int(int* p, int64_t count, int value, hipStream_t st);
+
+}  // namespace od

@@ -1,0 +1,724 @@
+// HIP kernels of the Orth-Dion optimizer step for gfx950 (CDNA4) and their launchers.
+//
+// Notation follows the library interface: B = M + G (paper Alg. 1 line 1, never stored),
+// P_raw = B Q (line 2), P = orth(P_raw) (line 2), R = B^T P (line 3), Q = orth(R) or
+// ColNorm(R) (line 4), X -= lr P Q^T (lines 5-6), M = a B - b P R^T (line 7).
+#include "od_kernels.h"
+
+#include "od_gemm.h"
+
+namespace od {
+
+static_assert(kMaxBatchHost == kMaxBatch, "batch limit");
+
+// ------------------------------------------------------------------------------------
+// tile shapes
+// ------------------------------------------------------------------------------------
+typedef Tile<128, 256, 32, 2, 2> TileWide;     // r > 128: wave tile 64 x 128
+typedef Tile<128, 128, 32, 2, 2> TileSquare;   // wave tile 64 x 64
+typedef Tile<128, 64, 32, 4, 1> TileNarrow;    // r <= 64: wave tile 32 x 64
+
+constexpr float kUnitScale = 1024.f;           // scale of orthonormal / unit-column factors in fp16
+
+OD_DEV int split_begin(int K, int splits, int KT, int s, int* kend) {
+  int per = ((K + splits - 1) / splits + KT - 1) / KT * KT;
+  int kb = s * per;
+  int ke = kb + per;
+  *kend = ke < K ? ke : K;
+  return kb;
+}
+
+template <class GSrc>
+OD_DEV SrcSum<GSrc> make_b_source(const ClassDims& d, const MatPtrs& ptrs, int z) {
+  SrcSum<GSrc> s;
+  s.m = SrcF32{ptrs.M[z], d.m, d.n, d.ldm};
+  s.g = GSrc{reinterpret_cast<decltype(GSrc::p)>(ptrs.G[z]), d.m, d.n, d.ldg};
+  return s;
+}
+
+// ------------------------------------------------------------------------------------
+// sampled power-of-two scale of B for the fp16 operand format
+// ------------------------------------------------------------------------------------
+template <class GSrc>
+__global__ __launch_bounds__(256) void k_stats(ClassDims d, MatPtrs ptrs, float* scal) {
+  const int z = blockIdx.x, tid = threadIdx.x;
+  SrcSum<GSrc> b = make_b_source<GSrc>(d, ptrs, z);
+  const int nrows = d.m < 64 ? d.m : 64;
+  float acc = 0.f;
+  const int groups = d.n / 8;
+  for (int idx = tid; idx < nrows * groups; idx += 256) {
+    int s = idx / groups, c = (idx % groups) * 8;
+    int row = (int)(((int64_t)s * d.m) / nrows);
+    float x[8];
+    SrcSum<GSrc>::unpack8(b.load8(row, c), x);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) acc += x[i] * x[i];
+  }
+  __shared__ float red[256];
+  red[tid] = acc;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if (tid < w) red[tid] += red[tid + w];
+    __syncthreads();
+  }
+  if (tid == 0) {
+    float ms = red[0] / ((float)nrows * (float)d.n);
+    float scale = 1.f;
+    if (ms > 0.f && ms < 3.0e38f) scale = ldexpf(1.f, -ilogbf(sqrtf(ms)));
+    scal[z * kScalPerMat + 0] = scale;
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// P_raw = B Q  (split over n)                                       Alg. 1 line 2
+// ------------------------------------------------------------------------------------
+template <class T, class Num, class GSrc>
+__global__ __launch_bounds__(T::THREADS) void k_proj(ClassDims d, MatPtrs ptrs, const float* scal, WsArr part, int splits) {
+  extern __shared__ __align__(16) char lds[];
+  const int tiles_n = (d.r + T::NT - 1) / T::NT;
+  const int tn = blockIdx.x % tiles_n, tm = blockIdx.x / tiles_n;
+  const int split = blockIdx.y, z = blockIdx.z;
+  SrcSum<GSrc> a = make_b_source<GSrc>(d, ptrs, z);
+  SrcF32 b{ptrs.Q[z], d.n, d.r, d.r};
+  int kend;
+  const int kbeg = split_begin(d.n, splits, T::KT, split, &kend);
+  const float sa = Num::F16 ? scal[z * kScalPerMat + 0] : 1.f;
+  const float sb = Num::F16 ? kUnitScale : 1.f;
+  f32x16 acc[T::FM][T::FN];
+  zero_acc<T>(acc);
+  gemm_mainloop<T, Num, KC, SrcSum<GSrc>, KS, SrcF32>(a, b, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc);
+  const float inv = 1.f / (sa * sb);
+  float* out = part.base + (int64_t)z * part.stride + (int64_t)split * d.m * d.r;
+  for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
+    if (row < d.m && col < d.r) out[(int64_t)row * d.r + col] = v * inv;
+  });
+}
+
+// ------------------------------------------------------------------------------------
+// R = B^T P  (split over m)                                         Alg. 1 line 3
+// ------------------------------------------------------------------------------------
+template <class T, class Num, class GSrc>
+__global__ __launch_bounds__(T::THREADS) void k_back(ClassDims d, MatPtrs ptrs, const float* scal, WsArr p, WsArr part, int splits) {
+  extern __shared__ __align__(16) char lds[];
+  const int tiles_n = (d.r + T::NT - 1) / T::NT;
+  const int tn = blockIdx.x % tiles_n, tm = blockIdx.x / tiles_n;
+  const int split = blockIdx.y, z = blockIdx.z;
+  SrcSum<GSrc> a = make_b_source<GSrc>(d, ptrs, z);      // read as [k = row i][operand row = column j]
+  SrcF32 b{p.base + (int64_t)z * p.stride, d.m, d.r, d.r};
+  int kend;
+  const int kbeg = split_begin(d.m, splits, T::KT, split, &kend);
+  const float sa = Num::F16 ? scal[z * kScalPerMat + 0] : 1.f;
+  const float sb = Num::F16 ? kUnitScale : 1.f;
+  f32x16 acc[T::FM][T::FN];
+  zero_acc<T>(acc);
+  gemm_mainloop<T, Num, KS, SrcSum<GSrc>, KS, SrcF32>(a, b, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc);
+  const float inv = 1.f / (sa * sb);
+  float* out = part.base + (int64_t)z * part.stride + (int64_t)split * d.n * d.r;
+  for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
+    if (row < d.n && col < d.r) out[(int64_t)row * d.r + col] = v * inv;
+  });
+}
+
+// ------------------------------------------------------------------------------------
+// deterministic second stage of the split contractions
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_reduce(WsArr part, int splits, int64_t count, WsArr out) {
+  const int z = blockIdx.y;
+  const float* src = part.base + (int64_t)z * part.stride;
+  float* dst = out.base + (int64_t)z * out.stride;
+  const int64_t n4 = count / 4;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
+    f32x4 s = reinterpret_cast<const f32x4*>(src)[i];
+    for (int k = 1; k < splits; ++k) {
+      f32x4 v = reinterpret_cast<const f32x4*>(src + (int64_t)k * count)[i];
+      s += v;
+    }
+    reinterpret_cast<f32x4*>(dst)[i] = s;
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// Gram matrix A^T A (split over rows)                 CholeskyQR for orth(), Alg. 1 l. 2, 4
+// ------------------------------------------------------------------------------------
+template <class T, class Num>
+__global__ __launch_bounds__(T::THREADS) void k_gram(int rows, int r, WsArr a, WsArr part, int splits) {
+  extern __shared__ __align__(16) char lds[];
+  const int tiles = (r + T::NT - 1) / T::NT;
+  const int tn = blockIdx.x % tiles, tm = blockIdx.x / tiles;
+  const int split = blockIdx.y, z = blockIdx.z;
+  SrcF32 s{a.base + (int64_t)z * a.stride, rows, r, r};
+  int kend;
+  const int kbeg = split_begin(rows, splits, T::KT, split, &kend);
+  f32x16 acc[T::FM][T::FN];
+  zero_acc<T>(acc);
+  gemm_mainloop<T, Num, KS, SrcF32, KS, SrcF32>(s, s, tm * T::MT, tn * T::NT, kbeg, kend, 1.f, 1.f, lds, acc);
+  float* out = part.base + (int64_t)z * part.stride + (int64_t)split * r * r;
+  for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
+    if (row < r && col < r) out[(int64_t)row * r + col] = v;
+  });
+}
+
+// ------------------------------------------------------------------------------------
+// out = A W with W upper triangular (the triangular solve of CholeskyQR as a product
+// with the explicit inverse factor)
+// ------------------------------------------------------------------------------------
+template <class T, class Num>
+__global__ __launch_bounds__(T::THREADS) void k_apply(int rows, int r, WsArr a, WsArr w, WsArr out, MatPtrs ptrs, int to_q) {
+  extern __shared__ __align__(16) char lds[];
+  const int tiles_n = (r + T::NT - 1) / T::NT;
+  const int tn = blockIdx.x % tiles_n, tm = blockIdx.x / tiles_n;
+  const int z = blockIdx.z;
+  SrcF32 sa{a.base + (int64_t)z * a.stride, rows, r, r};
+  SrcF32 sw{w.base + (int64_t)z * w.stride, r, r, r};
+  int kend = (tn + 1) * T::NT;          // W[k][j] = 0 for k > j
+  if (kend > r) kend = r;
+  f32x16 acc[T::FM][T::FN];
+  zero_acc<T>(acc);
+  gemm_mainloop<T, Num, KC, SrcF32, KS, SrcF32>(sa, sw, tm * T::MT, tn * T::NT, 0, kend, 1.f, 1.f, lds, acc);
+  float* dst = to_q ? ptrs.Q[z] : out.base + (int64_t)z * out.stride;
+  for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
+    if (row < rows && col < r) dst[(int64_t)row * r + col] = v;
+  });
+}
+
+// ------------------------------------------------------------------------------------
+// small general product on r x r workspace matrices, used by the blocked Cholesky and
+// triangular inverse:  C[cr.., cc..] = alpha * A * B + beta * C over Mc x Nc x Kc with
+// block origins that advance affinely with the inner batch index q.
+// ------------------------------------------------------------------------------------
+struct SgemmArgs {
+  WsArr a, b, c;
+  int r;                 // all three are r x r, ld r
+  int a_r0, a_k0, b_k0, b_c0, c_r0, c_c0;
+  int q_step;            // every origin advances by q * q_step
+  int nq;
+  int Mc, Nc, Kc;
+  float alpha, beta;
+};
+
+template <class D> OD_DEV constexpr bool DirA_is_kc() { return false; }
+template <> OD_DEV constexpr bool DirA_is_kc<KC>() { return true; }
+
+OD_DEV SrcF32 sub_view(const float* base, int r, int row0, int col0, int rows, int cols) {
+  int R = r - row0, C = r - col0;
+  if (R > rows) R = rows;
+  if (C > cols) C = cols;
+  if (R < 0) R = 0;
+  if (C < 0) C = 0;
+  return SrcF32{base + (int64_t)row0 * r + col0, R, C, r};
+}
+
+template <class T, class Num, class DirA>
+__global__ __launch_bounds__(T::THREADS) void k_sgemm(SgemmArgs g) {
+  extern __shared__ __align__(16) char lds[];
+  const int tiles_n = (g.Nc + T::NT - 1) / T::NT;
+  const int tn = blockIdx.x % tiles_n, tm = blockIdx.x / tiles_n;
+  const int q = blockIdx.z % g.nq, z = blockIdx.z / g.nq;
+  const int o = q * g.q_step;
+  const float* ap = g.a.base + (int64_t)z * g.a.stride;
+  const float* bp = g.b.base + (int64_t)z * g.b.stride;
+  float* cp = g.c.base + (int64_t)z * g.c.stride;
+  SrcF32 sa = DirA_is_kc<DirA>() ? sub_view(ap, g.r, g.a_r0 + o, g.a_k0 + o, g.Mc, g.Kc)
+                                 : sub_view(ap, g.r, g.a_k0 + o, g.a_r0 + o, g.Kc, g.Mc);
+  SrcF32 sb = sub_view(bp, g.r, g.b_k0 + o, g.b_c0 + o, g.Kc, g.Nc);
+  f32x16 acc[T::FM][T::FN];
+  zero_acc<T>(acc);
+  gemm_mainloop<T, Num, DirA, SrcF32, KS, SrcF32>(sa, sb, tm * T::MT, tn * T::NT, 0, g.Kc, 1.f, 1.f, lds, acc);
+  const int cr = g.c_r0 + o, cc = g.c_c0 + o;
+  for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
+    if (row < g.Mc && col < g.Nc && cr + row < g.r && cc + col < g.r) {
+      float* dst = cp + (int64_t)(cr + row) * g.r + (cc + col);
+      float old = g.beta != 0.f ? *dst : 0.f;
+      *dst = g.alpha * v + g.beta * old;
+    }
+  });
+}
+
+
+// ------------------------------------------------------------------------------------
+// Cholesky factor and inverse of one diagonal block (at most 128 x 128) in LDS.
+//   gram block = T^T T (upper T), W = T^-1.  One workgroup per matrix.
+// ------------------------------------------------------------------------------------
+constexpr int kLeaf = 128;
+constexpr int kLeafLd = kLeaf + 1;
+constexpr int kLeafLds = (2 * kLeaf * kLeafLd + kLeaf) * 4;
+
+__global__ __launch_bounds__(256) void k_chol_leaf(WsArr gram, WsArr t, WsArr w, int r, int blk, int* info, int info_slot) {
+  extern __shared__ __align__(16) char lds[];
+  float* A = reinterpret_cast<float*>(lds);
+  float* Wl = A + kLeaf * kLeafLd;
+  float* dd = Wl + kLeaf * kLeafLd;
+  const int z = blockIdx.x, tid = threadIdx.x;
+  const int o = blk * kLeaf;
+  const int nb = (r - o) < kLeaf ? (r - o) : kLeaf;
+  const int64_t off = (int64_t)o * r + o;
+  const float* g = gram.base + (int64_t)z * gram.stride + off;
+  float* tg = t.base + (int64_t)z * t.stride + off;
+  float* wg = w.base + (int64_t)z * w.stride + off;
+
+  for (int idx = tid; idx < nb * nb; idx += 256) {
+    int i = idx / nb, j = idx % nb;
+    A[i * kLeafLd + j] = g[(int64_t)i * r + j];
+    Wl[i * kLeafLd + j] = 0.f;
+  }
+  __syncthreads();
+
+  // right-looking Cholesky on the upper triangle; row k is scaled at the end
+  const int ty = tid >> 4, tx = tid & 15;
+  for (int k = 0; k < nb; ++k) {
+    float piv = A[k * kLeafLd + k];
+    if (!(piv > 0.f) || piv > 3.0e38f) {
+      if (tid == 0) atomicCAS(&info[z * kInfoPerMat + info_slot], 0, o + k + 1);
+      piv = 1.f;
+    }
+    const float ip = 1.f / piv;
+    if (tid == 0) dd[k] = piv;
+    for (int i = k + 1 + ty; i < nb; i += 16) {
+      const float aki = A[k * kLeafLd + i] * ip;
+      for (int j = k + 1 + tx; j < nb; j += 16)
+        if (j >= i) A[i * kLeafLd + j] -= aki * A[k * kLeafLd + j];
+    }
+    __syncthreads();
+  }
+  for (int idx = tid; idx < nb * nb; idx += 256) {
+    int i = idx / nb, j = idx % nb;
+    float v = 0.f;
+    if (j > i) v = A[i * kLeafLd + j] * rsqrtf(dd[i]);
+    else if (j == i) v = sqrtf(dd[i]);
+    A[i * kLeafLd + j] = v;
+    tg[(int64_t)i * r + j] = v;
+  }
+  __syncthreads();
+
+  // inverse of the upper-triangular T: 32 x 32 diagonal blocks by back substitution
+  // (one thread per column), then block rows outward by products.
+  if (tid < nb) {
+    const int c = tid, b0 = (c / 32) * 32;
+    Wl[c * kLeafLd + c] = 1.f / A[c * kLeafLd + c];
+    for (int i = c - 1; i >= b0; --i) {
+      float s = 0.f;
+      for (int k = i + 1; k <= c; ++k) s += A[i * kLeafLd + k] * Wl[k * kLeafLd + c];
+      Wl[i * kLeafLd + c] = -s / A[i * kLeafLd + i];
+    }
+  }
+  __syncthreads();
+  const int nbl = (nb + 31) / 32;
+  for (int d = 1; d < nbl; ++d) {
+    // S(I, J) = sum_{K = I+1..J} T(I, K) W(K, J), J = I + d; kept in the (unused) lower part of A
+    for (int idx = tid; idx < (nbl - d) * 1024; idx += 256) {
+      int I = idx / 1024, e = idx % 1024, i = I * 32 + e / 32, j = (I + d) * 32 + e % 32;
+      float s = 0.f;
+      if (j < nb) {
+        int kmax = (I + d + 1) * 32;
+        if (kmax > nb) kmax = nb;
+        for (int k = (I + 1) * 32; k < kmax; ++k) s += A[i * kLeafLd + k] * Wl[k * kLeafLd + j];
+        A[j * kLeafLd + i] = s;
+      }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < (nbl - d) * 1024; idx += 256) {
+      int I = idx / 1024, e = idx % 1024, i = I * 32 + e / 32, j = (I + d) * 32 + e % 32;
+      if (j < nb) {
+        float s = 0.f;
+        for (int k = i; k < (I + 1) * 32; ++k) s += Wl[i * kLeafLd + k] * A[j * kLeafLd + k];
+        Wl[i * kLeafLd + j] = -s;
+      }
+    }
+    __syncthreads();
+  }
+  for (int idx = tid; idx < nb * nb; idx += 256) {
+    int i = idx / nb, j = idx % nb;
+    wg[(int64_t)i * r + j] = j >= i ? Wl[i * kLeafLd + j] : 0.f;
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// small helpers
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(256) void k_fill_f32(float* p, int64_t count, float v) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) p[i] = v;
+}
+__global__ __launch_bounds__(256) void k_fill_i32(int* p, int64_t count, int v) {
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) p[i] = v;
+}
+
+OD_DEV float pow2_scale_for_rms(float ms) {
+  if (ms > 0.f && ms < 3.0e38f) return ldexpf(1.f, -ilogbf(sqrtf(ms)));
+  return 1.f;
+}
+
+__global__ __launch_bounds__(256) void k_scale_from_trace(int n, int r, WsArr gram, float* scal) {
+  const int z = blockIdx.x, tid = threadIdx.x;
+  const float* g = gram.base + (int64_t)z * gram.stride;
+  float acc = 0.f;
+  for (int i = tid; i < r; i += 256) acc += g[(int64_t)i * r + i];
+  __shared__ float red[256];
+  red[tid] = acc;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if (tid < w) red[tid] += red[tid + w];
+    __syncthreads();
+  }
+  if (tid == 0) scal[z * kScalPerMat + 1] = pow2_scale_for_rms(red[0] / ((float)n * (float)r));
+}
+
+// ColNorm stage 1: partial column sums of squares over a slab of rows (deterministic)
+__global__ __launch_bounds__(256) void k_colsq_partial(int n, int r, WsArr rr, WsArr part, int slabs) {
+  const int z = blockIdx.z, slab = blockIdx.y;
+  const int c = blockIdx.x * 256 + threadIdx.x;
+  const int per = (n + slabs - 1) / slabs;
+  const int r0 = slab * per, r1 = (r0 + per) < n ? (r0 + per) : n;
+  if (c >= r) return;
+  const float* src = rr.base + (int64_t)z * rr.stride;
+  float acc = 0.f;
+  for (int i = r0; i < r1; ++i) {
+    float v = src[(int64_t)i * r + c];
+    acc += v * v;
+  }
+  part.base[(int64_t)z * part.stride + (int64_t)slab * r + c] = acc;
+}
+// stage 2: column lengths, the scale of R, and the zero-column flag
+__global__ __launch_bounds__(256) void k_colsq_final(int n, int r, WsArr part, int slabs, WsArr colsq, float* scal, int* info) {
+  const int z = blockIdx.x, tid = threadIdx.x;
+  float tot = 0.f;
+  for (int c = tid; c < r; c += 256) {
+    float s = 0.f;
+    for (int k = 0; k < slabs; ++k) s += part.base[(int64_t)z * part.stride + (int64_t)k * r + c];
+    tot += s;
+    float len = sqrtf(s);
+    float inv = 0.f;
+    if (len > 1e-30f && len < 3.0e38f) inv = 1.f / len;
+    else atomicCAS(&info[z * kInfoPerMat + 2], 0, c + 1);
+    colsq.base[(int64_t)z * colsq.stride + c] = inv;
+  }
+  __shared__ float red[256];
+  red[tid] = tot;
+  __syncthreads();
+  for (int w = 128; w > 0; w >>= 1) {
+    if (tid < w) red[tid] += red[tid + w];
+    __syncthreads();
+  }
+  if (tid == 0) scal[z * kScalPerMat + 1] = pow2_scale_for_rms(red[0] / ((float)n * (float)r));
+}
+// stage 3: Q = R * diag(1/len)
+__global__ __launch_bounds__(256) void k_colnorm_apply(int n, int r, WsArr rr, WsArr colsq, MatPtrs ptrs) {
+  const int z = blockIdx.y;
+  const float* src = rr.base + (int64_t)z * rr.stride;
+  const float* inv = colsq.base + (int64_t)z * colsq.stride;
+  float* q = ptrs.Q[z];
+  const int64_t n4 = (int64_t)n * r / 4;
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
+    int c = (int)((i * 4) % r);
+    f32x4 v = reinterpret_cast<const f32x4*>(src)[i];
+    f32x4 s = *reinterpret_cast<const f32x4*>(inv + c);
+    reinterpret_cast<f32x4*>(q)[i] = v * s;
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// Error feedback and parameter update in one pass over M, G and X:
+//   M_new = a (M + G) - b P R^T     (Alg. 1 line 7 / default form)
+//   X_new = X - lr P Q^T            (Alg. 1 lines 5-6)
+// The products are computed transposed (tile rows = columns j of the matrix) so that each
+// lane owns 4 consecutive j of one row i and moves M, G, X with vector accesses.
+// ------------------------------------------------------------------------------------
+template <class T, class Num, bool XBF, bool GBF>
+__global__ __launch_bounds__(T::THREADS) void k_efx(ClassDims d, MatPtrs ptrs, const float* scal, WsArr p, WsArr rr,
+                                                    float a_coef, float b_coef, float lr) {
+  extern __shared__ __align__(16) char lds[];
+  const int tiles_i = (d.m + T::NT - 1) / T::NT;
+  const int ti = blockIdx.x % tiles_i, tj = blockIdx.x / tiles_i;
+  const int z = blockIdx.z;
+  SrcF32 sp{p.base + (int64_t)z * p.stride, d.m, d.r, d.r};
+  SrcF32 sr{rr.base + (int64_t)z * rr.stride, d.n, d.r, d.r};
+  SrcF32 sq{ptrs.Q[z], d.n, d.r, d.r};
+  const float s_r = Num::F16 ? scal[z * kScalPerMat + 1] : 1.f;
+  const float s_u = Num::F16 ? kUnitScale : 1.f;
+  f32x16 acc_r[T::FM][T::FN], acc_q[T::FM][T::FN];
+  zero_acc<T>(acc_r);
+  zero_acc<T>(acc_q);
+  gemm_mainloop<T, Num, KC, SrcF32, KC, SrcF32>(sr, sp, tj * T::MT, ti * T::NT, 0, d.r, s_r, s_u, lds, acc_r);
+  gemm_mainloop<T, Num, KC, SrcF32, KC, SrcF32>(sq, sp, tj * T::MT, ti * T::NT, 0, d.r, s_u, s_u, lds, acc_q);
+  const float cr = b_coef / (s_r * s_u), cq = lr / (s_u * s_u);
+
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / T::WN, wn = wave % T::WN;
+  float* Mz = ptrs.M[z];
+#pragma unroll
+  for (int fn = 0; fn < T::FN; ++fn) {
+    const int i = ti * T::NT + wn * T::WTN + fn * 32 + (lane & 31);
+#pragma unroll
+    for (int fm = 0; fm < T::FM; ++fm) {
+#pragma unroll
+      for (int vq = 0; vq < 4; ++vq) {
+        const int j = tj * T::MT + wm * T::WTM + fm * 32 + 8 * vq + 4 * (lane >> 5);
+        if (i < d.m && j < d.n) {
+          float g[4], x[4];
+          if constexpr (GBF) {
+            u32x2 gv = *reinterpret_cast<const u32x2*>(reinterpret_cast<const uint16_t*>(ptrs.G[z]) + (int64_t)i * d.ldg + j);
+            g[0] = bf16_lo(gv[0]); g[1] = bf16_hi(gv[0]); g[2] = bf16_lo(gv[1]); g[3] = bf16_hi(gv[1]);
+          } else {
+            f32x4 gv = *reinterpret_cast<const f32x4*>(reinterpret_cast<const float*>(ptrs.G[z]) + (int64_t)i * d.ldg + j);
+            g[0] = gv[0]; g[1] = gv[1]; g[2] = gv[2]; g[3] = gv[3];
+          }
+          f32x4* mp = reinterpret_cast<f32x4*>(Mz + (int64_t)i * d.ldm + j);
+          f32x4 mv = *mp, mo;
+#pragma unroll
+          for (int e = 0; e < 4; ++e) mo[e] = a_coef * (mv[e] + g[e]) - cr * acc_r[fm][fn][4 * vq + e];
+          *mp = mo;
+          if constexpr (XBF) {
+            u32x2* xp = reinterpret_cast<u32x2*>(reinterpret_cast<uint16_t*>(ptrs.X[z]) + (int64_t)i * d.ldx + j);
+            u32x2 xv = *xp;
+            x[0] = bf16_lo(xv[0]); x[1] = bf16_hi(xv[0]); x[2] = bf16_lo(xv[1]); x[3] = bf16_hi(xv[1]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) x[e] -= cq * acc_q[fm][fn][4 * vq + e];
+            u32x2 xo;
+            xo[0] = pack_bf16_rne(x[0], x[1]);
+            xo[1] = pack_bf16_rne(x[2], x[3]);
+            *xp = xo;
+          } else {
+            f32x4* xp = reinterpret_cast<f32x4*>(reinterpret_cast<float*>(ptrs.X[z]) + (int64_t)i * d.ldx + j);
+            f32x4 xv = *xp;
+#pragma unroll
+            for (int e = 0; e < 4; ++e) xv[e] -= cq * acc_q[fm][fn][4 * vq + e];
+            *xp = xv;
+          }
+        }
+      }
+    }
+  }
+}
+
+// ====================================================================================
+// launchers
+// ====================================================================================
+#define OD_CHECK_LAUNCH()                       \
+  do {                                          \
+    hipError_t e_ = hipGetLastError();          \
+    if (e_ != hipSuccess) return e_;            \
+  } while (0)
+
+template <class K>
+static hipError_t allow_lds(K kernel, int bytes) {
+  if (bytes > 64 * 1024) return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
+  return hipSuccess;
+}
+
+hipError_t launch_fill_int(int* p, int64_t count, int value, hipStream_t st) {
+  if (count <= 0) return hipSuccess;
+  int blocks = (int)((count + 255) / 256);
+  if (blocks > 1024) blocks = 1024;
+  hipLaunchKernelGGL(k_fill_i32, dim3(blocks), dim3(256), 0, st, p, count, value);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+
+static hipError_t fill_f32(float* p, int64_t count, float v, hipStream_t st) {
+  if (count <= 0) return hipSuccess;
+  int blocks = (int)((count + 255) / 256);
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(k_fill_f32, dim3(blocks), dim3(256), 0, st, p, count, v);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+
+hipError_t launch_stats(const ClassDims& d, const MatPtrs& ptrs, float* scal, hipStream_t st) {
+  if (d.g_bf16) hipLaunchKernelGGL(k_stats<SrcBF16>, dim3(d.nb), dim3(256), 0, st, d, ptrs, scal);
+  else hipLaunchKernelGGL(k_stats<SrcF32>, dim3(d.nb), dim3(256), 0, st, d, ptrs, scal);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+
+template <class T, class Num, class GSrc>
+static hipError_t proj_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr part, int splits, hipStream_t st) {
+  constexpr int lds = T::template lds_bytes<Num>();
+  hipError_t e = allow_lds(k_proj<T, Num, GSrc>, lds);
+  if (e != hipSuccess) return e;
+  dim3 grid(((d.m + T::MT - 1) / T::MT) * ((d.r + T::NT - 1) / T::NT), splits, d.nb);
+  hipLaunchKernelGGL((k_proj<T, Num, GSrc>), grid, dim3(T::THREADS), lds, st, d, ptrs, scal, part, splits);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+template <class GSrc>
+static hipError_t proj_g(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr part, int splits, hipStream_t st) {
+  if (prec == PREC_BF3) return proj_t<TileSquare, NumBF<3>, GSrc>(d, ptrs, scal, part, splits, st);
+  if (d.r <= 64) return proj_t<TileNarrow, NumF16, GSrc>(d, ptrs, scal, part, splits, st);
+  if (d.r <= 128) return proj_t<TileSquare, NumF16, GSrc>(d, ptrs, scal, part, splits, st);
+  return proj_t<TileWide, NumF16, GSrc>(d, ptrs, scal, part, splits, st);
+}
+hipError_t launch_proj(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr part, int splits, hipStream_t st) {
+  return d.g_bf16 ? proj_g<SrcBF16>(d, ptrs, prec, scal, part, splits, st) : proj_g<SrcF32>(d, ptrs, prec, scal, part, splits, st);
+}
+
+template <class T, class Num, class GSrc>
+static hipError_t back_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr p, WsArr part, int splits, hipStream_t st) {
+  constexpr int lds = T::template lds_bytes<Num>();
+  hipError_t e = allow_lds(k_back<T, Num, GSrc>, lds);
+  if (e != hipSuccess) return e;
+  dim3 grid(((d.n + T::MT - 1) / T::MT) * ((d.r + T::NT - 1) / T::NT), splits, d.nb);
+  hipLaunchKernelGGL((k_back<T, Num, GSrc>), grid, dim3(T::THREADS), lds, st, d, ptrs, scal, p, part, splits);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+template <class GSrc>
+static hipError_t back_g(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p, WsArr part, int splits, hipStream_t st) {
+  if (prec == PREC_BF3) return back_t<TileSquare, NumBF<3>, GSrc>(d, ptrs, scal, p, part, splits, st);
+  if (d.r <= 64) return back_t<TileNarrow, NumF16, GSrc>(d, ptrs, scal, p, part, splits, st);
+  if (d.r <= 128) return back_t<TileSquare, NumF16, GSrc>(d, ptrs, scal, p, part, splits, st);
+  return back_t<TileWide, NumF16, GSrc>(d, ptrs, scal, p, part, splits, st);
+}
+hipError_t launch_back(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p, WsArr part, int splits, hipStream_t st) {
+  return d.g_bf16 ? back_g<SrcBF16>(d, ptrs, prec, scal, p, part, splits, st) : back_g<SrcF32>(d, ptrs, prec, scal, p, part, splits, st);
+}
+
+hipError_t launch_reduce(int nb, WsArr part, int splits, int64_t count, WsArr out, hipStream_t st) {
+  int64_t n4 = count / 4;
+  int blocks = (int)((n4 + 255) / 256);
+  if (blocks > 2048) blocks = 2048;
+  if (blocks < 1) blocks = 1;
+  hipLaunchKernelGGL(k_reduce, dim3(blocks, nb), dim3(256), 0, st, part, splits, count, out);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+
+template <class Num>
+static hipError_t gram_t(int nb, int rows, int r, WsArr a, WsArr part, int splits, hipStream_t st) {
+  typedef TileSquare T;
+  constexpr int lds = T::template lds_bytes<Num>();
+  hipError_t e = allow_lds(k_gram<T, Num>, lds);
+  if (e != hipSuccess) return e;
+  int tiles = (r + T::NT - 1) / T::NT;
+  hipLaunchKernelGGL((k_gram<T, Num>), dim3(tiles * tiles, splits, nb), dim3(T::THREADS), lds, st, rows, r, a, part, splits);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits, int exact, hipStream_t st) {
+  return exact ? gram_t<NumBF<3>>(nb, rows, r, a, part, splits, st) : gram_t<NumBF<2>>(nb, rows, r, a, part, splits, st);
+}
+
+template <class Num>
+static hipError_t apply_t(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* ptrs, hipStream_t st) {
+  typedef TileSquare T;
+  constexpr int lds = T::template lds_bytes<Num>();
+  hipError_t e = allow_lds(k_apply<T, Num>, lds);
+  if (e != hipSuccess) return e;
+  MatPtrs none = {};
+  dim3 grid(((rows + T::MT - 1) / T::MT) * ((r + T::NT - 1) / T::NT), 1, nb);
+  hipLaunchKernelGGL((k_apply<T, Num>), grid, dim3(T::THREADS), lds, st, rows, r, a, w, out, ptrs ? *ptrs : none, ptrs ? 1 : 0);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs, int exact, hipStream_t st) {
+  return exact ? apply_t<NumBF<3>>(nb, rows, r, a, w, out, q_ptrs, st) : apply_t<NumBF<2>>(nb, rows, r, a, w, out, q_ptrs, st);
+}
+
+template <class Num, class DirA>
+static hipError_t sgemm_t(int nb, const SgemmArgs& g, hipStream_t st) {
+  typedef TileSquare T;
+  constexpr int lds = T::template lds_bytes<Num>();
+  hipError_t e = allow_lds(k_sgemm<T, Num, DirA>, lds);
+  if (e != hipSuccess) return e;
+  dim3 grid(((g.Mc + T::MT - 1) / T::MT) * ((g.Nc + T::NT - 1) / T::NT), 1, nb * g.nq);
+  hipLaunchKernelGGL((k_sgemm<T, Num, DirA>), grid, dim3(T::THREADS), lds, st, g);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+static hipError_t sgemm(int nb, const SgemmArgs& g, bool a_kc, int exact, hipStream_t st) {
+  if (g.Mc <= 0 || g.Nc <= 0 || g.Kc <= 0 || g.nq <= 0) return hipSuccess;
+  if (exact) return a_kc ? sgemm_t<NumBF<3>, KC>(nb, g, st) : sgemm_t<NumBF<3>, KS>(nb, g, st);
+  return a_kc ? sgemm_t<NumBF<2>, KC>(nb, g, st) : sgemm_t<NumBF<2>, KS>(nb, g, st);
+}
+
+hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp, int* info, int info_slot, int exact,
+                          hipStream_t st) {
+  hipError_t e = allow_lds(k_chol_leaf, kLeafLds);
+  if (e != hipSuccess) return e;
+  const int nblk = (r + kLeaf - 1) / kLeaf;
+  if (nblk > 1) {
+    // lower block triangles of T and W are never written below; clear them once
+    for (int z = 0; z < nb; ++z) {
+      if ((e = fill_f32(t.base + (int64_t)z * t.stride, (int64_t)r * r, 0.f, st)) != hipSuccess) return e;
+      if ((e = fill_f32(w.base + (int64_t)z * w.stride, (int64_t)r * r, 0.f, st)) != hipSuccess) return e;
+    }
+  }
+  for (int p = 0; p < nblk; ++p) {
+    hipLaunchKernelGGL(k_chol_leaf, dim3(nb), dim3(256), kLeafLds, st, gram, t, w, r, p, info, info_slot);
+    OD_CHECK_LAUNCH();
+    if (p + 1 == nblk) break;
+    const int o = p * kLeaf, o1 = (p + 1) * kLeaf, rest = r - o1;
+    SgemmArgs g = {};
+    g.r = r; g.nq = 1; g.q_step = 0;
+    // T(p, rest) = W_pp^T G(p, rest)
+    g.a = w; g.b = gram; g.c = t;
+    g.a_r0 = o; g.a_k0 = o; g.b_k0 = o; g.b_c0 = o1; g.c_r0 = o; g.c_c0 = o1;
+    g.Mc = kLeaf; g.Nc = rest; g.Kc = kLeaf; g.alpha = 1.f; g.beta = 0.f;
+    if ((e = sgemm(nb, g, false, exact, st)) != hipSuccess) return e;
+    // G(rest, rest) -= T(p, rest)^T T(p, rest)
+    g.a = t; g.b = t; g.c = gram;
+    g.a_r0 = o1; g.a_k0 = o; g.b_k0 = o; g.b_c0 = o1; g.c_r0 = o1; g.c_c0 = o1;
+    g.Mc = rest; g.Nc = rest; g.Kc = kLeaf; g.alpha = -1.f; g.beta = 1.f;
+    if ((e = sgemm(nb, g, false, exact, st)) != hipSuccess) return e;
+  }
+  // W(I, I+d) = -W_II * sum_{K=I+1..I+d} T(I, K) W(K, I+d), block diagonal by block diagonal
+  for (int d = 1; d < nblk; ++d) {
+    SgemmArgs g = {};
+    g.r = r; g.nq = nblk - d; g.q_step = kLeaf;
+    g.a = t; g.b = w; g.c = tmp;
+    g.a_r0 = 0; g.a_k0 = kLeaf; g.b_k0 = kLeaf; g.b_c0 = d * kLeaf; g.c_r0 = 0; g.c_c0 = d * kLeaf;
+    g.Mc = kLeaf; g.Nc = kLeaf; g.Kc = d * kLeaf; g.alpha = 1.f; g.beta = 0.f;
+    if ((e = sgemm(nb, g, true, exact, st)) != hipSuccess) return e;
+    g.a = w; g.b = tmp; g.c = w;
+    g.a_r0 = 0; g.a_k0 = 0; g.b_k0 = 0; g.b_c0 = d * kLeaf; g.c_r0 = 0; g.c_c0 = d * kLeaf;
+    g.Mc = kLeaf; g.Nc = kLeaf; g.Kc = kLeaf; g.alpha = -1.f; g.beta = 0.f;
+    if ((e = sgemm(nb, g, true, exact, st)) != hipSuccess) return e;
+  }
+  return hipSuccess;
+}
+
+hipError_t launch_scale_from_trace(int nb, int n, int r, WsArr gram, float* scal, hipStream_t st) {
+  hipLaunchKernelGGL(k_scale_from_trace, dim3(nb), dim3(256), 0, st, n, r, gram, scal);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+
+hipError_t launch_colnorm(int nb, int n, int r, WsArr rr, const MatPtrs& ptrs, WsArr part, int slabs, WsArr colsq,
+                          float* scal, int* info, hipStream_t st) {
+  hipLaunchKernelGGL(k_colsq_partial, dim3((r + 255) / 256, slabs, nb), dim3(256), 0, st, n, r, rr, part, slabs);
+  OD_CHECK_LAUNCH();
+  hipLaunchKernelGGL(k_colsq_final, dim3(nb), dim3(256), 0, st, n, r, part, slabs, colsq, scal, info);
+  OD_CHECK_LAUNCH();
+  int64_t n4 = (int64_t)n * r / 4;
+  int blocks = (int)((n4 + 255) / 256);
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(k_colnorm_apply, dim3(blocks, nb), dim3(256), 0, st, n, r, rr, colsq, ptrs);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+
+template <class Num, bool XBF, bool GBF>
+static hipError_t efx_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr p, WsArr rr, float a_coef,
+                        float b_coef, float lr, hipStream_t st) {
+  typedef TileSquare T;
+  constexpr int lds = T::template lds_bytes<Num>();
+  hipError_t e = allow_lds(k_efx<T, Num, XBF, GBF>, lds);
+  if (e != hipSuccess) return e;
+  dim3 grid(((d.m + T::NT - 1) / T::NT) * ((d.n + T::MT - 1) / T::MT), 1, d.nb);
+  hipLaunchKernelGGL((k_efx<T, Num, XBF, GBF>), grid, dim3(T::THREADS), lds, st, d, ptrs, scal, p, rr, a_coef, b_coef, lr);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+template <class Num>
+static hipError_t efx_n(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr p, WsArr rr, float a_coef,
+                        float b_coef, float lr, hipStream_t st) {
+  if (d.x_bf16) return d.g_bf16 ? efx_t<Num, true, true>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st)
+                                : efx_t<Num, true, false>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st);
+  return d.g_bf16 ? efx_t<Num, false, true>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st)
+                  : efx_t<Num, false, false>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st);
+}
+hipError_t launch_efx(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p, WsArr rr,
+                      float a_coef, float b_coef, float lr, hipStream_t st) {
+  return prec == PREC_BF3 ? efx_n<NumBF<3>>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st)
+                          : efx_n<NumF16>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st);
+}
+
+}  // namespace od
