@@ -129,6 +129,28 @@ int orthdion_get_info(orthdion_handle h, int32_t* info_host, void* stream);
 int orthdion_workspace_layout(orthdion_handle h, int32_t index, size_t* off_p, size_t* off_r,
                               size_t* off_tp1, size_t* off_tp2, size_t* off_tq1, size_t* off_tq2);
 
+/* Optional timing of the phases of orthdion_step with HIP events recorded on the step's
+ * own stream (host-side resources only; do not use while the stream is being captured into
+ * a graph).  A phase with one kernel (PROJ, BACK, EFX) is exactly that kernel's launch.
+ *   orthdion_profile_begin  brackets every phase whose bit (1u << phase) is set in
+ *                           phase_mask, for the next max_steps calls of orthdion_step.
+ *   orthdion_profile_end    waits for the recorded events, then writes, per phase, the summed
+ *                           elapsed milliseconds and the number of intervals summed (steps x
+ *                           shape-class batches) into two arrays of ORTHDION_NPHASE entries. */
+typedef enum {
+  ORTHDION_PHASE_STATS = 0,        /* sampled scale of B for the fp16 operand format      */
+  ORTHDION_PHASE_PROJ = 1,         /* kernel: P_raw partials = (M + G) Q      (line 2)    */
+  ORTHDION_PHASE_PROJ_REDUCE = 2,  /* second stage of the split contraction               */
+  ORTHDION_PHASE_ORTH_LEFT = 3,    /* P = orth(P_raw), CholeskyQR2            (line 2)    */
+  ORTHDION_PHASE_BACK = 4,         /* kernel: R partials = (M + G)^T P        (line 3)    */
+  ORTHDION_PHASE_BACK_REDUCE = 5,
+  ORTHDION_PHASE_ORTH_RIGHT = 6,   /* Q = orth(R) or ColNorm(R)               (line 4)    */
+  ORTHDION_PHASE_EFX = 7,          /* kernel: error feedback + update         (lines 5-7) */
+  ORTHDION_NPHASE = 8
+} orthdion_phase;
+int orthdion_profile_begin(orthdion_handle h, uint32_t phase_mask, int32_t max_steps);
+int orthdion_profile_end(orthdion_handle h, float* ms_per_phase, int32_t* count_per_phase);
+
 const char* orthdion_strerror(int status);
 
 int orthdion_destroy(orthdion_handle h);

@@ -26,7 +26,10 @@ ORTHDION_PREC_AUTO, ORTHDION_PREC_FAST, ORTHDION_PREC_EXACT = 0, 1, 2
 
 EXPORTS = ["orthdion_create", "orthdion_workspace_bytes", "orthdion_set_lr", "orthdion_set_mu",
            "orthdion_set_variant", "orthdion_step", "orthdion_get_info", "orthdion_workspace_layout",
-           "orthdion_strerror", "orthdion_destroy"]
+           "orthdion_profile_begin", "orthdion_profile_end", "orthdion_strerror", "orthdion_destroy"]
+
+PHASES = ["stats", "proj", "proj_reduce", "orth_left", "back", "back_reduce", "orth_right", "efx"]
+ORTHDION_NPHASE = len(PHASES)
 
 
 class orthdion_matdesc(ctypes.Structure):
@@ -43,6 +46,23 @@ class orthdion_config(ctypes.Structure):
 _lib: Optional[ctypes.CDLL] = None
 
 
+def _share_torch_hip_runtime() -> None:
+    """PyTorch wheels ship their own copy of the HIP runtime (same SONAME as ROCm's).  Device
+    pointers and streams are only meaningful inside one runtime instance, so when this
+    library is loaded before torch it must bind to torch's copy, not to /opt/rocm's: map
+    torch's copy first and the loader resolves our dependency to it by SONAME."""
+    import importlib.util
+    try:
+        spec = importlib.util.find_spec("torch")
+    except (ImportError, ValueError):
+        spec = None
+    if spec is None or not spec.submodule_search_locations:
+        return
+    cand = os.path.join(list(spec.submodule_search_locations)[0], "lib", "libamdhip64.so")
+    if os.path.exists(cand):
+        ctypes.CDLL(cand, mode=ctypes.RTLD_GLOBAL)
+
+
 def load() -> ctypes.CDLL:
     """Loads the in-tree library (built by build.py); raises if it is not there."""
     global _lib
@@ -51,6 +71,7 @@ def load() -> ctypes.CDLL:
     if not os.path.exists(LIB_PATH):
         raise RuntimeError(f"{LIB_PATH} is missing: build it with `python -m paper_2605_16341_amd.build` "
                            "(there is no fallback path)")
+    _share_torch_hip_runtime()
     lib = ctypes.CDLL(LIB_PATH)
     vp, sz = ctypes.c_void_p, ctypes.c_size_t
     lib.orthdion_create.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(orthdion_matdesc), ctypes.c_int32,
@@ -71,6 +92,10 @@ def load() -> ctypes.CDLL:
     lib.orthdion_get_info.restype = ctypes.c_int
     lib.orthdion_workspace_layout.argtypes = [vp, ctypes.c_int32] + [ctypes.POINTER(sz)] * 6
     lib.orthdion_workspace_layout.restype = ctypes.c_int
+    lib.orthdion_profile_begin.argtypes = [vp, ctypes.c_uint32, ctypes.c_int32]
+    lib.orthdion_profile_begin.restype = ctypes.c_int
+    lib.orthdion_profile_end.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32)]
+    lib.orthdion_profile_end.restype = ctypes.c_int
     lib.orthdion_strerror.argtypes = [ctypes.c_int]
     lib.orthdion_strerror.restype = ctypes.c_char_p
     lib.orthdion_destroy.argtypes = [vp]
@@ -153,6 +178,18 @@ def orthdion_workspace_layout(handle: int, index: int) -> dict:
     _check(load().orthdion_workspace_layout(handle, int(index), *[ctypes.byref(v) for v in vals]))
     keys = ["P", "R", "T_P1", "T_P2", "T_Q1", "T_Q2"]
     return {k: int(v.value) for k, v in zip(keys, vals)}
+
+
+def orthdion_profile_begin(handle: int, phase_mask: int, max_steps: int) -> None:
+    _check(load().orthdion_profile_begin(handle, int(phase_mask), int(max_steps)))
+
+
+def orthdion_profile_end(handle: int) -> dict:
+    """{phase name: (total milliseconds, intervals)} for the phases that were bracketed."""
+    ms = (ctypes.c_float * ORTHDION_NPHASE)()
+    cnt = (ctypes.c_int32 * ORTHDION_NPHASE)()
+    _check(load().orthdion_profile_end(handle, ms, cnt))
+    return {PHASES[i]: (float(ms[i]), int(cnt[i])) for i in range(ORTHDION_NPHASE) if cnt[i] > 0}
 
 
 def orthdion_destroy(handle: int) -> None:

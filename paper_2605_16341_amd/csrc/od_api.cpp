@@ -51,7 +51,19 @@ struct orthdion_ctx {
   std::vector<int> batch_of, slot_of;     // per matrix
   size_t off_scal, off_info, ws_bytes;
   void* last_ws;
+  // optional phase timing with HIP events (host resources only)
+  bool prof_on = false;
+  unsigned prof_mask = 0;
+  int prof_max_steps = 0, prof_steps = 0;
+  std::vector<hipEvent_t> prof_events;    // [step][batch][phase][begin/end]
 };
+
+static hipEvent_t* prof_slot(orthdion_ctx* h, int batch, int phase, int end) {
+  if (!h->prof_on || h->prof_steps >= h->prof_max_steps || !(h->prof_mask & (1u << phase))) return nullptr;
+  size_t nb = h->batches.size();
+  size_t idx = (((size_t)h->prof_steps * nb + (size_t)batch) * ORTHDION_NPHASE + (size_t)phase) * 2 + (size_t)end;
+  return &h->prof_events[idx];
+}
 
 static od::Prec resolve_prec(const orthdion_config& c) {
   if (c.precision == ORTHDION_PREC_FAST) return od::PREC_F16;
@@ -230,6 +242,9 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
   }
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   char* ws = reinterpret_cast<char*>(workspace);
+  // Launch errors are read back with hipGetLastError; drop whatever an earlier, unrelated
+  // HIP call of this thread left there (e.g. a not-ready event query of the caller).
+  (void)hipGetLastError();
   const od::Prec prec = resolve_prec(h->cfg);
   const int exact = prec == od::PREC_BF3 ? 1 : 0;
   float a_coef, b_coef;
@@ -241,7 +256,17 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
   OD_TRY(od::launch_fill_int(info_all, (int64_t)nmat * od::kInfoPerMat, 0, st));
   h->last_ws = workspace;
 
-  for (const Batch& b : h->batches) {
+#define OD_PHASE_BEGIN(ph)                                                   \
+  do {                                                                       \
+    if (hipEvent_t* e_ = prof_slot(h, bi, ph, 0)) OD_TRY(hipEventRecord(*e_, st)); \
+  } while (0)
+#define OD_PHASE_END(ph)                                                     \
+  do {                                                                       \
+    if (hipEvent_t* e_ = prof_slot(h, bi, ph, 1)) OD_TRY(hipEventRecord(*e_, st)); \
+  } while (0)
+
+  for (int bi = 0; bi < (int)h->batches.size(); ++bi) {
+    const Batch& b = h->batches[bi];
     const ClassDims& d = b.d;
     MatPtrs ptrs;
     std::memset(&ptrs, 0, sizeof(ptrs));
@@ -257,16 +282,29 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     WsArr colsq{reinterpret_cast<float*>(ws + b.off_colsq), b.st_colsq};
 
     // Alg. 1 lines 1-2: P_raw = (M + G) Q, then P = orth(P_raw)
+    OD_PHASE_BEGIN(ORTHDION_PHASE_STATS);
     if (prec == od::PREC_F16) OD_TRY(od::launch_stats(d, ptrs, scal, st));
+    OD_PHASE_END(ORTHDION_PHASE_STATS);
+    OD_PHASE_BEGIN(ORTHDION_PHASE_PROJ);
     OD_TRY(od::launch_proj(d, ptrs, prec, scal, part, b.splits_proj, st));
+    OD_PHASE_END(ORTHDION_PHASE_PROJ);
+    OD_PHASE_BEGIN(ORTHDION_PHASE_PROJ_REDUCE);
     OD_TRY(od::launch_reduce(d.nb, part, b.splits_proj, (int64_t)d.m * d.r, pa, st));
+    OD_PHASE_END(ORTHDION_PHASE_PROJ_REDUCE);
+    OD_PHASE_BEGIN(ORTHDION_PHASE_ORTH_LEFT);
     int rc = cholqr2(b, ws, d.m, b.off_pa, b.off_pb, b.st_p, b.splits_gram_p, b.off_tp1, b.off_tp2, 0, nullptr,
                      false, scal, info, exact, st);
     if (rc != ORTHDION_OK) return rc;
+    OD_PHASE_END(ORTHDION_PHASE_ORTH_LEFT);
     // line 3: R = (M + G)^T P
+    OD_PHASE_BEGIN(ORTHDION_PHASE_BACK);
     OD_TRY(od::launch_back(d, ptrs, prec, scal, pa, part, b.splits_back, st));
+    OD_PHASE_END(ORTHDION_PHASE_BACK);
+    OD_PHASE_BEGIN(ORTHDION_PHASE_BACK_REDUCE);
     OD_TRY(od::launch_reduce(d.nb, part, b.splits_back, (int64_t)d.n * d.r, ra, st));
+    OD_PHASE_END(ORTHDION_PHASE_BACK_REDUCE);
     // line 4: Q = orth(R) or ColNorm(R), written to the callers' Q (Q_prev is no longer needed)
+    OD_PHASE_BEGIN(ORTHDION_PHASE_ORTH_RIGHT);
     if (h->cfg.variant == ORTHDION_QR) {
       rc = cholqr2(b, ws, d.n, b.off_ra, b.off_rb, b.st_r, b.splits_gram_q, b.off_tq1, b.off_tq2, 1, &ptrs, true,
                    scal, info, exact, st);
@@ -274,10 +312,61 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     } else {
       OD_TRY(od::launch_colnorm(d.nb, d.n, d.r, ra, ptrs, part, b.slabs, colsq, scal, info, st));
     }
+    OD_PHASE_END(ORTHDION_PHASE_ORTH_RIGHT);
     // lines 5-7: parameter update and error feedback in one pass
+    OD_PHASE_BEGIN(ORTHDION_PHASE_EFX);
     OD_TRY(od::launch_efx(d, ptrs, prec, scal, pa, ra, a_coef, b_coef, h->cfg.lr, st));
+    OD_PHASE_END(ORTHDION_PHASE_EFX);
   }
+  if (h->prof_on && h->prof_steps < h->prof_max_steps) h->prof_steps++;
   return ORTHDION_OK;
+}
+
+extern "C" int orthdion_profile_begin(orthdion_handle h, uint32_t phase_mask, int32_t max_steps) {
+  if (!h) return ORTHDION_E_NULL_PTR;
+  if (max_steps < 1 || max_steps > 100000 || h->prof_on) return ORTHDION_E_INVALID_ARG;
+  size_t count = (size_t)max_steps * h->batches.size() * ORTHDION_NPHASE * 2;
+  h->prof_events.assign(count, nullptr);
+  for (int s = 0; s < max_steps; ++s)
+    for (size_t b = 0; b < h->batches.size(); ++b)
+      for (int ph = 0; ph < ORTHDION_NPHASE; ++ph)
+        if (phase_mask & (1u << ph))
+          for (int e = 0; e < 2; ++e) {
+            size_t idx = (((size_t)s * h->batches.size() + b) * ORTHDION_NPHASE + (size_t)ph) * 2 + (size_t)e;
+            if (hipEventCreate(&h->prof_events[idx]) != hipSuccess) return ORTHDION_E_HIP;
+          }
+  h->prof_mask = phase_mask;
+  h->prof_max_steps = max_steps;
+  h->prof_steps = 0;
+  h->prof_on = true;
+  return ORTHDION_OK;
+}
+
+extern "C" int orthdion_profile_end(orthdion_handle h, float* ms_per_phase, int32_t* count_per_phase) {
+  if (!h || !ms_per_phase || !count_per_phase) return ORTHDION_E_NULL_PTR;
+  if (!h->prof_on) return ORTHDION_E_INVALID_ARG;
+  int rc = ORTHDION_OK;
+  for (int ph = 0; ph < ORTHDION_NPHASE; ++ph) { ms_per_phase[ph] = 0.f; count_per_phase[ph] = 0; }
+  const size_t nb = h->batches.size();
+  for (int s = 0; s < h->prof_steps; ++s)
+    for (size_t b = 0; b < nb; ++b)
+      for (int ph = 0; ph < ORTHDION_NPHASE; ++ph) {
+        if (!(h->prof_mask & (1u << ph))) continue;
+        size_t idx = (((size_t)s * nb + b) * ORTHDION_NPHASE + (size_t)ph) * 2;
+        float ms = 0.f;
+        if (hipEventSynchronize(h->prof_events[idx + 1]) != hipSuccess ||
+            hipEventElapsedTime(&ms, h->prof_events[idx], h->prof_events[idx + 1]) != hipSuccess) {
+          rc = ORTHDION_E_HIP;
+          continue;
+        }
+        ms_per_phase[ph] += ms;
+        count_per_phase[ph] += 1;
+      }
+  for (hipEvent_t e : h->prof_events)
+    if (e) (void)hipEventDestroy(e);
+  h->prof_events.clear();
+  h->prof_on = false;
+  return rc;
 }
 
 extern "C" int orthdion_get_info(orthdion_handle h, int32_t* info_host, void* stream) {
@@ -332,6 +421,8 @@ extern "C" const char* orthdion_strerror(int status) {
 
 extern "C" int orthdion_destroy(orthdion_handle h) {
   if (!h) return ORTHDION_E_NULL_PTR;
+  for (hipEvent_t e : h->prof_events)
+    if (e) (void)hipEventDestroy(e);
   delete h;
   return ORTHDION_OK;
 }
