@@ -152,8 +152,10 @@ extern "C" int orthdion_create(orthdion_handle* out, const orthdion_matdesc* mat
     b.splits_proj = pick_splits(((m + 127) / 128) * tiles_r, d.nb, n, 128);
     b.splits_back = pick_splits(((n + 127) / 128) * tiles_r, d.nb, m, 128);
     const int64_t gt = ((r + 127) / 128) * ((r + 127) / 128);
-    b.splits_gram_p = pick_splits(gt, d.nb, m, 128);
-    b.splits_gram_q = pick_splits(gt, d.nb, n, 128);
+    b.splits_gram_p = pick_splits(gt, d.nb, m, 256);
+    b.splits_gram_q = pick_splits(gt, d.nb, n, 256);
+    if (b.splits_gram_p > 8) b.splits_gram_p = 8;
+    if (b.splits_gram_q > 8) b.splits_gram_q = 8;
     b.slabs = (int)((n + 511) / 512);
     if (b.slabs > 64) b.slabs = 64;
     int64_t part = (int64_t)b.splits_proj * m * r;
@@ -206,7 +208,8 @@ extern "C" int orthdion_set_variant(orthdion_handle h, orthdion_variant v) {
     if ((expr) != hipSuccess) return ORTHDION_E_HIP;  \
   } while (0)
 
-// CholeskyQR2 of `a0` (rows x r): pass 1 a0 -> a1, pass 2 a1 -> (a0 | callers' Q).
+// orth() of `a0` (rows x r) by CholeskyQR2: pass 1 (Gram, Cholesky, a1 = a0 W1) and a
+// first-order second pass (Gram of a1, W2 = I - Phi(E), result = a1 W2 -> a0 | callers' Q).
 static int cholqr2(const Batch& b, char* ws, int rows, size_t off_a0, size_t off_a1, int64_t st_a, int splits,
                    size_t off_t1, size_t off_t2, int info_slot, const MatPtrs* q_out, bool want_r_scale, float* scal,
                    int* info, int exact, hipStream_t st) {
@@ -216,14 +219,12 @@ static int cholqr2(const Batch& b, char* ws, int rows, size_t off_a0, size_t off
   WsArr gram{reinterpret_cast<float*>(ws + b.off_gram), b.st_rr};
   WsArr w{reinterpret_cast<float*>(ws + b.off_w), b.st_rr}, tmp{reinterpret_cast<float*>(ws + b.off_tmp), b.st_rr};
   WsArr t1{reinterpret_cast<float*>(ws + off_t1), b.st_rr}, t2{reinterpret_cast<float*>(ws + off_t2), b.st_rr};
-  OD_TRY(od::launch_gram(nb, rows, r, a0, part, splits, exact, st));
-  OD_TRY(od::launch_reduce(nb, part, splits, (int64_t)r * r, gram, st));
-  if (want_r_scale) OD_TRY(od::launch_scale_from_trace(nb, rows, r, gram, scal, st));
-  OD_TRY(od::launch_cholinv(nb, r, gram, t1, w, tmp, info, info_slot, exact, st));
+  OD_TRY(od::launch_gram(nb, rows, r, a0, part, splits, 1, st));
+  OD_TRY(od::launch_cholinv(nb, r, gram, part, splits, t1, w, tmp, info, info_slot, want_r_scale ? scal : nullptr,
+                            rows, st));
   OD_TRY(od::launch_apply(nb, rows, r, a0, w, a1, nullptr, exact, st));
   OD_TRY(od::launch_gram(nb, rows, r, a1, part, splits, exact, st));
-  OD_TRY(od::launch_reduce(nb, part, splits, (int64_t)r * r, gram, st));
-  OD_TRY(od::launch_cholinv(nb, r, gram, t2, w, tmp, info, info_slot, exact, st));
+  OD_TRY(od::launch_corr(nb, r, part, splits, t2, w, scal, 2 + info_slot, st));
   OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, exact, st));
   return ORTHDION_OK;
 }
@@ -254,6 +255,7 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
   int* info_all = reinterpret_cast<int*>(ws + h->off_info);
   float* scal_all = reinterpret_cast<float*>(ws + h->off_scal);
   OD_TRY(od::launch_fill_int(info_all, (int64_t)nmat * od::kInfoPerMat, 0, st));
+  OD_TRY(od::launch_fill_f32(scal_all, (int64_t)nmat * od::kScalPerMat, 0.f, st));
   h->last_ws = workspace;
 
 #define OD_PHASE_BEGIN(ph)                                                   \

@@ -33,8 +33,11 @@ struct WsArr {
   int64_t stride;      // elements between consecutive matrices
 };
 
-// scal layout per matrix (floats): [0] scale of B, [1] scale of R, [2..7] spare
-constexpr int kScalPerMat = 8;
+// scal layout per matrix (floats): [1] scale of R, [2] / [3] largest deviation of the
+// first-pass Gram matrix of the left / right factor from identity, [8..39] sampled row sums
+// of squares of B
+constexpr int kScalPerMat = 40;
+constexpr int kScalSample = 8;
 // info layout per matrix (ints): [0] left-factor breakdown column, [1] right-factor
 // breakdown column (1-based, 0 = none), [2] zero-column flag of ColNorm, [3] spare
 constexpr int kInfoPerMat = 4;
@@ -57,13 +60,20 @@ hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits,
 hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs,
                         int exact, hipStream_t st);
 
-// Cholesky factor and its inverse of an SPD r x r matrix (ld r): gram = T^T T, W = T^-1,
-// both upper triangular with zeros below the diagonal.  `gram` is destroyed; `tmp` is
-// r x r scratch.  A non-positive or non-finite pivot writes its 1-based column to
-// info[mat * kInfoPerMat + info_slot] (first failure wins) and the factorisation goes on
-// with that pivot replaced by 1.
-hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp, int* info,
-                          int info_slot, int exact, hipStream_t st);
+// Cholesky factor and its inverse of the SPD r x r matrix sum_s part[s] (ld r): = T^T T,
+// W = T^-1, both upper triangular with zeros below the diagonal.  For r <= 256 one workgroup
+// per matrix does everything; above, `gram` receives the reduced matrix (destroyed) and the
+// factorisation is blocked, `tmp` being r x r scratch.  A non-positive or non-finite pivot
+// writes its 1-based column to info[mat * kInfoPerMat + info_slot] (first failure wins) and
+// the factorisation goes on with that pivot replaced by 1.  With scal != nullptr also writes
+// the power-of-two scale of the tall matrix (trace_rows x r) whose Gram matrix this is.
+hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr part, int splits, WsArr t, WsArr w, WsArr tmp, int* info,
+                          int info_slot, float* scal, int trace_rows, hipStream_t st);
+
+// First-order second pass: from the Gram partials of a nearly orthonormal matrix writes
+// T2 = I + Phi(E), W2 = I - Phi(E) and max |E| into scal[mat][scal_slot] (must be zeroed).
+hipError_t launch_corr(int nb, int r, WsArr part, int splits, WsArr t2, WsArr w2, float* scal, int scal_slot,
+                       hipStream_t st);
 
 // scal[mat][1] = power-of-two scale for R from trace(gram) = ||R||_F^2 (rows n, cols r)
 hipError_t launch_scale_from_trace(int nb, int n, int r, WsArr gram, float* scal, hipStream_t st);
@@ -78,5 +88,6 @@ hipError_t launch_efx(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const 
                       WsArr rr, float a_coef, float b_coef, float lr, hipStream_t st);
 
 hipError_t launch_fill_int(int* p, int64_t count, int value, hipStream_t st);
+hipError_t launch_fill_f32(float* p, int64_t count, float value, hipStream_t st);
 
 }  // namespace od

@@ -5,6 +5,7 @@
 // ColNorm(R) (line 4), X -= lr P Q^T (lines 5-6), M = a B - b P R^T (line 7).
 #include "od_kernels.h"
 
+#include "od_chol.h"
 #include "od_gemm.h"
 
 namespace od {
@@ -39,15 +40,23 @@ OD_DEV SrcSum<GSrc> make_b_source(const ClassDims& d, const MatPtrs& ptrs, int z
 // ------------------------------------------------------------------------------------
 // sampled power-of-two scale of B for the fp16 operand format
 // ------------------------------------------------------------------------------------
+OD_DEV float pow2_scale_for_rms(float ms) {
+  if (ms > 0.f && ms < 3.0e38f) return ldexpf(1.f, -ilogbf(sqrtf(ms)));
+  return 1.f;
+}
+
+constexpr int kStatRows = 32;      // sampled rows per matrix, one workgroup each
+
 template <class GSrc>
 __global__ __launch_bounds__(256) void k_stats(ClassDims d, MatPtrs ptrs, float* scal) {
-  const int z = blockIdx.x, tid = threadIdx.x;
+  const int z = blockIdx.y, tid = threadIdx.x;
   SrcSum<GSrc> b = make_b_source<GSrc>(d, ptrs, z);
-  const int nrows = d.m < 64 ? d.m : 64;
+  const int nrows = d.m < kStatRows ? d.m : kStatRows;
   float acc = 0.f;
   const int groups = d.n / 8;
-  for (int idx = tid; idx < nrows * groups; idx += 256) {
-    int s = idx / groups, c = (idx % groups) * 8;
+  if ((int)blockIdx.x < nrows)
+  for (int idx = tid; idx < groups; idx += 256) {
+    int s = blockIdx.x, c = idx * 8;
     int row = (int)(((int64_t)s * d.m) / nrows);
     float x[8];
     SrcSum<GSrc>::unpack8(b.load8(row, c), x);
@@ -61,12 +70,15 @@ __global__ __launch_bounds__(256) void k_stats(ClassDims d, MatPtrs ptrs, float*
     if (tid < w) red[tid] += red[tid + w];
     __syncthreads();
   }
-  if (tid == 0) {
-    float ms = red[0] / ((float)nrows * (float)d.n);
-    float scale = 1.f;
-    if (ms > 0.f && ms < 3.0e38f) scale = ldexpf(1.f, -ilogbf(sqrtf(ms)));
-    scal[z * kScalPerMat + 0] = scale;
-  }
+  if (tid == 0) scal[z * kScalPerMat + kScalSample + blockIdx.x] = red[0];
+}
+
+// scale of B from the sampled row sums of squares (same value in every consumer)
+OD_DEV float b_scale(const ClassDims& d, const float* scal, int z) {
+  const int nrows = d.m < kStatRows ? d.m : kStatRows;
+  float tot = 0.f;
+  for (int i = 0; i < nrows; ++i) tot += scal[z * kScalPerMat + kScalSample + i];
+  return pow2_scale_for_rms(tot / ((float)nrows * (float)d.n));
 }
 
 // ------------------------------------------------------------------------------------
@@ -82,7 +94,7 @@ __global__ __launch_bounds__(T::THREADS) void k_proj(ClassDims d, MatPtrs ptrs, 
   SrcF32 b{ptrs.Q[z], d.n, d.r, d.r};
   int kend;
   const int kbeg = split_begin(d.n, splits, T::KT, split, &kend);
-  const float sa = Num::F16 ? scal[z * kScalPerMat + 0] : 1.f;
+  const float sa = Num::F16 ? b_scale(d, scal, z) : 1.f;
   const float sb = Num::F16 ? kUnitScale : 1.f;
   f32x16 acc[T::FM][T::FN];
   zero_acc<T>(acc);
@@ -107,7 +119,7 @@ __global__ __launch_bounds__(T::THREADS) void k_back(ClassDims d, MatPtrs ptrs, 
   SrcF32 b{p.base + (int64_t)z * p.stride, d.m, d.r, d.r};
   int kend;
   const int kbeg = split_begin(d.m, splits, T::KT, split, &kend);
-  const float sa = Num::F16 ? scal[z * kScalPerMat + 0] : 1.f;
+  const float sa = Num::F16 ? b_scale(d, scal, z) : 1.f;
   const float sb = Num::F16 ? kUnitScale : 1.f;
   f32x16 acc[T::FM][T::FN];
   zero_acc<T>(acc);
@@ -235,100 +247,45 @@ __global__ __launch_bounds__(T::THREADS) void k_sgemm(SgemmArgs g) {
 }
 
 
+constexpr int kLeaf = kCholMax;   // diagonal block of the blocked factorisation
+
 // ------------------------------------------------------------------------------------
-// Cholesky factor and inverse of one diagonal block (at most 128 x 128) in LDS.
-//   gram block = T^T T (upper T), W = T^-1.  One workgroup per matrix.
+// Second CholeskyQR pass as a first-order correction.  After the first pass the Gram matrix
+// is I + E with small E; its Cholesky factor is I + Phi(E) + O(E^2), Phi = strict upper
+// triangle + half the diagonal, and the inverse factor I - Phi(E) + O(E^2).  Writes
+// T2 = I + Phi(E), W2 = I - Phi(E) and the largest |E| entry (scal[mat][scal_slot]).
 // ------------------------------------------------------------------------------------
-constexpr int kLeaf = 128;
-constexpr int kLeafLd = kLeaf + 1;
-constexpr int kLeafLds = (2 * kLeaf * kLeafLd + kLeaf) * 4;
-
-__global__ __launch_bounds__(256) void k_chol_leaf(WsArr gram, WsArr t, WsArr w, int r, int blk, int* info, int info_slot) {
-  extern __shared__ __align__(16) char lds[];
-  float* A = reinterpret_cast<float*>(lds);
-  float* Wl = A + kLeaf * kLeafLd;
-  float* dd = Wl + kLeaf * kLeafLd;
-  const int z = blockIdx.x, tid = threadIdx.x;
-  const int o = blk * kLeaf;
-  const int nb = (r - o) < kLeaf ? (r - o) : kLeaf;
-  const int64_t off = (int64_t)o * r + o;
-  const float* g = gram.base + (int64_t)z * gram.stride + off;
-  float* tg = t.base + (int64_t)z * t.stride + off;
-  float* wg = w.base + (int64_t)z * w.stride + off;
-
-  for (int idx = tid; idx < nb * nb; idx += 256) {
-    int i = idx / nb, j = idx % nb;
-    A[i * kLeafLd + j] = g[(int64_t)i * r + j];
-    Wl[i * kLeafLd + j] = 0.f;
+__global__ __launch_bounds__(256) void k_corr(int r, WsArr part, int splits, WsArr t2, WsArr w2, float* scal, int scal_slot) {
+  const int z = blockIdx.y;
+  const float* src = part.base + (int64_t)z * part.stride;
+  float* tp = t2.base + (int64_t)z * t2.stride;
+  float* wp = w2.base + (int64_t)z * w2.stride;
+  const int64_t count = (int64_t)r * r;
+  float emax = 0.f;
+  for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < count; idx += (int64_t)gridDim.x * 256) {
+    const int i = (int)(idx / r), j = (int)(idx % r);
+    float g = 0.f;
+    for (int sp = 0; sp < splits; ++sp) g += src[(int64_t)sp * count + idx];
+    const float e = (i == j) ? g - 1.f : g;
+    emax = fmaxf(emax, fabsf(e));
+    float phi = 0.f;
+    if (j > i) phi = e;
+    else if (j == i) phi = 0.5f * e;
+    const float id = (i == j) ? 1.f : 0.f;
+    tp[idx] = id + phi;
+    wp[idx] = id - phi;
   }
+  __shared__ float red[256];
+  red[threadIdx.x] = emax;
   __syncthreads();
-
-  // right-looking Cholesky on the upper triangle; row k is scaled at the end
-  const int ty = tid >> 4, tx = tid & 15;
-  for (int k = 0; k < nb; ++k) {
-    float piv = A[k * kLeafLd + k];
-    if (!(piv > 0.f) || piv > 3.0e38f) {
-      if (tid == 0) atomicCAS(&info[z * kInfoPerMat + info_slot], 0, o + k + 1);
-      piv = 1.f;
-    }
-    const float ip = 1.f / piv;
-    if (tid == 0) dd[k] = piv;
-    for (int i = k + 1 + ty; i < nb; i += 16) {
-      const float aki = A[k * kLeafLd + i] * ip;
-      for (int j = k + 1 + tx; j < nb; j += 16)
-        if (j >= i) A[i * kLeafLd + j] -= aki * A[k * kLeafLd + j];
-    }
+  for (int w = 128; w > 0; w >>= 1) {
+    if ((int)threadIdx.x < w) red[threadIdx.x] = fmaxf(red[threadIdx.x], red[threadIdx.x + w]);
     __syncthreads();
   }
-  for (int idx = tid; idx < nb * nb; idx += 256) {
-    int i = idx / nb, j = idx % nb;
-    float v = 0.f;
-    if (j > i) v = A[i * kLeafLd + j] * rsqrtf(dd[i]);
-    else if (j == i) v = sqrtf(dd[i]);
-    A[i * kLeafLd + j] = v;
-    tg[(int64_t)i * r + j] = v;
-  }
-  __syncthreads();
-
-  // inverse of the upper-triangular T: 32 x 32 diagonal blocks by back substitution
-  // (one thread per column), then block rows outward by products.
-  if (tid < nb) {
-    const int c = tid, b0 = (c / 32) * 32;
-    Wl[c * kLeafLd + c] = 1.f / A[c * kLeafLd + c];
-    for (int i = c - 1; i >= b0; --i) {
-      float s = 0.f;
-      for (int k = i + 1; k <= c; ++k) s += A[i * kLeafLd + k] * Wl[k * kLeafLd + c];
-      Wl[i * kLeafLd + c] = -s / A[i * kLeafLd + i];
-    }
-  }
-  __syncthreads();
-  const int nbl = (nb + 31) / 32;
-  for (int d = 1; d < nbl; ++d) {
-    // S(I, J) = sum_{K = I+1..J} T(I, K) W(K, J), J = I + d; kept in the (unused) lower part of A
-    for (int idx = tid; idx < (nbl - d) * 1024; idx += 256) {
-      int I = idx / 1024, e = idx % 1024, i = I * 32 + e / 32, j = (I + d) * 32 + e % 32;
-      float s = 0.f;
-      if (j < nb) {
-        int kmax = (I + d + 1) * 32;
-        if (kmax > nb) kmax = nb;
-        for (int k = (I + 1) * 32; k < kmax; ++k) s += A[i * kLeafLd + k] * Wl[k * kLeafLd + j];
-        A[j * kLeafLd + i] = s;
-      }
-    }
-    __syncthreads();
-    for (int idx = tid; idx < (nbl - d) * 1024; idx += 256) {
-      int I = idx / 1024, e = idx % 1024, i = I * 32 + e / 32, j = (I + d) * 32 + e % 32;
-      if (j < nb) {
-        float s = 0.f;
-        for (int k = i; k < (I + 1) * 32; ++k) s += Wl[i * kLeafLd + k] * A[j * kLeafLd + k];
-        Wl[i * kLeafLd + j] = -s;
-      }
-    }
-    __syncthreads();
-  }
-  for (int idx = tid; idx < nb * nb; idx += 256) {
-    int i = idx / nb, j = idx % nb;
-    wg[(int64_t)i * r + j] = j >= i ? Wl[i * kLeafLd + j] : 0.f;
+  if (threadIdx.x == 0) {
+    float v = red[0];
+    if (!(v == v)) v = 3.0e38f;       // NaN -> huge
+    atomicMax(reinterpret_cast<int*>(scal + z * kScalPerMat + scal_slot), __float_as_int(v));
   }
 }
 
@@ -342,10 +299,6 @@ __global__ __launch_bounds__(256) void k_fill_i32(int* p, int64_t count, int v) 
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) p[i] = v;
 }
 
-OD_DEV float pow2_scale_for_rms(float ms) {
-  if (ms > 0.f && ms < 3.0e38f) return ldexpf(1.f, -ilogbf(sqrtf(ms)));
-  return 1.f;
-}
 
 __global__ __launch_bounds__(256) void k_scale_from_trace(int n, int r, WsArr gram, float* scal) {
   const int z = blockIdx.x, tid = threadIdx.x;
@@ -513,7 +466,7 @@ hipError_t launch_fill_int(int* p, int64_t count, int value, hipStream_t st) {
   return hipSuccess;
 }
 
-static hipError_t fill_f32(float* p, int64_t count, float v, hipStream_t st) {
+hipError_t launch_fill_f32(float* p, int64_t count, float v, hipStream_t st) {
   if (count <= 0) return hipSuccess;
   int blocks = (int)((count + 255) / 256);
   if (blocks > 2048) blocks = 2048;
@@ -523,8 +476,8 @@ static hipError_t fill_f32(float* p, int64_t count, float v, hipStream_t st) {
 }
 
 hipError_t launch_stats(const ClassDims& d, const MatPtrs& ptrs, float* scal, hipStream_t st) {
-  if (d.g_bf16) hipLaunchKernelGGL(k_stats<SrcBF16>, dim3(d.nb), dim3(256), 0, st, d, ptrs, scal);
-  else hipLaunchKernelGGL(k_stats<SrcF32>, dim3(d.nb), dim3(256), 0, st, d, ptrs, scal);
+  if (d.g_bf16) hipLaunchKernelGGL(k_stats<SrcBF16>, dim3(kStatRows, d.nb), dim3(256), 0, st, d, ptrs, scal);
+  else hipLaunchKernelGGL(k_stats<SrcF32>, dim3(kStatRows, d.nb), dim3(256), 0, st, d, ptrs, scal);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -629,20 +582,34 @@ static hipError_t sgemm(int nb, const SgemmArgs& g, bool a_kc, int exact, hipStr
   return a_kc ? sgemm_t<NumBF<2>, KC>(nb, g, st) : sgemm_t<NumBF<2>, KS>(nb, g, st);
 }
 
-hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp, int* info, int info_slot, int exact,
-                          hipStream_t st) {
-  hipError_t e = allow_lds(k_chol_leaf, kLeafLds);
+hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr part, int splits, WsArr t, WsArr w, WsArr tmp, int* info,
+                          int info_slot, float* scal, int trace_rows, hipStream_t st) {
+  hipError_t e = allow_lds(k_chol256, kCholLds);
   if (e != hipSuccess) return e;
   const int nblk = (r + kLeaf - 1) / kLeaf;
-  if (nblk > 1) {
-    // lower block triangles of T and W are never written below; clear them once
-    for (int z = 0; z < nb; ++z) {
-      if ((e = fill_f32(t.base + (int64_t)z * t.stride, (int64_t)r * r, 0.f, st)) != hipSuccess) return e;
-      if ((e = fill_f32(w.base + (int64_t)z * w.stride, (int64_t)r * r, 0.f, st)) != hipSuccess) return e;
-    }
+  CholArgs ca = {};
+  ca.t = t; ca.w = w; ca.r = r; ca.info = info; ca.info_slot = info_slot; ca.scal = scal; ca.trace_rows = trace_rows;
+  if (nblk == 1) {
+    // the whole matrix in one workgroup, straight from the split partial sums
+    ca.src = part; ca.splits = splits; ca.split_stride = (int64_t)r * r; ca.blk = 0;
+    hipLaunchKernelGGL(k_chol256, dim3(nb), dim3(256), kCholLds, st, ca);
+    OD_CHECK_LAUNCH();
+    return hipSuccess;
   }
+  // blocked right-looking factorisation on the reduced Gram matrix
+  if ((e = launch_reduce(nb, part, splits, (int64_t)r * r, gram, st)) != hipSuccess) return e;
+  if (scal != nullptr && (e = launch_scale_from_trace(nb, trace_rows, r, gram, scal, st)) != hipSuccess) return e;
+  ca.scal = nullptr;
+  ca.src = gram; ca.splits = 1; ca.split_stride = 0;
+  // lower block triangles of T and W are never written below; clear them once
+  for (int z = 0; z < nb; ++z) {
+    if ((e = launch_fill_f32(t.base + (int64_t)z * t.stride, (int64_t)r * r, 0.f, st)) != hipSuccess) return e;
+    if ((e = launch_fill_f32(w.base + (int64_t)z * w.stride, (int64_t)r * r, 0.f, st)) != hipSuccess) return e;
+  }
+  const int exact = 1;
   for (int p = 0; p < nblk; ++p) {
-    hipLaunchKernelGGL(k_chol_leaf, dim3(nb), dim3(256), kLeafLds, st, gram, t, w, r, p, info, info_slot);
+    ca.blk = p;
+    hipLaunchKernelGGL(k_chol256, dim3(nb), dim3(256), kCholLds, st, ca);
     OD_CHECK_LAUNCH();
     if (p + 1 == nblk) break;
     const int o = p * kLeaf, o1 = (p + 1) * kLeaf, rest = r - o1;
@@ -672,6 +639,15 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp
     g.Mc = kLeaf; g.Nc = kLeaf; g.Kc = kLeaf; g.alpha = -1.f; g.beta = 0.f;
     if ((e = sgemm(nb, g, true, exact, st)) != hipSuccess) return e;
   }
+  return hipSuccess;
+}
+
+hipError_t launch_corr(int nb, int r, WsArr part, int splits, WsArr t2, WsArr w2, float* scal, int scal_slot, hipStream_t st) {
+  int64_t count = (int64_t)r * r;
+  int blocks = (int)((count + 255) / 256);
+  if (blocks > 1024) blocks = 1024;
+  hipLaunchKernelGGL(k_corr, dim3(blocks, nb), dim3(256), 0, st, r, part, splits, t2, w2, scal, scal_slot);
+  OD_CHECK_LAUNCH();
   return hipSuccess;
 }
 
