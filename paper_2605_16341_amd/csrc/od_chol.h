@@ -36,6 +36,12 @@ constexpr int kCTileF = kCT * kCPitch; // floats per LDS tile
 // LDS: Wrow[8] | Wt | Dtmp | panel[8]
 constexpr int kCholLds = (kCNT + 1 + 1 + kCNT) * kCTileF * 4;
 
+#ifdef OD_CHOL_TIMING
+#define OD_TICK(slot) do { if (lane == 0) a.dbg[(z * 4 + wave) * 64 + (slot)] = wall_clock64(); } while (0)
+#else
+#define OD_TICK(slot) do { } while (0)
+#endif
+
 struct CholArgs {
   WsArr src;           // Gram block source: `splits` partial sums, `split_stride` elements apart
   int splits;
@@ -47,6 +53,9 @@ struct CholArgs {
   int info_slot;
   float* scal;         // if non-null: scal[z * kScalPerMat + 1] = power-of-two scale from the trace
   int trace_rows;      // rows of the tall matrix whose Gram this is (for the scale)
+#ifdef OD_CHOL_TIMING
+  long long* dbg;
+#endif
 };
 
 // tile enumeration: I descending, K ascending; tile t belongs to wave t % 4, slot t / 4
@@ -57,6 +66,16 @@ __device__ __constant__ const unsigned char kTileK[kCTiles] = {7, 6, 7, 5, 6, 7,
 
 OD_DEV float lane_bcast(float v, int lane) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
+// 1/sqrt(d) and 1/d to fp32 accuracy: hardware estimate (1 ulp) plus one Newton step.
+OD_DEV float fast_rsqrt(float d) {
+  float y = __builtin_amdgcn_rsqf(d);
+  return y * fmaf(-0.5f * d * y, y, 1.5f);
+}
+OD_DEV float fast_rcp(float d) {
+  float y = __builtin_amdgcn_rcpf(d);
+  return y * fmaf(-d, y, 2.f);
 }
 
 OD_DEV void wave_lds_fence() {
@@ -141,22 +160,45 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
   float* wg = a.w.base + (int64_t)z * a.w.stride + off;
   const int col = lane & 31, half = lane >> 5;
 
+  OD_TICK(0);
   // ---- load the owned tiles (sum of the split partials); identity outside the block
   f32x16 acc[kCSlots];
   float tr = 0.f;
+#pragma unroll
+  for (int s = 0; s < kCSlots; ++s)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) acc[s][v] = 0.f;
+  // split by split, so that the loads of one split are all in flight together.  The Gram
+  // matrix is symmetric: the 4 consecutive rows a lane needs of column gj are read as 4
+  // consecutive columns of row gj (one 16-byte load).
+  for (int sp = 0; sp < a.splits; ++sp) {
+    const float* sp_src = src + (int64_t)sp * a.split_stride;
+#pragma unroll
+    for (int s = 0; s < kCSlots; ++s) {
+      const int t = s * 4 + wave, I = kTileI[t], K = kTileK[t];
+      if (I < nt && K < nt) {
+        const int gj = K * kCT + col;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int gi = I * kCT + 8 * q + 4 * half;
+          if (gi < nb && gj < nb) {
+            f32x4 v4 = *reinterpret_cast<const f32x4*>(sp_src + (int64_t)gj * r + gi);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[s][4 * q + e] += v4[e];
+          }
+        }
+      }
+    }
+  }
 #pragma unroll
   for (int s = 0; s < kCSlots; ++s) {
     const int t = s * 4 + wave, I = kTileI[t], K = kTileK[t];
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
       const int gi = I * kCT + acc_row(v, lane), gj = K * kCT + col;
-      float x = (gi == gj) ? 1.f : 0.f;
-      if (I < nt && K < nt && gi < nb && gj < nb) {
-        x = 0.f;
-        for (int sp = 0; sp < a.splits; ++sp) x += src[(int64_t)sp * a.split_stride + (int64_t)gi * r + gj];
-        if (gi == gj) tr += x;
-      }
-      acc[s][v] = x;
+      const bool inside = I < nt && K < nt && gi < nb && gj < nb;
+      if (!inside) acc[s][v] = (gi == gj) ? 1.f : 0.f;
+      else if (gi == gj) tr += acc[s][v];
     }
   }
   if (a.scal != nullptr) {       // trace -> power-of-two scale of the tall matrix (uniform branch)
@@ -176,8 +218,10 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
   }
   __syncthreads();
 
+  OD_TICK(1);
   // ================================ factorisation ================================
   for (int J = 0; J < nt; ++J) {
+    OD_TICK(2 + 4 * J);
     // ---- (a) diagonal tile: Cholesky and inverse inside the owning wave
     {
       // tile (J, J) is entry t = sum_{i=J+1..7} (8 - i) = (7 - J)(8 - J) / 2 of the enumeration
@@ -207,12 +251,13 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
             if (bad == 0) bad = J * kCT + k + 1;
             dk = 1.f;
           }
-          const float sq = sqrtf(dk);
-          const float rs = 1.f / sq;
+          const float rs = fast_rsqrt(dk);
+          const float sq = dk * rs;
           const float tk = rowv[k] * (rs * rs);
           rowv[k] = (col == k) ? sq : rowv[k] * rs;
 #pragma unroll
           for (int j = k + 1; j < 32; ++j) rowv[j] = fmaf(-tk, lane_bcast(rowv[j], k), rowv[j]);
+          __builtin_amdgcn_sched_barrier(0);     // keep the broadcasts of one column together
         }
 #pragma unroll
         for (int j = 0; j < 32; ++j)
@@ -227,8 +272,9 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
           float s = 0.f;
 #pragma unroll
           for (int k = 0; k < i; ++k) s = fmaf(lane_bcast(rowv[k], i), m[k], s);
-          const float dinv = 1.f / lane_bcast(rowv[i], i);
+          const float dinv = fast_rcp(lane_bcast(rowv[i], i));
           m[i] = ((col == i) ? 1.f : -s) * dinv;
+          __builtin_amdgcn_sched_barrier(0);
         }
         const int nv = (nb - J * kCT) < kCT ? (nb - J * kCT) : kCT;   // valid rows / cols of this tile
         if (half == 0) {
@@ -259,7 +305,9 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
         }
       }
     }
+    OD_TICK(3 + 4 * J);
     __syncthreads();
+    OD_TICK(4 + 4 * J);
     // ---- (b) row panel: T(J, K) = W_JJ^T S(J, K), K > J
 #pragma unroll
     for (int s = 0; s < kCSlots; ++s) {
@@ -286,6 +334,7 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
       }
     }
     __syncthreads();
+    OD_TICK(5 + 4 * J);
     // ---- (c) trailing update: S(I, K) -= T(J, I)^T T(J, K), J < I <= K
 #pragma unroll
     for (int s = 0; s < kCSlots; ++s) {
@@ -304,7 +353,9 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
     // the next (a) writes Wt / Dtmp only after every wave is done with this step's (b);
     // the next (b) writes `panel` only after the barrier that follows (a).
   }
+  OD_TICK(40);
   __syncthreads();     // all of T is in global memory and visible to this workgroup
+  OD_TICK(41);
 
   // ================================ inverse ================================
   // Wave w builds block columns K = w, 7 - w (in that order the long and the short one pair up).
@@ -359,6 +410,7 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
       }
     }
   }
+  OD_TICK(42);
   // lower block triangle of T and W inside this block: zero (tiles strictly below the diagonal)
   for (int idx = tid; idx < nb * nb; idx += 256) {
     const int i = idx / nb, j = idx % nb;
