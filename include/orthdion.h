@@ -118,8 +118,9 @@ int orthdion_step(orthdion_handle h, void* const* X, const void* const* G, float
 
 /* Waits for `stream`, then copies the per-matrix breakdown words of the last step to
  * info_host[nmat]: 0 = fine; k > 0 = the left factor B Q lost rank (or went non-finite) at
- * column k; k < 0 = the same for the right factor (QR) or a zero column (ColNorm) at
- * column -k. */
+ * column k (k = r when the loss only shows as a failed orthogonality check after the first
+ * CholeskyQR pass); k < 0 = the same for the right factor (QR) or a zero column (ColNorm)
+ * at column -k. */
 int orthdion_get_info(orthdion_handle h, int32_t* info_host, void* stream);
 
 /* Debug / test hook: byte offsets inside the workspace of what the last step left for

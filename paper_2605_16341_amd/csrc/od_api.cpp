@@ -226,7 +226,7 @@ static int cholqr2(const Batch& b, char* ws, int rows, size_t off_a0, size_t off
                             rows, st));
   OD_TRY(od::launch_apply(nb, rows, r, a0, w, a1, nullptr, exact, st));
   OD_TRY(od::launch_gram(nb, rows, r, a1, part, splits, exact, st));
-  OD_TRY(od::launch_corr(nb, r, part, splits, t2, w, scal, 2 + info_slot, st));
+  OD_TRY(od::launch_corr(nb, r, part, splits, t2, w, scal, 2 + info_slot, info, info_slot, st));
   OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, exact, st));
   return ORTHDION_OK;
 }

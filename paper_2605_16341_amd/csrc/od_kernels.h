@@ -71,9 +71,10 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr part, int splits, WsA
                           int info_slot, float* scal, int trace_rows, hipStream_t st);
 
 // First-order second pass: from the Gram partials of a nearly orthonormal matrix writes
-// T2 = I + Phi(E), W2 = I - Phi(E) and max |E| into scal[mat][scal_slot] (must be zeroed).
+// T2 = I + Phi(E), W2 = I - Phi(E) and max |E| into scal[mat][scal_slot] (must be zeroed);
+// a deviation above 0.1 (or NaN) is a breakdown: info[mat][info_slot] = r unless already set.
 hipError_t launch_corr(int nb, int r, WsArr part, int splits, WsArr t2, WsArr w2, float* scal, int scal_slot,
-                       hipStream_t st);
+                       int* info, int info_slot, hipStream_t st);
 
 // scal[mat][1] = power-of-two scale for R from trace(gram) = ||R||_F^2 (rows n, cols r)
 hipError_t launch_scale_from_trace(int nb, int n, int r, WsArr gram, float* scal, hipStream_t st);

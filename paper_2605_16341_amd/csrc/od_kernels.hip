@@ -248,6 +248,7 @@ __global__ __launch_bounds__(T::THREADS) void k_sgemm(SgemmArgs g) {
 
 
 constexpr int kLeaf = kCholMax;   // diagonal block of the blocked factorisation
+constexpr float kMaxGramDeviation = 0.1f;   // largest |E| entry the first-order second pass accepts
 
 // ------------------------------------------------------------------------------------
 // Second CholeskyQR pass as a first-order correction.  After the first pass the Gram matrix
@@ -255,7 +256,8 @@ constexpr int kLeaf = kCholMax;   // diagonal block of the blocked factorisation
 // triangle + half the diagonal, and the inverse factor I - Phi(E) + O(E^2).  Writes
 // T2 = I + Phi(E), W2 = I - Phi(E) and the largest |E| entry (scal[mat][scal_slot]).
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_corr(int r, WsArr part, int splits, WsArr t2, WsArr w2, float* scal, int scal_slot) {
+__global__ __launch_bounds__(256) void k_corr(int r, WsArr part, int splits, WsArr t2, WsArr w2, float* scal, int scal_slot,
+                                              int* info, int info_slot) {
   const int z = blockIdx.y;
   const float* src = part.base + (int64_t)z * part.stride;
   float* tp = t2.base + (int64_t)z * t2.stride;
@@ -286,6 +288,9 @@ __global__ __launch_bounds__(256) void k_corr(int r, WsArr part, int splits, WsA
     float v = red[0];
     if (!(v == v)) v = 3.0e38f;       // NaN -> huge
     atomicMax(reinterpret_cast<int*>(scal + z * kScalPerMat + scal_slot), __float_as_int(v));
+    // The first pass left the factor far from orthonormal: the input had (numerically) less
+    // than full column rank, which the Cholesky pivots alone do not always show.
+    if (v > kMaxGramDeviation) atomicCAS(&info[z * kInfoPerMat + info_slot], 0, r);
   }
 }
 
@@ -642,11 +647,12 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr part, int splits, WsA
   return hipSuccess;
 }
 
-hipError_t launch_corr(int nb, int r, WsArr part, int splits, WsArr t2, WsArr w2, float* scal, int scal_slot, hipStream_t st) {
+hipError_t launch_corr(int nb, int r, WsArr part, int splits, WsArr t2, WsArr w2, float* scal, int scal_slot, int* info,
+                       int info_slot, hipStream_t st) {
   int64_t count = (int64_t)r * r;
   int blocks = (int)((count + 255) / 256);
   if (blocks > 1024) blocks = 1024;
-  hipLaunchKernelGGL(k_corr, dim3(blocks, nb), dim3(256), 0, st, r, part, splits, t2, w2, scal, scal_slot);
+  hipLaunchKernelGGL(k_corr, dim3(blocks, nb), dim3(256), 0, st, r, part, splits, t2, w2, scal, scal_slot, info, info_slot);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }

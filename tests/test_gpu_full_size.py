@@ -1,0 +1,131 @@
+"""Parity at the benchmark's full sizes, in the launch configuration bench.py times.
+
+C2 (4096 x 4096, r = 256, 20 steps) is compared with the oracle in full.  For the larger
+matrix sets (C3, C4, C5 shapes; r up to 2048) a full fp64 oracle step would take minutes per
+matrix, so one matrix per distinct shape is stepped once and checked through
+  * properties that identify the result at any size: P^T P = I, Q^T Q = I (unit columns for
+    ColNorm), P (T2 T1) = B Q_prev with an upper-triangular positive-diagonal factor (the
+    thin QR factor is unique), Q (T2 T1) = R;
+  * outputs the oracle computes one by one: sampled rows of B Q_prev, sampled rows of
+    R = B^T P, and sampled rows of the new momentum and parameter from the oracle's own
+    error-feedback and update functions.
+Inputs are generated on the device with the bench's recipe and copied back only in samples.
+"""
+import numpy as np
+import pytest
+
+from gpu_harness import bf16_ulp_distance, to_host
+from oracle.orthdion_oracle import OrthDionOracle, bf16_bits_to_f64, f64_to_bf16_bits, rel_fro
+from paper_2605_16341_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+
+
+def test_config2_4096_rank256_twenty_steps_free_running():
+    from test_gpu_parity import _free_running
+    res = _free_running(synth.WORKLOADS["C2"], check_every=5)
+    assert res["D"] < 5e-3 and res["M"] < 1e-3
+
+
+def _sampled_check(w, index, variant, sample=48, seed=0):
+    import torch
+    import bench
+    dev = torch.device("cuda:0")
+    m, n = w.shapes[index]
+    r = w.r
+    one = synth.Workload(w.name, (w.shapes[index],), r=r, x_dtype=w.x_dtype, mu=w.mu, lr=w.lr)
+    x, mom, q = bench.device_state(torch, one, 0, dev)
+    g0, g1 = bench.device_gradients(torch, one, 0, 2, dev)
+    opt = binding.OrthDion([(m, n)], r, x_dtype="bf16", variant=variant, mu=w.mu, lr=w.lr)
+    opt.step([x], [g0], [mom], [q])            # a first step so that M is not zero
+    torch.cuda.synchronize()
+    assert opt.info() == [0]
+    x0, m0, q0 = x.clone(), mom.clone(), q.clone()
+    opt.step([x], [g1], [mom], [q])
+    torch.cuda.synchronize()
+    assert opt.info() == [0]
+    f = opt.debug_factors(0)
+    P, R = f["P"].double(), f["R"].double()
+    Qn = q.double()
+    eye = torch.eye(r, device=dev, dtype=torch.float64)
+    B = m0.double() + g1.double()
+
+    # --- properties
+    assert float((P.T @ P - eye).abs().max()) < 2e-5
+    t_p = f["T_P2"].double() @ f["T_P1"].double()
+    assert bool((torch.diagonal(t_p) > 0).all())
+    assert float(torch.tril(t_p, -1).abs().max()) <= 1e-6 * float(t_p.abs().max())
+    praw = B @ q0.double()
+    assert float(torch.linalg.norm(P @ t_p - praw) / torch.linalg.norm(praw)) < 2e-2
+    if variant == "qr":
+        assert float((Qn.T @ Qn - eye).abs().max()) < 2e-5
+        t_q = f["T_Q2"].double() @ f["T_Q1"].double()
+        assert bool((torch.diagonal(t_q) > 0).all())
+        assert float(torch.linalg.norm(Qn @ t_q - R) / torch.linalg.norm(R)) < 1e-4
+    else:
+        assert float(((Qn * Qn).sum(0) - 1.0).abs().max()) < 1e-5
+        assert float(torch.linalg.norm(Qn * torch.linalg.norm(R, dim=0)[None, :] - R) / torch.linalg.norm(R)) < 1e-5
+    assert float(torch.linalg.norm(R - B.T @ P) / torch.linalg.norm(R)) < 2e-2
+
+    # --- sampled outputs against the oracle's functions
+    rng = np.random.default_rng(seed)
+    rows = np.sort(rng.choice(m, size=min(sample, m), replace=False))
+    cols = np.sort(rng.choice(n, size=min(sample, n), replace=False))
+    rows_t = torch.from_numpy(rows).to(dev)
+    cols_t = torch.from_numpy(cols).to(dev)
+    orc = OrthDionOracle(mu=w.mu, lr=w.lr, variant=variant, x_bf16=True)
+    b_rows = orc.buffer(m0[rows_t].cpu().numpy().astype(np.float64), bf16_bits_to_f64(to_host(g1[rows_t].contiguous(), torch)))
+    q0_np, p_np, r_np, q_np = (t.cpu().numpy().astype(np.float64) for t in (q0, f["P"], f["R"], q))
+    # P_raw rows: (B Q_prev)[rows] must equal (P T_P)[rows]
+    want = orc.project(b_rows, q0_np)
+    got = p_np[rows] @ t_p.cpu().numpy()
+    assert rel_fro(got, want) < 2e-2
+    # R rows: R[cols] = B[:, cols]^T P
+    b_cols = (m0[:, cols_t].double() + g1[:, cols_t].double()).cpu().numpy()
+    assert rel_fro(r_np[cols], orc.back_project(b_cols, p_np)) < 2e-2
+    # new momentum and parameter rows from the GPU's own factors
+    m_want = orc.error_feedback(b_rows, p_np[rows], r_np)
+    assert rel_fro(mom[rows_t].cpu().numpy(), m_want) < 1e-3
+    x_prev = bf16_bits_to_f64(to_host(x0[rows_t].contiguous(), torch))
+    x_want = f64_to_bf16_bits(orc.update(x_prev, p_np[rows], q_np))
+    dist = bf16_ulp_distance(to_host(x[rows_t].contiguous(), torch), x_want)
+    assert np.mean(dist != 0) < 0.02 and np.mean(dist > 1) < 1e-3
+
+
+@pytest.mark.parametrize("name,index", [("C3", 0), ("C3", 1), ("C3", 2), ("C3", 3)])
+def test_config3_shapes_rank512(name, index):
+    _sampled_check(synth.WORKLOADS[name], index, "qr")
+
+
+@pytest.mark.parametrize("index", [0, 2, 4])
+def test_config4_shapes_rank1024(index):
+    _sampled_check(synth.WORKLOADS["C4"], index, "qr")
+
+
+@pytest.mark.parametrize("r,variant", [(16, "qr"), (64, "colnorm"), (256, "qr"), (1024, "colnorm"), (2048, "qr")])
+def test_config5_rank_sweep(r, variant):
+    _sampled_check(synth.WORKLOADS[f"C5-r{r}"], 0, variant)
+
+
+def test_whole_config3_set_runs_in_one_call():
+    """All 96 matrices (4 shape classes, 3 launch batches each) in one handle: every matrix
+    gets orthonormal factors and a finite state."""
+    import torch
+    import bench
+    dev = torch.device("cuda:0")
+    w = synth.WORKLOADS["C3"]
+    X, M, Q, G = [], [], [], []
+    for i in range(len(w.shapes)):
+        x, mom, q = bench.device_state(torch, w, i, dev)
+        X.append(x); M.append(mom); Q.append(q)
+        G.append(bench.device_gradients(torch, w, i, 1, dev)[0])
+    opt = binding.OrthDion(w.shapes, w.r, x_dtype="bf16", mu=w.mu, lr=w.lr)
+    opt.step(X, G, M, Q)
+    torch.cuda.synchronize()
+    assert opt.info() == [0] * len(w.shapes)
+    eye = torch.eye(w.r, device=dev)
+    for i in range(0, len(w.shapes), 7):
+        assert float((Q[i].T @ Q[i] - eye).abs().max()) < 1e-4
+        assert bool(torch.isfinite(M[i]).all())
+        p = opt.debug_factors(i)["P"]
+        assert float((p.T @ p - eye).abs().max()) < 1e-4
