@@ -154,10 +154,8 @@ extern "C" int orthdion_create(orthdion_handle* out, const orthdion_matdesc* mat
     const int64_t gt = ((r + 127) / 128) * ((r + 127) / 128);
     b.splits_gram_p = pick_splits(gt, d.nb, m, 256);
     b.splits_gram_q = pick_splits(gt, d.nb, n, 256);
-    if (b.splits_gram_p > 4 && r <= 256) b.splits_gram_p = 4;   // one workgroup sums them in the factorisation
-    if (b.splits_gram_q > 4 && r <= 256) b.splits_gram_q = 4;
-    if (b.splits_gram_p > 16) b.splits_gram_p = 16;
-    if (b.splits_gram_q > 16) b.splits_gram_q = 16;
+    if (b.splits_gram_p > 32) b.splits_gram_p = 32;
+    if (b.splits_gram_q > 32) b.splits_gram_q = 32;
     b.slabs = (int)((n + 511) / 512);
     if (b.slabs > 64) b.slabs = 64;
     int64_t part = (int64_t)b.splits_proj * m * r;

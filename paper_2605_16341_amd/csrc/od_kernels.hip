@@ -594,18 +594,18 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr part, int splits, WsA
   const int nblk = (r + kLeaf - 1) / kLeaf;
   CholArgs ca = {};
   ca.t = t; ca.w = w; ca.r = r; ca.info = info; ca.info_slot = info_slot; ca.scal = scal; ca.trace_rows = trace_rows;
+  // ordered reduction of the split partial sums on many workgroups first: the factorisation
+  // below runs on one workgroup per matrix and should not spend its time summing
+  if ((e = launch_reduce(nb, part, splits, (int64_t)r * r, gram, st)) != hipSuccess) return e;
+  ca.src = gram; ca.splits = 1; ca.split_stride = 0;
   if (nblk == 1) {
-    // the whole matrix in one workgroup, straight from the split partial sums
-    ca.src = part; ca.splits = splits; ca.split_stride = (int64_t)r * r; ca.blk = 0;
+    ca.blk = 0;
     hipLaunchKernelGGL(k_chol256, dim3(nb), dim3(256), kCholLds, st, ca);
     OD_CHECK_LAUNCH();
     return hipSuccess;
   }
-  // blocked right-looking factorisation on the reduced Gram matrix
-  if ((e = launch_reduce(nb, part, splits, (int64_t)r * r, gram, st)) != hipSuccess) return e;
   if (scal != nullptr && (e = launch_scale_from_trace(nb, trace_rows, r, gram, scal, st)) != hipSuccess) return e;
   ca.scal = nullptr;
-  ca.src = gram; ca.splits = 1; ca.split_stride = 0;
   // lower block triangles of T and W are never written below; clear them once
   for (int z = 0; z < nb; ++z) {
     if ((e = launch_fill_f32(t.base + (int64_t)z * t.stride, (int64_t)r * r, 0.f, st)) != hipSuccess) return e;
