@@ -15,6 +15,7 @@ namespace {
 using od::ClassDims;
 using od::MatPtrs;
 using od::WsArr;
+using od::HalfArr;
 
 constexpr size_t kAlign = 256;
 
@@ -27,6 +28,7 @@ struct Batch {
   // per-matrix float arrays (offset of matrix 0 in bytes, stride in elements)
   size_t off_pa, off_pb, off_ra, off_rb, off_part, off_gram, off_tp1, off_tp2, off_tq1, off_tq2, off_w,
       off_tmp, off_colsq;
+  size_t off_ph, off_pht, off_rh, off_qh, off_qht;   // pre-scaled fp16 copies of the factors (uint16 arrays)
   int64_t st_p, st_r, st_part, st_rr, st_colsq;
   int splits_proj, splits_back, splits_gram_p, splits_gram_q, slabs;
   int slot_base;                     // first row of this batch in the scal / info tables
@@ -174,6 +176,9 @@ extern "C" int orthdion_create(orthdion_handle* out, const orthdion_matdesc* mat
     b.off_tp1 = take(b.st_rr); b.off_tp2 = take(b.st_rr); b.off_tq1 = take(b.st_rr); b.off_tq2 = take(b.st_rr);
     b.off_w = take(b.st_rr); b.off_tmp = take(b.st_rr);
     b.off_colsq = take(b.st_colsq);
+    auto take_h = [&](int64_t stride) { size_t o = off; off = align_up(off + (size_t)stride * d.nb * sizeof(uint16_t)); return o; };
+    b.off_ph = take_h(b.st_p); b.off_pht = take_h(b.st_p);
+    b.off_rh = take_h(b.st_r); b.off_qh = take_h(b.st_r); b.off_qht = take_h(b.st_r);
   }
   h->ws_bytes = off;
   *out = h;
@@ -211,7 +216,7 @@ extern "C" int orthdion_set_variant(orthdion_handle h, orthdion_variant v) {
 // orth() of `a0` (rows x r) by CholeskyQR2: pass 1 (Gram, Cholesky, a1 = a0 W1) and a
 // first-order second pass (Gram of a1, W2 = I - Phi(E), result = a1 W2 -> a0 | callers' Q).
 static int cholqr2(const Batch& b, char* ws, int rows, size_t off_a0, size_t off_a1, int64_t st_a, int splits,
-                   size_t off_t1, size_t off_t2, int info_slot, const MatPtrs* q_out, bool want_r_scale, float* scal,
+                   size_t off_t1, size_t off_t2, int info_slot, const MatPtrs* q_out, HalfArr hn, HalfArr ht, float* scal,
                    int* info, int exact, hipStream_t st) {
   const int nb = b.d.nb, r = b.d.r;
   WsArr a0{reinterpret_cast<float*>(ws + off_a0), st_a}, a1{reinterpret_cast<float*>(ws + off_a1), st_a};
@@ -220,12 +225,12 @@ static int cholqr2(const Batch& b, char* ws, int rows, size_t off_a0, size_t off
   WsArr w{reinterpret_cast<float*>(ws + b.off_w), b.st_rr}, tmp{reinterpret_cast<float*>(ws + b.off_tmp), b.st_rr};
   WsArr t1{reinterpret_cast<float*>(ws + off_t1), b.st_rr}, t2{reinterpret_cast<float*>(ws + off_t2), b.st_rr};
   OD_TRY(od::launch_gram(nb, rows, r, a0, part, splits, 1, st));
-  OD_TRY(od::launch_cholinv(nb, r, gram, part, splits, t1, w, tmp, info, info_slot, want_r_scale ? scal : nullptr,
-                            rows, st));
-  OD_TRY(od::launch_apply(nb, rows, r, a0, w, a1, nullptr, exact, st));
+  OD_TRY(od::launch_cholinv(nb, r, gram, part, splits, t1, w, tmp, info, info_slot, nullptr, rows, st));
+  const HalfArr none{nullptr, 0};
+  OD_TRY(od::launch_apply(nb, rows, r, a0, w, a1, nullptr, none, none, exact, st));
   OD_TRY(od::launch_gram(nb, rows, r, a1, part, splits, exact, st));
   OD_TRY(od::launch_corr(nb, r, part, splits, t2, w, scal, 2 + info_slot, info, info_slot, st));
-  OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, exact, st));
+  OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, hn, ht, exact, st));
   return ORTHDION_OK;
 }
 
@@ -282,42 +287,49 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     WsArr ra{reinterpret_cast<float*>(ws + b.off_ra), b.st_r};
     WsArr part{reinterpret_cast<float*>(ws + b.off_part), b.st_part};
     WsArr colsq{reinterpret_cast<float*>(ws + b.off_colsq), b.st_colsq};
+    const bool fast = prec == od::PREC_F16;
+    const HalfArr none{nullptr, 0};
+    HalfArr ph{reinterpret_cast<uint16_t*>(ws + b.off_ph), b.st_p}, pht{reinterpret_cast<uint16_t*>(ws + b.off_pht), b.st_p};
+    HalfArr rh{reinterpret_cast<uint16_t*>(ws + b.off_rh), b.st_r}, qh{reinterpret_cast<uint16_t*>(ws + b.off_qh), b.st_r};
+    HalfArr qht{reinterpret_cast<uint16_t*>(ws + b.off_qht), b.st_r};
 
     // Alg. 1 lines 1-2: P_raw = (M + G) Q, then P = orth(P_raw)
     OD_PHASE_BEGIN(ORTHDION_PHASE_STATS);
-    if (prec == od::PREC_F16) OD_TRY(od::launch_stats(d, ptrs, scal, st));
+    if (fast) OD_TRY(od::launch_stats(d, ptrs, scal, qht, st));
     OD_PHASE_END(ORTHDION_PHASE_STATS);
     OD_PHASE_BEGIN(ORTHDION_PHASE_PROJ);
-    OD_TRY(od::launch_proj(d, ptrs, prec, scal, part, b.splits_proj, st));
+    OD_TRY(od::launch_proj(d, ptrs, prec, scal, part, b.splits_proj, qht, st));
     OD_PHASE_END(ORTHDION_PHASE_PROJ);
     OD_PHASE_BEGIN(ORTHDION_PHASE_PROJ_REDUCE);
     OD_TRY(od::launch_reduce(d.nb, part, b.splits_proj, (int64_t)d.m * d.r, pa, st));
     OD_PHASE_END(ORTHDION_PHASE_PROJ_REDUCE);
     OD_PHASE_BEGIN(ORTHDION_PHASE_ORTH_LEFT);
     int rc = cholqr2(b, ws, d.m, b.off_pa, b.off_pb, b.st_p, b.splits_gram_p, b.off_tp1, b.off_tp2, 0, nullptr,
-                     false, scal, info, exact, st);
+                     fast ? ph : none, fast ? pht : none, scal, info, exact, st);
     if (rc != ORTHDION_OK) return rc;
     OD_PHASE_END(ORTHDION_PHASE_ORTH_LEFT);
     // line 3: R = (M + G)^T P
     OD_PHASE_BEGIN(ORTHDION_PHASE_BACK);
-    OD_TRY(od::launch_back(d, ptrs, prec, scal, pa, part, b.splits_back, st));
+    OD_TRY(od::launch_back(d, ptrs, prec, scal, pa, part, b.splits_back, pht, st));
     OD_PHASE_END(ORTHDION_PHASE_BACK);
     OD_PHASE_BEGIN(ORTHDION_PHASE_BACK_REDUCE);
-    OD_TRY(od::launch_reduce(d.nb, part, b.splits_back, (int64_t)d.n * d.r, ra, st));
+    if (fast) OD_TRY(od::launch_reduce_r(d, part, b.splits_back, ra, rh, scal, st));
+    else OD_TRY(od::launch_reduce(d.nb, part, b.splits_back, (int64_t)d.n * d.r, ra, st));
     OD_PHASE_END(ORTHDION_PHASE_BACK_REDUCE);
     // line 4: Q = orth(R) or ColNorm(R), written to the callers' Q (Q_prev is no longer needed)
     OD_PHASE_BEGIN(ORTHDION_PHASE_ORTH_RIGHT);
     if (h->cfg.variant == ORTHDION_QR) {
-      rc = cholqr2(b, ws, d.n, b.off_ra, b.off_rb, b.st_r, b.splits_gram_q, b.off_tq1, b.off_tq2, 1, &ptrs, true,
-                   scal, info, exact, st);
+      rc = cholqr2(b, ws, d.n, b.off_ra, b.off_rb, b.st_r, b.splits_gram_q, b.off_tq1, b.off_tq2, 1, &ptrs,
+                   fast ? qh : none, none, scal, info, exact, st);
       if (rc != ORTHDION_OK) return rc;
     } else {
-      OD_TRY(od::launch_colnorm(d.nb, d.n, d.r, ra, ptrs, part, b.slabs, colsq, scal, info, st));
+      OD_TRY(od::launch_colnorm(d.nb, d.n, d.r, ra, ptrs, part, b.slabs, colsq, scal, info, fast ? qh : none, st));
     }
     OD_PHASE_END(ORTHDION_PHASE_ORTH_RIGHT);
     // lines 5-7: parameter update and error feedback in one pass
     OD_PHASE_BEGIN(ORTHDION_PHASE_EFX);
-    OD_TRY(od::launch_efx(d, ptrs, prec, scal, pa, ra, a_coef, b_coef, h->cfg.lr, st));
+    if (fast) OD_TRY(od::launch_efx_h(d, ptrs, scal, ph, rh, qh, a_coef, b_coef, h->cfg.lr, st));
+    else OD_TRY(od::launch_efx(d, ptrs, prec, scal, pa, ra, a_coef, b_coef, h->cfg.lr, st));
     OD_PHASE_END(ORTHDION_PHASE_EFX);
   }
   if (h->prof_on && h->prof_steps < h->prof_max_steps) h->prof_steps++;

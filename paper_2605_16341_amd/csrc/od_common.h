@@ -117,6 +117,7 @@ struct NumBF {
 // columns is either wholly inside or wholly outside.
 // ---------------------------------------------------------------------------------
 struct SrcF32 {
+  static constexpr bool PACKED = false;
   const float* p;
   int R, C;
   int64_t ld;
@@ -149,6 +150,7 @@ struct SrcF32 {
 };
 
 struct SrcBF16 {
+  static constexpr bool PACKED = false;
   const uint16_t* p;
   int R, C;
   int64_t ld;
@@ -172,10 +174,42 @@ struct SrcBF16 {
   }
 };
 
+// Operand words already in matrix-core format (fp16, scaled by their producer): a loader
+// copies them to LDS untouched.  Only read along k (load8).
+struct SrcH16 {
+  static constexpr bool PACKED = true;
+  const uint16_t* p;
+  int R, C;
+  int64_t ld;
+  typedef u32x4 Raw8;
+  typedef u32x2 Raw4;
+  OD_DEV Raw8 load8(int r, int c) const {
+    if (r < R && c < C) return *reinterpret_cast<const u32x4*>(p + (int64_t)r * ld + c);
+    return u32x4{0u, 0u, 0u, 0u};
+  }
+  OD_DEV Raw4 load4(int, int) const { return u32x2{0u, 0u}; }
+  OD_DEV static void unpack8(const Raw8&, float* x) {
+#pragma unroll
+    for (int i = 0; i < 8; ++i) x[i] = 0.f;
+  }
+  OD_DEV static void unpack4(const Raw4&, float* x) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) x[i] = 0.f;
+  }
+};
+
+OD_DEV uint32_t pack_f16_sat(float lo, float hi) {
+  f16x2 p;
+  p[0] = (_Float16)__builtin_amdgcn_fmed3f(lo, -65504.f, 65504.f);
+  p[1] = (_Float16)__builtin_amdgcn_fmed3f(hi, -65504.f, 65504.f);
+  return __builtin_bit_cast(uint32_t, p);
+}
+
 // The buffer B = M + G of the method, formed on the fly from the fp32 momentum and the
 // gradient in its storage type; never written to memory.
 template <class GSrc>
 struct SrcSum {
+  static constexpr bool PACKED = false;
   SrcF32 m;
   GSrc g;
   struct Raw8 { SrcF32::Raw8 a; typename GSrc::Raw8 b; };

@@ -46,13 +46,18 @@ struct LoadKC {
     for (int p = 0; p < PER; ++p) {
       int item = tid + p * THREADS;
       if (ITEMS % THREADS == 0 || item < ITEMS) {
-        float x[8];
-        Src::unpack8(raw[p], x);
-        u32x4 w[Num::PARTS];
-        Num::pack(x, scale, w);
         char* dst = lds + (item / KG) * PITCH + (item % KG) * 16;
+        if constexpr (Src::PACKED) {
+          static_assert(Num::PARTS == 1, "packed operands have one part");
+          *reinterpret_cast<u32x4*>(dst) = raw[p];
+        } else {
+          float x[8];
+          Src::unpack8(raw[p], x);
+          u32x4 w[Num::PARTS];
+          Num::pack(x, scale, w);
 #pragma unroll
-        for (int s = 0; s < Num::PARTS; ++s) *reinterpret_cast<u32x4*>(dst + s * plane) = w[s];
+          for (int s = 0; s < Num::PARTS; ++s) *reinterpret_cast<u32x4*>(dst + s * plane) = w[s];
+        }
       }
     }
   }

@@ -33,6 +33,12 @@ struct WsArr {
   int64_t stride;      // elements between consecutive matrices
 };
 
+// A workspace array of pre-scaled fp16 operand words, one slice per matrix.
+struct HalfArr {
+  uint16_t* base;
+  int64_t stride;      // elements between consecutive matrices
+};
+
 // scal layout per matrix (floats): [1] scale of R, [2] / [3] largest deviation of the
 // first-pass Gram matrix of the left / right factor from identity, [8..39] sampled row sums
 // of squares of B
@@ -42,23 +48,28 @@ constexpr int kScalSample = 8;
 // breakdown column (1-based, 0 = none), [2] zero-column flag of ColNorm, [3] spare
 constexpr int kInfoPerMat = 4;
 
-hipError_t launch_stats(const ClassDims& d, const MatPtrs& ptrs, float* scal, hipStream_t st);
+// sampled sums of squares of B (for its fp16 scale) and Q as pre-scaled fp16, transposed [r][n]
+hipError_t launch_stats(const ClassDims& d, const MatPtrs& ptrs, float* scal, HalfArr qht, hipStream_t st);
 
 // P_raw partials: part[split][m][r] = (M+G)[:, k-range] * Q[k-range, :]
 hipError_t launch_proj(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal,
-                       WsArr part, int splits, hipStream_t st);
+                       WsArr part, int splits, HalfArr qht, hipStream_t st);
 // R partials: part[split][n][r] = (M+G)[k-range, :]^T * P[k-range, :]
 hipError_t launch_back(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal,
-                       WsArr p, WsArr part, int splits, hipStream_t st);
+                       WsArr p, WsArr part, int splits, HalfArr pht, hipStream_t st);
 // out[i] = sum_s part[s * count + i], i < count, per matrix
 hipError_t launch_reduce(int nb, WsArr part, int splits, int64_t count, WsArr out, hipStream_t st);
+// the same for R (n x r), also written as pre-scaled fp16 [n][r]
+hipError_t launch_reduce_r(const ClassDims& d, WsArr part, int splits, WsArr out, HalfArr rh, const float* scal, hipStream_t st);
 
 // Gram partials: part[split][r][r] = A[k-range, :]^T A[k-range, :], A is rows x r (ld r)
 hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits, int exact, hipStream_t st);
 // out = A * W, A rows x r, W r x r upper triangular (both ld r); the result goes to the
 // callers' Q buffers when q_ptrs is given, else to the workspace array `out`.
-hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs,
-                        int exact, hipStream_t st);
+// With hn.base / ht.base non-null the result is also stored as fp16 scaled by 2^10, in
+// natural [rows][r] and transposed [r][rows] layout.
+hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs, HalfArr hn,
+                        HalfArr ht, int exact, hipStream_t st);
 
 // Cholesky factor and its inverse of the SPD r x r matrix sum_s part[s] (ld r): = T^T T,
 // W = T^-1, both upper triangular with zeros below the diagonal.  For r <= 256 one workgroup
@@ -82,11 +93,15 @@ hipError_t launch_scale_from_trace(int nb, int n, int r, WsArr gram, float* scal
 // ColNorm: Q[:, c] = R[:, c] / ||R[:, c]||; also writes the scale of R.  `part` holds
 // slabs x r partial sums per matrix, `colsq` r reciprocal lengths per matrix.
 hipError_t launch_colnorm(int nb, int n, int r, WsArr rr, const MatPtrs& ptrs, WsArr part, int slabs, WsArr colsq,
-                          float* scal, int* info, hipStream_t st);
+                          float* scal, int* info, HalfArr qh, hipStream_t st);
 
 // M_new = a (M+G) - b P R^T ;  X_new = X - lr P Q^T   (one pass over M, G, X)
 hipError_t launch_efx(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p,
                       WsArr rr, float a_coef, float b_coef, float lr, hipStream_t st);
+
+// the same pass from the pre-scaled fp16 factors (fast precision)
+hipError_t launch_efx_h(const ClassDims& d, const MatPtrs& ptrs, const float* scal, HalfArr ph, HalfArr rh, HalfArr qh,
+                        float a_coef, float b_coef, float lr, hipStream_t st);
 
 hipError_t launch_fill_int(int* p, int64_t count, int value, hipStream_t st);
 hipError_t launch_fill_f32(float* p, int64_t count, float value, hipStream_t st);

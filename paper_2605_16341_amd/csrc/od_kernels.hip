@@ -73,19 +73,57 @@ __global__ __launch_bounds__(256) void k_stats(ClassDims d, MatPtrs ptrs, float*
   if (tid == 0) scal[z * kScalPerMat + kScalSample + blockIdx.x] = red[0];
 }
 
+// Q (n x r fp32, the caller's state) -> pre-scaled fp16, transposed to [r][n]
+__global__ __launch_bounds__(256) void k_prep_q(ClassDims d, MatPtrs ptrs, HalfArr qht) {
+  __shared__ uint16_t tile[64][66];
+  const int z = blockIdx.z, tid = threadIdx.x;
+  const int k0 = blockIdx.x * 64, c0 = blockIdx.y * 64;       // k over n, c over r
+  const float* q = ptrs.Q[z];
+  uint16_t* out = qht.base + (int64_t)z * qht.stride;
+  for (int idx = tid; idx < 64 * 16; idx += 256) {            // 64 rows (k) x 16 groups of 4 columns
+    const int kk = idx / 16, cg = (idx % 16) * 4;
+    f32x4 v = {0.f, 0.f, 0.f, 0.f};
+    if (k0 + kk < d.n && c0 + cg < d.r) v = *reinterpret_cast<const f32x4*>(q + (int64_t)(k0 + kk) * d.r + c0 + cg);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      _Float16 x = (_Float16)__builtin_amdgcn_fmed3f(v[e] * kUnitScale, -65504.f, 65504.f);
+      tile[cg + e][kk] = __builtin_bit_cast(uint16_t, x);
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < 64 * 16; idx += 256) {            // 64 rows (c) x 16 groups of 4 k
+    const int cc = idx / 16, kg = (idx % 16) * 4;
+    if (c0 + cc < d.r && k0 + kg < d.n) {
+      u32x2 h = {(uint32_t)tile[cc][kg] | ((uint32_t)tile[cc][kg + 1] << 16),
+                 (uint32_t)tile[cc][kg + 2] | ((uint32_t)tile[cc][kg + 3] << 16)};
+      *reinterpret_cast<u32x2*>(out + (int64_t)(c0 + cc) * d.n + k0 + kg) = h;
+    }
+  }
+}
+
 // scale of B from the sampled row sums of squares (same value in every consumer)
 OD_DEV float b_scale(const ClassDims& d, const float* scal, int z) {
   const int nrows = d.m < kStatRows ? d.m : kStatRows;
-  float tot = 0.f;
-  for (int i = 0; i < nrows; ++i) tot += scal[z * kScalPerMat + kScalSample + i];
+  // all kStatRows slots are written (zero beyond nrows): fixed-size vector loads, no loop-carried latency
+  const f32x4* p = reinterpret_cast<const f32x4*>(scal + z * kScalPerMat + kScalSample);
+  f32x4 acc4 = p[0];
+#pragma unroll
+  for (int i = 1; i < kStatRows / 4; ++i) acc4 += p[i];
+  const float tot = (acc4[0] + acc4[1]) + (acc4[2] + acc4[3]);
   return pow2_scale_for_rms(tot / ((float)nrows * (float)d.n));
 }
 
 // ------------------------------------------------------------------------------------
 // P_raw = B Q  (split over n)                                       Alg. 1 line 2
 // ------------------------------------------------------------------------------------
+// scale of R = B^T P in fp16: P is orthonormal, so rms(R) <= rms(B) sqrt(m / r); a power of
+// two derived from the scale of B alone, known before R exists
+OD_DEV float r_scale(const ClassDims& d, const float* scal, int z) {
+  return ldexpf(b_scale(d, scal, z), -(ilogbf((float)d.m / (float)d.r) / 2));
+}
+
 template <class T, class Num, class GSrc>
-__global__ __launch_bounds__(T::THREADS) void k_proj(ClassDims d, MatPtrs ptrs, const float* scal, WsArr part, int splits) {
+__global__ __launch_bounds__(T::THREADS, 2) void k_proj(ClassDims d, MatPtrs ptrs, const float* scal, WsArr part, int splits, HalfArr qht) {
   extern __shared__ __align__(16) char lds[];
   const int tiles_n = (d.r + T::NT - 1) / T::NT;
   const int tn = blockIdx.x % tiles_n, tm = blockIdx.x / tiles_n;
@@ -98,7 +136,13 @@ __global__ __launch_bounds__(T::THREADS) void k_proj(ClassDims d, MatPtrs ptrs, 
   const float sb = Num::F16 ? kUnitScale : 1.f;
   f32x16 acc[T::FM][T::FN];
   zero_acc<T>(acc);
-  gemm_mainloop<T, Num, KC, SrcSum<GSrc>, KS, SrcF32>(a, b, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc);
+  if constexpr (Num::F16) {
+    // Q as pre-scaled fp16, transposed to [r][n] so that k is contiguous
+    SrcH16 bh{qht.base + (int64_t)z * qht.stride, d.r, d.n, d.n};
+    gemm_mainloop<T, Num, KC, SrcSum<GSrc>, KC, SrcH16>(a, bh, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc);
+  } else {
+    gemm_mainloop<T, Num, KC, SrcSum<GSrc>, KS, SrcF32>(a, b, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc);
+  }
   const float inv = 1.f / (sa * sb);
   float* out = part.base + (int64_t)z * part.stride + (int64_t)split * d.m * d.r;
   for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
@@ -110,7 +154,7 @@ __global__ __launch_bounds__(T::THREADS) void k_proj(ClassDims d, MatPtrs ptrs, 
 // R = B^T P  (split over m)                                         Alg. 1 line 3
 // ------------------------------------------------------------------------------------
 template <class T, class Num, class GSrc>
-__global__ __launch_bounds__(T::THREADS) void k_back(ClassDims d, MatPtrs ptrs, const float* scal, WsArr p, WsArr part, int splits) {
+__global__ __launch_bounds__(T::THREADS, 2) void k_back(ClassDims d, MatPtrs ptrs, const float* scal, WsArr p, WsArr part, int splits, HalfArr pht) {
   extern __shared__ __align__(16) char lds[];
   const int tiles_n = (d.r + T::NT - 1) / T::NT;
   const int tn = blockIdx.x % tiles_n, tm = blockIdx.x / tiles_n;
@@ -123,7 +167,12 @@ __global__ __launch_bounds__(T::THREADS) void k_back(ClassDims d, MatPtrs ptrs, 
   const float sb = Num::F16 ? kUnitScale : 1.f;
   f32x16 acc[T::FM][T::FN];
   zero_acc<T>(acc);
-  gemm_mainloop<T, Num, KS, SrcSum<GSrc>, KS, SrcF32>(a, b, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc);
+  if constexpr (Num::F16) {
+    SrcH16 bh{pht.base + (int64_t)z * pht.stride, d.r, d.m, d.m};      // P^T as fp16, [r][m]
+    gemm_mainloop<T, Num, KS, SrcSum<GSrc>, KC, SrcH16>(a, bh, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc);
+  } else {
+    gemm_mainloop<T, Num, KS, SrcSum<GSrc>, KS, SrcF32>(a, b, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc);
+  }
   const float inv = 1.f / (sa * sb);
   float* out = part.base + (int64_t)z * part.stride + (int64_t)split * d.n * d.r;
   for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
@@ -146,6 +195,23 @@ __global__ __launch_bounds__(256) void k_reduce(WsArr part, int splits, int64_t 
       s += v;
     }
     reinterpret_cast<f32x4*>(dst)[i] = s;
+  }
+}
+
+// the same for R, which is also stored as pre-scaled fp16 for the error-feedback kernel
+__global__ __launch_bounds__(256) void k_reduce_r(ClassDims d, WsArr part, int splits, WsArr out, HalfArr rh, const float* scal) {
+  const int z = blockIdx.y;
+  const float* src = part.base + (int64_t)z * part.stride;
+  float* dst = out.base + (int64_t)z * out.stride;
+  uint16_t* dh = rh.base + (int64_t)z * rh.stride;
+  const int64_t count = (int64_t)d.n * d.r, n4 = count / 4;
+  const float sr = r_scale(d, scal, z);
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
+    f32x4 s = reinterpret_cast<const f32x4*>(src)[i];
+    for (int k = 1; k < splits; ++k) s += reinterpret_cast<const f32x4*>(src + (int64_t)k * count)[i];
+    reinterpret_cast<f32x4*>(dst)[i] = s;
+    u32x2 h = {pack_f16_sat(s[0] * sr, s[1] * sr), pack_f16_sat(s[2] * sr, s[3] * sr)};
+    reinterpret_cast<u32x2*>(dh)[i] = h;
   }
 }
 
@@ -175,7 +241,8 @@ __global__ __launch_bounds__(T::THREADS) void k_gram(int rows, int r, WsArr a, W
 // with the explicit inverse factor)
 // ------------------------------------------------------------------------------------
 template <class T, class Num>
-__global__ __launch_bounds__(T::THREADS) void k_apply(int rows, int r, WsArr a, WsArr w, WsArr out, MatPtrs ptrs, int to_q) {
+__global__ __launch_bounds__(T::THREADS) void k_apply(int rows, int r, WsArr a, WsArr w, WsArr out, MatPtrs ptrs, int to_q,
+                                                      HalfArr hn, HalfArr ht) {
   extern __shared__ __align__(16) char lds[];
   const int tiles_n = (r + T::NT - 1) / T::NT;
   const int tn = blockIdx.x % tiles_n, tm = blockIdx.x / tiles_n;
@@ -191,6 +258,36 @@ __global__ __launch_bounds__(T::THREADS) void k_apply(int rows, int r, WsArr a, 
   for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
     if (row < rows && col < r) dst[(int64_t)row * r + col] = v;
   });
+  // pre-scaled fp16 copies of the (orthonormal) result for the large contractions
+  if (hn.base != nullptr) {
+    uint16_t* h = hn.base + (int64_t)z * hn.stride;
+    for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
+      if (row < rows && col < r) {
+        _Float16 x = (_Float16)__builtin_amdgcn_fmed3f(v * kUnitScale, -65504.f, 65504.f);
+        h[(int64_t)row * r + col] = __builtin_bit_cast(uint16_t, x);
+      }
+    });
+  }
+  if (ht.base != nullptr) {     // transposed [r][rows]: 4 consecutive rows of one column per store
+    uint16_t* h = ht.base + (int64_t)z * ht.stride;
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int wm = wave / T::WN, wn = wave % T::WN;
+#pragma unroll
+    for (int fm = 0; fm < T::FM; ++fm)
+#pragma unroll
+      for (int fn = 0; fn < T::FN; ++fn) {
+        const int col = tn * T::NT + wn * T::WTN + fn * 32 + (lane & 31);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int row = tm * T::MT + wm * T::WTM + fm * 32 + 8 * q + 4 * (lane >> 5);
+          if (col < r && row < rows) {
+            u32x2 hv = {pack_f16_sat(acc[fm][fn][4 * q] * kUnitScale, acc[fm][fn][4 * q + 1] * kUnitScale),
+                        pack_f16_sat(acc[fm][fn][4 * q + 2] * kUnitScale, acc[fm][fn][4 * q + 3] * kUnitScale)};
+            *reinterpret_cast<u32x2*>(h + (int64_t)col * rows + row) = hv;
+          }
+        }
+      }
+  }
 }
 
 // ------------------------------------------------------------------------------------
@@ -359,7 +456,7 @@ __global__ __launch_bounds__(256) void k_colsq_final(int n, int r, WsArr part, i
   if (tid == 0) scal[z * kScalPerMat + 1] = pow2_scale_for_rms(red[0] / ((float)n * (float)r));
 }
 // stage 3: Q = R * diag(1/len)
-__global__ __launch_bounds__(256) void k_colnorm_apply(int n, int r, WsArr rr, WsArr colsq, MatPtrs ptrs) {
+__global__ __launch_bounds__(256) void k_colnorm_apply(int n, int r, WsArr rr, WsArr colsq, MatPtrs ptrs, HalfArr qh) {
   const int z = blockIdx.y;
   const float* src = rr.base + (int64_t)z * rr.stride;
   const float* inv = colsq.base + (int64_t)z * colsq.stride;
@@ -369,7 +466,12 @@ __global__ __launch_bounds__(256) void k_colnorm_apply(int n, int r, WsArr rr, W
     int c = (int)((i * 4) % r);
     f32x4 v = reinterpret_cast<const f32x4*>(src)[i];
     f32x4 s = *reinterpret_cast<const f32x4*>(inv + c);
-    reinterpret_cast<f32x4*>(q)[i] = v * s;
+    f32x4 o = v * s;
+    reinterpret_cast<f32x4*>(q)[i] = o;
+    if (qh.base != nullptr) {
+      u32x2 h = {pack_f16_sat(o[0] * kUnitScale, o[1] * kUnitScale), pack_f16_sat(o[2] * kUnitScale, o[3] * kUnitScale)};
+      reinterpret_cast<u32x2*>(qh.base + (int64_t)z * qh.stride)[i] = h;
+    }
   }
 }
 
@@ -447,6 +549,129 @@ __global__ __launch_bounds__(T::THREADS) void k_efx(ClassDims d, MatPtrs ptrs, c
   }
 }
 
+// ------------------------------------------------------------------------------------
+// The same pass with every factor already in matrix-core format (fp16, pre-scaled by its
+// producer): P [m][r], R [n][r], Q [n][r].  Tile: 128 rows i x 128 columns j, 8 waves.
+//   * one K loop feeds both products from one P tile;
+//   * wave w owns rows 32 (w % 4) .. +31 and the column half 64 (w / 4) .. +63; the R and Q
+//     tiles are laid out in LDS so that lane c of the wave's two accumulator blocks holds
+//     columns 2c and 2c + 1: every lane moves pairs, every wave instruction moves whole
+//     256-byte (M) or 128-byte (G, X) row segments;
+//   * all M, G, X values of the lane are requested together after the K loop; two workgroups
+//     per CU (16 waves) overlap one's HBM traffic with the other's products.  (Requests
+//     issued before the K loop would not overlap it: the loop's waits for its own operand
+//     loads complete in issue order, behind the older requests.)
+// ------------------------------------------------------------------------------------
+template <bool XBF, bool GBF>
+__global__ __launch_bounds__(512, 2) void k_efx_h(ClassDims d, MatPtrs ptrs, const float* scal, HalfArr ph, HalfArr rh,
+                                               HalfArr qh, float a_coef, float b_coef, float lr) {
+  constexpr int TJ = 128, TI = 128, KT = 32, PITCH = KT * 2 + 16, PLANE = 128 * PITCH, BUF = 3 * PLANE;
+  extern __shared__ __align__(16) char lds[];
+  const int tiles_i = (d.m + TI - 1) / TI;
+  const int ti = blockIdx.x % tiles_i, tj = blockIdx.x / tiles_i;
+  const int z = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wi = wave & 3, wj = wave >> 2, c = lane & 31;
+  SrcH16 sp{ph.base + (int64_t)z * ph.stride, d.m, d.r, d.r};
+  SrcH16 sr{rh.base + (int64_t)z * rh.stride, d.n, d.r, d.r};
+  SrcH16 sq{qh.base + (int64_t)z * qh.stride, d.n, d.r, d.r};
+  // loader: thread t brings 16 bytes (8 k) of row t / 4 of each tile
+  const int lrow = tid >> 2, lkg = tid & 3;
+  const int jj = lrow & 63;
+  const int prow = (lrow & 64) + (jj & 1) * 32 + (jj >> 1);     // LDS position of column lrow of the R / Q tiles
+  const int off_p = lrow * PITCH + lkg * 16, off_rq = prow * PITCH + lkg * 16;
+
+  f32x16 acc_r[2], acc_q[2];
+#pragma unroll
+  for (int f = 0; f < 2; ++f)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { acc_r[f][v] = 0.f; acc_q[f][v] = 0.f; }
+
+  u32x4 nr = sr.load8(tj * TJ + lrow, lkg * 8), nq = sq.load8(tj * TJ + lrow, lkg * 8), np = sp.load8(ti * TI + lrow, lkg * 8);
+  *reinterpret_cast<u32x4*>(lds + off_rq) = nr;
+  *reinterpret_cast<u32x4*>(lds + PLANE + off_rq) = nq;
+  *reinterpret_cast<u32x4*>(lds + 2 * PLANE + off_p) = np;
+  __syncthreads();
+  int buf = 0;
+  for (int k = 0; k < d.r; k += KT) {
+    const bool more = (k + KT) < d.r;
+    if (more) {
+      nr = sr.load8(tj * TJ + lrow, k + KT + lkg * 8);
+      nq = sq.load8(tj * TJ + lrow, k + KT + lkg * 8);
+      np = sp.load8(ti * TI + lrow, k + KT + lkg * 8);
+    }
+    const char* base = lds + buf * BUF;
+#pragma unroll
+    for (int kk = 0; kk < KT / 16; ++kk) {
+      const int off = c * PITCH + (2 * kk + (lane >> 5)) * 16;
+      const u32x4 fp = *reinterpret_cast<const u32x4*>(base + 2 * PLANE + (wi * 32) * PITCH + off);
+#pragma unroll
+      for (int f = 0; f < 2; ++f) {
+        const u32x4 fr = *reinterpret_cast<const u32x4*>(base + (wj * 64 + f * 32) * PITCH + off);
+        const u32x4 fq = *reinterpret_cast<const u32x4*>(base + PLANE + (wj * 64 + f * 32) * PITCH + off);
+        acc_r[f] = mfma_32x32x16<true>(fp, fr, acc_r[f]);
+        acc_q[f] = mfma_32x32x16<true>(fp, fq, acc_q[f]);
+      }
+    }
+    if (more) {
+      char* nb = lds + (buf ^ 1) * BUF;
+      *reinterpret_cast<u32x4*>(nb + off_rq) = nr;
+      *reinterpret_cast<u32x4*>(nb + PLANE + off_rq) = nq;
+      *reinterpret_cast<u32x4*>(nb + 2 * PLANE + off_p) = np;
+    }
+    __syncthreads();
+    buf ^= 1;
+  }
+
+  // ---- epilogue: this lane's 16 rows x 2 adjacent columns, in two halves of 8 rows; within a
+  // half every load is issued before the first store
+  const int j0 = tj * TJ + 64 * wj + 2 * c;
+  float* __restrict__ Mz = ptrs.M[z];
+  const char* __restrict__ Gz = reinterpret_cast<const char*>(ptrs.G[z]);
+  char* __restrict__ Xz = reinterpret_cast<char*>(ptrs.X[z]);
+  constexpr int GE = GBF ? 2 : 4, XE = XBF ? 2 : 4;
+  const float s_r = r_scale(d, scal, z);
+  const float cr = b_coef / (s_r * kUnitScale), cq = lr / (kUnitScale * kUnitScale);
+#pragma unroll
+  for (int hv = 0; hv < 2; ++hv) {
+    f32x2 mv[8], gv[8], xv[8];
+    uint32_t gp[8], xp[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int v = 8 * hv + u;
+      const int i = ti * TI + 32 * wi + acc_row(v, lane);
+      mv[u] = f32x2{0.f, 0.f};
+      gp[u] = 0u; xp[u] = 0u; gv[u] = f32x2{0.f, 0.f}; xv[u] = f32x2{0.f, 0.f};
+      if (i < d.m && j0 < d.n) {
+        mv[u] = *reinterpret_cast<const f32x2*>(Mz + (int64_t)i * d.ldm + j0);
+        if constexpr (GBF) gp[u] = *reinterpret_cast<const uint32_t*>(Gz + ((int64_t)i * d.ldg + j0) * GE);
+        else gv[u] = *reinterpret_cast<const f32x2*>(Gz + ((int64_t)i * d.ldg + j0) * GE);
+        if constexpr (XBF) xp[u] = *reinterpret_cast<const uint32_t*>(Xz + ((int64_t)i * d.ldx + j0) * XE);
+        else xv[u] = *reinterpret_cast<const f32x2*>(Xz + ((int64_t)i * d.ldx + j0) * XE);
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int v = 8 * hv + u;
+      const int i = ti * TI + 32 * wi + acc_row(v, lane);
+      if (i < d.m && j0 < d.n) {
+        f32x2 g = gv[u], x = xv[u];
+        if constexpr (GBF) g = f32x2{bf16_lo(gp[u]), bf16_hi(gp[u])};
+        if constexpr (XBF) x = f32x2{bf16_lo(xp[u]), bf16_hi(xp[u])};
+        f32x2 mo, xo;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          mo[e] = a_coef * (mv[u][e] + g[e]) - cr * acc_r[e][v];
+          xo[e] = x[e] - cq * acc_q[e][v];
+        }
+        *reinterpret_cast<f32x2*>(Mz + (int64_t)i * d.ldm + j0) = mo;
+        if constexpr (XBF) *reinterpret_cast<uint32_t*>(Xz + ((int64_t)i * d.ldx + j0) * XE) = pack_bf16_rne(xo[0], xo[1]);
+        else *reinterpret_cast<f32x2*>(Xz + ((int64_t)i * d.ldx + j0) * XE) = xo;
+      }
+    }
+  }
+}
+
 // ====================================================================================
 // launchers
 // ====================================================================================
@@ -480,53 +705,55 @@ hipError_t launch_fill_f32(float* p, int64_t count, float v, hipStream_t st) {
   return hipSuccess;
 }
 
-hipError_t launch_stats(const ClassDims& d, const MatPtrs& ptrs, float* scal, hipStream_t st) {
+hipError_t launch_stats(const ClassDims& d, const MatPtrs& ptrs, float* scal, HalfArr qht, hipStream_t st) {
   if (d.g_bf16) hipLaunchKernelGGL(k_stats<SrcBF16>, dim3(kStatRows, d.nb), dim3(256), 0, st, d, ptrs, scal);
   else hipLaunchKernelGGL(k_stats<SrcF32>, dim3(kStatRows, d.nb), dim3(256), 0, st, d, ptrs, scal);
+  OD_CHECK_LAUNCH();
+  hipLaunchKernelGGL(k_prep_q, dim3((d.n + 63) / 64, (d.r + 63) / 64, d.nb), dim3(256), 0, st, d, ptrs, qht);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
 
 template <class T, class Num, class GSrc>
-static hipError_t proj_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr part, int splits, hipStream_t st) {
+static hipError_t proj_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr part, int splits, HalfArr qht, hipStream_t st) {
   constexpr int lds = T::template lds_bytes<Num>();
   hipError_t e = allow_lds(k_proj<T, Num, GSrc>, lds);
   if (e != hipSuccess) return e;
   dim3 grid(((d.m + T::MT - 1) / T::MT) * ((d.r + T::NT - 1) / T::NT), splits, d.nb);
-  hipLaunchKernelGGL((k_proj<T, Num, GSrc>), grid, dim3(T::THREADS), lds, st, d, ptrs, scal, part, splits);
+  hipLaunchKernelGGL((k_proj<T, Num, GSrc>), grid, dim3(T::THREADS), lds, st, d, ptrs, scal, part, splits, qht);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
 template <class GSrc>
-static hipError_t proj_g(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr part, int splits, hipStream_t st) {
-  if (prec == PREC_BF3) return proj_t<TileSquare, NumBF<3>, GSrc>(d, ptrs, scal, part, splits, st);
-  if (d.r <= 64) return proj_t<TileNarrow, NumF16, GSrc>(d, ptrs, scal, part, splits, st);
-  if (d.r <= 128) return proj_t<TileSquare, NumF16, GSrc>(d, ptrs, scal, part, splits, st);
-  return proj_t<TileWide, NumF16, GSrc>(d, ptrs, scal, part, splits, st);
+static hipError_t proj_g(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr part, int splits, HalfArr qht, hipStream_t st) {
+  if (prec == PREC_BF3) return proj_t<TileSquare, NumBF<3>, GSrc>(d, ptrs, scal, part, splits, qht, st);
+  if (d.r <= 64) return proj_t<TileNarrow, NumF16, GSrc>(d, ptrs, scal, part, splits, qht, st);
+  if (d.r <= 128) return proj_t<TileSquare, NumF16, GSrc>(d, ptrs, scal, part, splits, qht, st);
+  return proj_t<TileWide, NumF16, GSrc>(d, ptrs, scal, part, splits, qht, st);
 }
-hipError_t launch_proj(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr part, int splits, hipStream_t st) {
-  return d.g_bf16 ? proj_g<SrcBF16>(d, ptrs, prec, scal, part, splits, st) : proj_g<SrcF32>(d, ptrs, prec, scal, part, splits, st);
+hipError_t launch_proj(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr part, int splits, HalfArr qht, hipStream_t st) {
+  return d.g_bf16 ? proj_g<SrcBF16>(d, ptrs, prec, scal, part, splits, qht, st) : proj_g<SrcF32>(d, ptrs, prec, scal, part, splits, qht, st);
 }
 
 template <class T, class Num, class GSrc>
-static hipError_t back_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr p, WsArr part, int splits, hipStream_t st) {
+static hipError_t back_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr p, WsArr part, int splits, HalfArr pht, hipStream_t st) {
   constexpr int lds = T::template lds_bytes<Num>();
   hipError_t e = allow_lds(k_back<T, Num, GSrc>, lds);
   if (e != hipSuccess) return e;
   dim3 grid(((d.n + T::MT - 1) / T::MT) * ((d.r + T::NT - 1) / T::NT), splits, d.nb);
-  hipLaunchKernelGGL((k_back<T, Num, GSrc>), grid, dim3(T::THREADS), lds, st, d, ptrs, scal, p, part, splits);
+  hipLaunchKernelGGL((k_back<T, Num, GSrc>), grid, dim3(T::THREADS), lds, st, d, ptrs, scal, p, part, splits, pht);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
 template <class GSrc>
-static hipError_t back_g(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p, WsArr part, int splits, hipStream_t st) {
-  if (prec == PREC_BF3) return back_t<TileSquare, NumBF<3>, GSrc>(d, ptrs, scal, p, part, splits, st);
-  if (d.r <= 64) return back_t<TileNarrow, NumF16, GSrc>(d, ptrs, scal, p, part, splits, st);
-  if (d.r <= 128) return back_t<TileSquare, NumF16, GSrc>(d, ptrs, scal, p, part, splits, st);
-  return back_t<TileWide, NumF16, GSrc>(d, ptrs, scal, p, part, splits, st);
+static hipError_t back_g(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p, WsArr part, int splits, HalfArr pht, hipStream_t st) {
+  if (prec == PREC_BF3) return back_t<TileSquare, NumBF<3>, GSrc>(d, ptrs, scal, p, part, splits, pht, st);
+  if (d.r <= 64) return back_t<TileNarrow, NumF16, GSrc>(d, ptrs, scal, p, part, splits, pht, st);
+  if (d.r <= 128) return back_t<TileSquare, NumF16, GSrc>(d, ptrs, scal, p, part, splits, pht, st);
+  return back_t<TileWide, NumF16, GSrc>(d, ptrs, scal, p, part, splits, pht, st);
 }
-hipError_t launch_back(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p, WsArr part, int splits, hipStream_t st) {
-  return d.g_bf16 ? back_g<SrcBF16>(d, ptrs, prec, scal, p, part, splits, st) : back_g<SrcF32>(d, ptrs, prec, scal, p, part, splits, st);
+hipError_t launch_back(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p, WsArr part, int splits, HalfArr pht, hipStream_t st) {
+  return d.g_bf16 ? back_g<SrcBF16>(d, ptrs, prec, scal, p, part, splits, pht, st) : back_g<SrcF32>(d, ptrs, prec, scal, p, part, splits, pht, st);
 }
 
 hipError_t launch_reduce(int nb, WsArr part, int splits, int64_t count, WsArr out, hipStream_t st) {
@@ -535,6 +762,15 @@ hipError_t launch_reduce(int nb, WsArr part, int splits, int64_t count, WsArr ou
   if (blocks > 2048) blocks = 2048;
   if (blocks < 1) blocks = 1;
   hipLaunchKernelGGL(k_reduce, dim3(blocks, nb), dim3(256), 0, st, part, splits, count, out);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+
+hipError_t launch_reduce_r(const ClassDims& d, WsArr part, int splits, WsArr out, HalfArr rh, const float* scal, hipStream_t st) {
+  int64_t n4 = (int64_t)d.n * d.r / 4;
+  int blocks = (int)((n4 + 255) / 256);
+  if (blocks > 2048) blocks = 2048;
+  hipLaunchKernelGGL(k_reduce_r, dim3(blocks, d.nb), dim3(256), 0, st, d, part, splits, out, rh, scal);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -555,19 +791,19 @@ hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits,
 }
 
 template <class Num>
-static hipError_t apply_t(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* ptrs, hipStream_t st) {
+static hipError_t apply_t(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
   typedef TileSquare T;
   constexpr int lds = T::template lds_bytes<Num>();
   hipError_t e = allow_lds(k_apply<T, Num>, lds);
   if (e != hipSuccess) return e;
   MatPtrs none = {};
   dim3 grid(((rows + T::MT - 1) / T::MT) * ((r + T::NT - 1) / T::NT), 1, nb);
-  hipLaunchKernelGGL((k_apply<T, Num>), grid, dim3(T::THREADS), lds, st, rows, r, a, w, out, ptrs ? *ptrs : none, ptrs ? 1 : 0);
+  hipLaunchKernelGGL((k_apply<T, Num>), grid, dim3(T::THREADS), lds, st, rows, r, a, w, out, ptrs ? *ptrs : none, ptrs ? 1 : 0, hn, ht);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
-hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs, int exact, hipStream_t st) {
-  return exact ? apply_t<NumBF<3>>(nb, rows, r, a, w, out, q_ptrs, st) : apply_t<NumBF<2>>(nb, rows, r, a, w, out, q_ptrs, st);
+hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs, HalfArr hn, HalfArr ht, int exact, hipStream_t st) {
+  return exact ? apply_t<NumBF<3>>(nb, rows, r, a, w, out, q_ptrs, hn, ht, st) : apply_t<NumBF<2>>(nb, rows, r, a, w, out, q_ptrs, hn, ht, st);
 }
 
 template <class Num, class DirA>
@@ -664,7 +900,7 @@ hipError_t launch_scale_from_trace(int nb, int n, int r, WsArr gram, float* scal
 }
 
 hipError_t launch_colnorm(int nb, int n, int r, WsArr rr, const MatPtrs& ptrs, WsArr part, int slabs, WsArr colsq,
-                          float* scal, int* info, hipStream_t st) {
+                          float* scal, int* info, HalfArr qh, hipStream_t st) {
   hipLaunchKernelGGL(k_colsq_partial, dim3((r + 255) / 256, slabs, nb), dim3(256), 0, st, n, r, rr, part, slabs);
   OD_CHECK_LAUNCH();
   hipLaunchKernelGGL(k_colsq_final, dim3(nb), dim3(256), 0, st, n, r, part, slabs, colsq, scal, info);
@@ -672,7 +908,7 @@ hipError_t launch_colnorm(int nb, int n, int r, WsArr rr, const MatPtrs& ptrs, W
   int64_t n4 = (int64_t)n * r / 4;
   int blocks = (int)((n4 + 255) / 256);
   if (blocks > 2048) blocks = 2048;
-  hipLaunchKernelGGL(k_colnorm_apply, dim3(blocks, nb), dim3(256), 0, st, n, r, rr, colsq, ptrs);
+  hipLaunchKernelGGL(k_colnorm_apply, dim3(blocks, nb), dim3(256), 0, st, n, r, rr, colsq, ptrs, qh);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -697,6 +933,23 @@ static hipError_t efx_n(const ClassDims& d, const MatPtrs& ptrs, const float* sc
   return d.g_bf16 ? efx_t<Num, false, true>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st)
                   : efx_t<Num, false, false>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st);
 }
+template <bool XBF, bool GBF>
+static hipError_t efx_h_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, HalfArr ph, HalfArr rh, HalfArr qh,
+                          float a_coef, float b_coef, float lr, hipStream_t st) {
+  constexpr int lds = 2 * 3 * 128 * 80;
+  dim3 grid(((d.m + 127) / 128) * ((d.n + 127) / 128), 1, d.nb);
+  hipLaunchKernelGGL((k_efx_h<XBF, GBF>), grid, dim3(512), lds, st, d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+hipError_t launch_efx_h(const ClassDims& d, const MatPtrs& ptrs, const float* scal, HalfArr ph, HalfArr rh, HalfArr qh,
+                        float a_coef, float b_coef, float lr, hipStream_t st) {
+  if (d.x_bf16) return d.g_bf16 ? efx_h_t<true, true>(d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr, st)
+                                : efx_h_t<true, false>(d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr, st);
+  return d.g_bf16 ? efx_h_t<false, true>(d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr, st)
+                  : efx_h_t<false, false>(d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr, st);
+}
+
 hipError_t launch_efx(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p, WsArr rr,
                       float a_coef, float b_coef, float lr, hipStream_t st) {
   return prec == PREC_BF3 ? efx_n<NumBF<3>>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st)
