@@ -225,7 +225,7 @@ static int cholqr2(const Batch& b, char* ws, int rows, size_t off_a0, size_t off
   WsArr w{reinterpret_cast<float*>(ws + b.off_w), b.st_rr}, tmp{reinterpret_cast<float*>(ws + b.off_tmp), b.st_rr};
   WsArr t1{reinterpret_cast<float*>(ws + off_t1), b.st_rr}, t2{reinterpret_cast<float*>(ws + off_t2), b.st_rr};
   OD_TRY(od::launch_gram(nb, rows, r, a0, part, splits, 1, st));
-  OD_TRY(od::launch_cholinv(nb, r, gram, part, splits, t1, w, tmp, info, info_slot, nullptr, rows, st));
+  OD_TRY(od::launch_cholinv(nb, r, gram, part, splits, t1, w, tmp, info, info_slot, st));
   const HalfArr none{nullptr, 0};
   OD_TRY(od::launch_apply(nb, rows, r, a0, w, a1, nullptr, none, none, exact, st));
   OD_TRY(od::launch_gram(nb, rows, r, a1, part, splits, exact, st));

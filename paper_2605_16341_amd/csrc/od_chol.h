@@ -6,15 +6,19 @@
 //
 // Layout of the computation
 //   * The block is cut into 32 x 32 tiles; only tiles (I, K) with I <= K are kept, each as a
-//     matrix-core accumulator (16 registers per lane) owned by one wave, so the trailing
+//     matrix-core accumulator (16 registers per lane: register v of lane l is row
+//     8 (v / 4) + 4 (l / 32) + v % 4, column l % 32) owned by one wave, so the trailing
 //     matrix never leaves the register file.
-//   * Step J: (a) the owner of the diagonal tile factors it and inverts its factor inside
-//     the wave, rows in lanes, columns in registers, broadcasting with readlane;
-//     (b) the owners of the tiles (J, K) form T(J, K) = W_JJ^T S(J, K) on the matrix cores;
-//     (c) every remaining tile gets S(I, K) -= T(J, I)^T T(J, K).
-//     An accumulator tile serves directly as the k-side operand of the next product: register
-//     v of lane l is row 8 (v / 4) + 4 (l / 32) + v % 4, and the other operand is read from
-//     LDS in that same row order, so no data moves between lanes.
+//   * Step J, (a): the owner of the diagonal tile factors it in place, four rows at a time.
+//     The 4 x 4 diagonal block is gathered with readlane, factored and inverted in scalar
+//     (wave-uniform) arithmetic; the new rows are a 4 x 4 product inside each lane; the
+//     rank-4 trailing update of the tile is one matrix-core product whose operands are the
+//     four registers just written.  The same operations applied to an identity tile give
+//     the inverse of the tile's factor at no extra data movement.
+//     (b): owners of the tiles (J, K) form T(J, K) = W_JJ^T S(J, K) on the matrix cores, the
+//     accumulator tile serving directly as the k-side operand, and publish it to LDS
+//     already split into three bf16 terms in the operand's register order.
+//     (c): every remaining tile gets S(I, K) -= T(J, I)^T T(J, K) from those LDS operands.
 //   * All products use three-way split bf16 operands (six products, 24 significant bits).
 //   * The inverse is then built one block column per wave by back substitution with the
 //     same tile products; T is read back from global memory (written earlier by this same
@@ -31,10 +35,18 @@ constexpr int kCT = 32;                // tile size
 constexpr int kCNT = kCholMax / kCT;   // 8 tiles per side
 constexpr int kCTiles = kCNT * (kCNT + 1) / 2;   // 36
 constexpr int kCSlots = kCTiles / 4;   // 9 tiles per wave
-constexpr int kCPitch = 36;            // floats per LDS tile row (16-byte aligned, conflict free)
-constexpr int kCTileF = kCT * kCPitch; // floats per LDS tile
-// LDS: Wrow[8] | Wt | Dtmp | panel[8]
-constexpr int kCholLds = (kCNT + 1 + 1 + kCNT) * kCTileF * 4;
+constexpr int kCPitch = 36;            // floats per row of an fp32 LDS tile (16-byte aligned, conflict free)
+constexpr int kCTileF = kCT * kCPitch; // floats per fp32 LDS tile
+constexpr int kPPitch = 80;            // bytes per row of a pre-split operand tile (32 bf16 + pad)
+constexpr int kPPlane = kCT * kPPitch; // bytes per part of a pre-split tile
+constexpr int kPTile = 3 * kPPlane;    // bytes per pre-split tile
+constexpr int kStagePitch = kCholMax + 4;        // floats per staged input row
+// LDS: Wrow[8] fp32 | Wt fp32 | panel[8] pre-split | (input staging aliases the panel)
+constexpr int kCholOffWt = kCNT * kCTileF * 4;
+constexpr int kCholOffPanel = kCholOffWt + kCTileF * 4;
+constexpr int kCholPanelBytes = kCNT * kPTile;
+constexpr int kCholStageBytes = kCT * kStagePitch * 4;
+constexpr int kCholLds = kCholOffPanel + (kCholPanelBytes > kCholStageBytes ? kCholPanelBytes : kCholStageBytes);
 
 #ifdef OD_CHOL_TIMING
 #define OD_TICK(slot) do { if (lane == 0) a.dbg[(z * 4 + wave) * 64 + (slot)] = wall_clock64(); } while (0)
@@ -51,8 +63,6 @@ struct CholArgs {
   int blk;             // which diagonal block of kCholMax
   int* info;
   int info_slot;
-  float* scal;         // if non-null: scal[z * kScalPerMat + 1] = power-of-two scale from the trace
-  int trace_rows;      // rows of the tall matrix whose Gram this is (for the scale)
 #ifdef OD_CHOL_TIMING
   long long* dbg;
 #endif
@@ -68,23 +78,27 @@ OD_DEV float lane_bcast(float v, int lane) {
   return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
 }
 
-// 1/sqrt(d) and 1/d to fp32 accuracy: hardware estimate (1 ulp) plus one Newton step.
+// 1/sqrt(d) to fp32 accuracy: hardware estimate (1 ulp) plus one Newton step.
 OD_DEV float fast_rsqrt(float d) {
   float y = __builtin_amdgcn_rsqf(d);
   return y * fmaf(-0.5f * d * y, y, 1.5f);
 }
-OD_DEV float fast_rcp(float d) {
-  float y = __builtin_amdgcn_rcpf(d);
-  return y * fmaf(-d, y, 2.f);
-}
-
-OD_DEV void wave_lds_fence() {
-  __builtin_amdgcn_fence(__ATOMIC_SEQ_CST, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-}
 
 // Three-way split bf16 operand words of 8 floats.
 OD_DEV void split3(const float* x, u32x4* parts) { NumBF<3>::pack(x, 1.f, parts); }
+
+// the same for 4 values in the first four k-slots, the other four being zero
+OD_DEV void split3_four(const float* x, u32x4* parts) {
+  float rem[4] = {x[0], x[1], x[2], x[3]};
+#pragma unroll
+  for (int s = 0; s < 3; ++s) {
+    const uint32_t p0 = pack_bf16_rne(rem[0], rem[1]), p1 = pack_bf16_rne(rem[2], rem[3]);
+    parts[s] = u32x4{p0, p1, 0u, 0u};
+    if (s < 2) {
+      rem[0] -= bf16_lo(p0); rem[1] -= bf16_hi(p0); rem[2] -= bf16_lo(p1); rem[3] -= bf16_hi(p1);
+    }
+  }
+}
 
 OD_DEV void negate3(u32x4* parts) {
 #pragma unroll
@@ -101,8 +115,9 @@ OD_DEV f32x16 mma6(const u32x4* a, const u32x4* b, f32x16 c) {
   return c;
 }
 
-// A-side operand of k-step kk from an LDS tile stored [row][k] with pitch kCPitch:
-// this lane's row is l % 32 and its 8 k-slots are 16 kk + 4 g + {0..3} and 16 kk + 8 + 4 g + {0..3}.
+// Operand of k-step kk from an fp32 LDS tile stored [row][k] with pitch kCPitch: this lane's
+// row is l % 32 and its 8 k-slots are 16 kk + 4 g + {0..3} and 16 kk + 8 + 4 g + {0..3}
+// (the rows an accumulator lane holds in registers 8 kk .. 8 kk + 7).
 OD_DEV void lds_operand(const float* tile, int lane, int kk, u32x4* parts) {
   const float* p = tile + (lane & 31) * kCPitch + 16 * kk + 4 * (lane >> 5);
   f32x4 lo = *reinterpret_cast<const f32x4*>(p);
@@ -132,22 +147,108 @@ OD_DEV void acc_operand(const f32x16& acc, int kk, u32x4* parts) {
   split3(x, parts);
 }
 
-// Transposed store of an accumulator tile into an LDS tile: element (row, col) -> [col][row].
-OD_DEV void store_tile_transposed(float* tile, const f32x16& acc, int lane) {
-  float* p = tile + (lane & 31) * kCPitch + 4 * (lane >> 5);
+// Pre-split operand tile in LDS: the transpose of an accumulator tile (element (row, col) is
+// operand row col, k = row), three bf16 planes, each row holding its 32 k in register order
+// so that the operand words of k-step kk are one 16-byte read per plane.
+OD_DEV void store_presplit(char* tile, const f32x16& acc, int lane) {
+  char* p = tile + (lane & 31) * kPPitch + (lane >> 5) * 16;
 #pragma unroll
-  for (int q = 0; q < 4; ++q) {
-    f32x4 v = {acc[4 * q], acc[4 * q + 1], acc[4 * q + 2], acc[4 * q + 3]};
-    *reinterpret_cast<f32x4*>(p + 8 * q) = v;
+  for (int kk = 0; kk < 2; ++kk) {
+    u32x4 parts[3];
+    acc_operand(acc, kk, parts);
+#pragma unroll
+    for (int s = 0; s < 3; ++s) *reinterpret_cast<u32x4*>(p + s * kPPlane + kk * 32) = parts[s];
   }
+}
+OD_DEV void load_presplit(const char* tile, int lane, int kk, u32x4* parts) {
+  const char* p = tile + (lane & 31) * kPPitch + (lane >> 5) * 16 + kk * 32;
+#pragma unroll
+  for (int s = 0; s < 3; ++s) parts[s] = *reinterpret_cast<const u32x4*>(p + s * kPPlane);
+}
+
+// ---------------------------------------------------------------------------------------
+// Diagonal tile: in-place upper Cholesky factor of the symmetric tile `d` and, in `zt`, the
+// inverse of its transpose (M = L^-1, lower triangular), both in accumulator layout.
+// Returns the 1-based index of the first bad pivot within the tile, or 0.
+// ---------------------------------------------------------------------------------------
+OD_DEV int diag_tile_factor(f32x16& d, f32x16& zt, int lane) {
+  const int c = lane & 31, h = lane >> 5;
+  int bad = 0;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) zt[v] = (acc_row(v, lane) == c) ? 1.f : 0.f;
+#pragma unroll
+  for (int g = 0; g < 8; ++g) {
+    const int q = g >> 1, hh = g & 1, src_lane = 32 * hh + 4 * g;
+    // 4 x 4 diagonal block (upper part), wave-uniform
+    const float d00 = lane_bcast(d[4 * q + 0], src_lane + 0), d01 = lane_bcast(d[4 * q + 0], src_lane + 1);
+    const float d02 = lane_bcast(d[4 * q + 0], src_lane + 2), d03 = lane_bcast(d[4 * q + 0], src_lane + 3);
+    const float d11 = lane_bcast(d[4 * q + 1], src_lane + 1), d12 = lane_bcast(d[4 * q + 1], src_lane + 2);
+    const float d13 = lane_bcast(d[4 * q + 1], src_lane + 3), d22 = lane_bcast(d[4 * q + 2], src_lane + 2);
+    const float d23 = lane_bcast(d[4 * q + 2], src_lane + 3), d33 = lane_bcast(d[4 * q + 3], src_lane + 3);
+    float p0 = d00;
+    if (!(p0 > 0.f) || p0 > 3.0e38f) { if (bad == 0) bad = 4 * g + 1; p0 = 1.f; }
+    const float i00 = fast_rsqrt(p0);
+    const float t01 = d01 * i00, t02 = d02 * i00, t03 = d03 * i00;
+    float p1 = d11 - t01 * t01;
+    if (!(p1 > 0.f) || p1 > 3.0e38f) { if (bad == 0) bad = 4 * g + 2; p1 = 1.f; }
+    const float i11 = fast_rsqrt(p1);
+    const float t12 = (d12 - t01 * t02) * i11, t13 = (d13 - t01 * t03) * i11;
+    float p2 = d22 - t02 * t02 - t12 * t12;
+    if (!(p2 > 0.f) || p2 > 3.0e38f) { if (bad == 0) bad = 4 * g + 3; p2 = 1.f; }
+    const float i22 = fast_rsqrt(p2);
+    const float t23 = (d23 - t02 * t03 - t12 * t13) * i22;
+    float p3 = d33 - t03 * t03 - t13 * t13 - t23 * t23;
+    if (!(p3 > 0.f) || p3 > 3.0e38f) { if (bad == 0) bad = 4 * g + 4; p3 = 1.f; }
+    const float i33 = fast_rsqrt(p3);
+    // inverse of the 4 x 4 upper factor
+    const float w01 = -(t01 * i11) * i00, w12 = -(t12 * i22) * i11, w23 = -(t23 * i33) * i22;
+    const float w02 = -(t01 * w12 + t02 * i22) * i00, w13 = -(t12 * w23 + t13 * i33) * i11;
+    const float w03 = -(t01 * w13 + t02 * w23 + t03 * i33) * i00;
+    // new rows of the factor and of the inverse: (W4^T s)_a = sum_{b <= a} W4[b][a] s_b
+    const float s0 = d[4 * q + 0], s1 = d[4 * q + 1], s2 = d[4 * q + 2], s3 = d[4 * q + 3];
+    const float z0 = zt[4 * q + 0], z1 = zt[4 * q + 1], z2 = zt[4 * q + 2], z3 = zt[4 * q + 3];
+    float tn[4], zn[4];
+    tn[0] = i00 * s0;
+    tn[1] = w01 * s0 + i11 * s1;
+    tn[2] = w02 * s0 + w12 * s1 + i22 * s2;
+    tn[3] = w03 * s0 + w13 * s1 + w23 * s2 + i33 * s3;
+    zn[0] = i00 * z0;
+    zn[1] = w01 * z0 + i11 * z1;
+    zn[2] = w02 * z0 + w12 * z1 + i22 * z2;
+    zn[3] = w03 * z0 + w13 * z1 + w23 * z2 + i33 * z3;
+    const bool mine = h == hh;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (!mine || c < 4 * g + e) tn[e] = 0.f;       // row 4g+e of an upper factor starts at its diagonal
+      if (!mine) zn[e] = 0.f;
+    }
+    if (g < 7) {
+      // rank-4 update of both tiles: -T_g^T T_g and -T_g^T Z_g; the four values sit in the
+      // first k-slots of this lane half, every other slot is zero
+      u32x4 ta[3], tb[3], zb[3];
+      split3_four(tn, tb);
+      split3_four(zn, zb);
+#pragma unroll
+      for (int s = 0; s < 3; ++s) ta[s] = tb[s];
+      negate3(ta);
+      d = mma6(ta, tb, d);
+      zt = mma6(ta, zb, zt);
+    }
+    // the rows of this group are final: put them (back) in place
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      if (mine) { d[4 * q + e] = tn[e]; zt[4 * q + e] = zn[e]; }
+    }
+  }
+  return bad;
 }
 
 __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
   extern __shared__ __align__(16) char lds_raw[];
-  float* Wrow = reinterpret_cast<float*>(lds_raw);            // W_JJ, [i][k], one tile per J
-  float* Wt = Wrow + kCNT * kCTileF;                         // W_JJ^T of the current step
-  float* Dtmp = Wt + kCTileF;                                // staging of the diagonal tile
-  float* panel = Dtmp + kCTileF;                             // T(J, K)^T, one tile per K
+  float* Wrow = reinterpret_cast<float*>(lds_raw);                       // W_JJ, [i][k], one tile per J
+  float* Wt = reinterpret_cast<float*>(lds_raw + kCholOffWt);            // W_JJ^T of the current step
+  char* panel = lds_raw + kCholOffPanel;                                 // T(J, K)^T pre-split, one tile per K
+  float* stage = reinterpret_cast<float*>(lds_raw + kCholOffPanel);      // input rows (before the loop only)
 
   const int z = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int r = a.r;
@@ -159,36 +260,68 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
   float* tg = a.t.base + (int64_t)z * a.t.stride + off;
   float* wg = a.w.base + (int64_t)z * a.w.stride + off;
   const int col = lane & 31, half = lane >> 5;
-
   OD_TICK(0);
-  // ---- load the owned tiles (sum of the split partials); identity outside the block
+
+  // ---- tiles strictly below the diagonal of T and W are zero and written by nobody else
+  {
+    const int lower = nt * (nt - 1) / 2;
+    for (int idx = tid; idx < lower * kCT * (kCT / 4); idx += 256) {
+      const int tile = idx / (kCT * (kCT / 4)), e = idx % (kCT * (kCT / 4));
+      // tile -> (I, K) with I > K: row-wise enumeration of the strict lower triangle
+      int I = 1, base = 0;
+      while (base + I <= tile) { base += I; ++I; }
+      const int K = tile - base;
+      const int gi = I * kCT + e / (kCT / 4), gj = K * kCT + (e % (kCT / 4)) * 4;
+      if (gi < nb && gj < nb) {
+        const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+        *reinterpret_cast<f32x4*>(tg + (int64_t)gi * r + gj) = zero;
+        *reinterpret_cast<f32x4*>(wg + (int64_t)gi * r + gj) = zero;
+      }
+    }
+  }
+
+  // ---- load: 32 rows at a time through LDS (coalesced reads), then each owner picks its
+  // tiles up in accumulator layout; identity outside the block
   f32x16 acc[kCSlots];
-  float tr = 0.f;
 #pragma unroll
   for (int s = 0; s < kCSlots; ++s)
 #pragma unroll
     for (int v = 0; v < 16; ++v) acc[s][v] = 0.f;
-  // split by split, so that the loads of one split are all in flight together.  The Gram
-  // matrix is symmetric: the 4 consecutive rows a lane needs of column gj are read as 4
-  // consecutive columns of row gj (one 16-byte load).
-  for (int sp = 0; sp < a.splits; ++sp) {
-    const float* sp_src = src + (int64_t)sp * a.split_stride;
+  constexpr int kPer = kCT * (kCholMax / 4) / 256;      // float4 per thread per 32 rows
+  f32x4 pre[kPer];
+  auto fetch = [&](int I) {
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      const int idx = tid + u * 256;
+      const int rr = idx / (kCholMax / 4), c4 = (idx % (kCholMax / 4)) * 4;
+      f32x4 v4 = {0.f, 0.f, 0.f, 0.f};
+      if (I * kCT + rr < nb && c4 < nb) {
+        const float* p = src + (int64_t)(I * kCT + rr) * r + c4;
+        v4 = *reinterpret_cast<const f32x4*>(p);
+        for (int sp = 1; sp < a.splits; ++sp) v4 += *reinterpret_cast<const f32x4*>(p + (int64_t)sp * a.split_stride);
+      }
+      pre[u] = v4;
+    }
+  };
+  fetch(0);
+  for (int I = 0; I < nt; ++I) {
+#pragma unroll
+    for (int u = 0; u < kPer; ++u) {
+      const int idx = tid + u * 256;
+      *reinterpret_cast<f32x4*>(stage + (idx / (kCholMax / 4)) * kStagePitch + (idx % (kCholMax / 4)) * 4) = pre[u];
+    }
+    __syncthreads();
+    if (I + 1 < nt) fetch(I + 1);      // in flight while this block is picked up
 #pragma unroll
     for (int s = 0; s < kCSlots; ++s) {
-      const int t = s * 4 + wave, I = kTileI[t], K = kTileK[t];
-      if (I < nt && K < nt) {
-        const int gj = K * kCT + col;
+      const int t = s * 4 + wave;
+      if (kTileI[t] == I && kTileK[t] < nt) {
+        const int K = kTileK[t];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          const int gi = I * kCT + 8 * q + 4 * half;
-          if (gi < nb && gj < nb) {
-            f32x4 v4 = *reinterpret_cast<const f32x4*>(sp_src + (int64_t)gj * r + gi);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) acc[s][4 * q + e] += v4[e];
-          }
-        }
+        for (int v = 0; v < 16; ++v) acc[s][v] = stage[acc_row(v, lane) * kStagePitch + K * kCT + col];
       }
     }
+    __syncthreads();
   }
 #pragma unroll
   for (int s = 0; s < kCSlots; ++s) {
@@ -198,110 +331,42 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
       const int gi = I * kCT + acc_row(v, lane), gj = K * kCT + col;
       const bool inside = I < nt && K < nt && gi < nb && gj < nb;
       if (!inside) acc[s][v] = (gi == gj) ? 1.f : 0.f;
-      else if (gi == gj) tr += acc[s][v];
     }
   }
-  if (a.scal != nullptr) {       // trace -> power-of-two scale of the tall matrix (uniform branch)
-    __shared__ float s_tr[256];
-    s_tr[tid] = tr;
-    __syncthreads();
-    for (int w2 = 128; w2 > 0; w2 >>= 1) {
-      if (tid < w2) s_tr[tid] += s_tr[tid + w2];
-      __syncthreads();
-    }
-    if (tid == 0) {
-      float ms = s_tr[0] / ((float)a.trace_rows * (float)r);
-      float sc = 1.f;
-      if (ms > 0.f && ms < 3.0e38f) sc = ldexpf(1.f, -ilogbf(sqrtf(ms)));
-      a.scal[z * kScalPerMat + 1] = sc;
-    }
-  }
-  __syncthreads();
-
   OD_TICK(1);
+
   // ================================ factorisation ================================
   for (int J = 0; J < nt; ++J) {
     OD_TICK(2 + 4 * J);
-    // ---- (a) diagonal tile: Cholesky and inverse inside the owning wave
+    // ---- (a) diagonal tile
     {
-      // tile (J, J) is entry t = sum_{i=J+1..7} (8 - i) = (7 - J)(8 - J) / 2 of the enumeration
+      // tile (J, J) is entry t = (7 - J)(8 - J) / 2 of the enumeration
       const int t = (7 - J) * (8 - J) / 2;
       if ((t & 3) == wave) {
         const int slot = t >> 2;
-        f32x16 d;
+        f32x16 d, zt;
 #pragma unroll
         for (int s = 0; s < kCSlots; ++s)
           if (s == slot) d = acc[s];
-        // stage [row][col] so that lane i can pick up row i
-#pragma unroll
-        for (int v = 0; v < 16; ++v) Dtmp[acc_row(v, lane) * kCPitch + col] = d[v];
-        wave_lds_fence();
-        float rowv[32];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-          f32x4 v4 = *reinterpret_cast<const f32x4*>(Dtmp + col * kCPitch + 4 * q);
-          rowv[4 * q] = v4[0]; rowv[4 * q + 1] = v4[1]; rowv[4 * q + 2] = v4[2]; rowv[4 * q + 3] = v4[3];
-        }
-        // right-looking Cholesky, lane i = row i (both lane halves compute the same)
-        int bad = 0;
-#pragma unroll
-        for (int k = 0; k < 32; ++k) {
-          float dk = lane_bcast(rowv[k], k);
-          if (!(dk > 0.f) || dk > 3.0e38f) {
-            if (bad == 0) bad = J * kCT + k + 1;
-            dk = 1.f;
-          }
-          const float rs = fast_rsqrt(dk);
-          const float sq = dk * rs;
-          const float tk = rowv[k] * (rs * rs);
-          rowv[k] = (col == k) ? sq : rowv[k] * rs;
-#pragma unroll
-          for (int j = k + 1; j < 32; ++j) rowv[j] = fmaf(-tk, lane_bcast(rowv[j], k), rowv[j]);
-          __builtin_amdgcn_sched_barrier(0);     // keep the broadcasts of one column together
-        }
-#pragma unroll
-        for (int j = 0; j < 32; ++j)
-          if (j > col) rowv[j] = 0.f;            // rowv[j] = L[col][j]
-        if (bad != 0 && lane == 0) {
-          atomicCAS(&a.info[z * kInfoPerMat + a.info_slot], 0, o + bad);
-        }
-        // inverse of L: lane c = column c, m[i] = M[i][c]
-        float m[32];
-#pragma unroll
-        for (int i = 0; i < 32; ++i) {
-          float s = 0.f;
-#pragma unroll
-          for (int k = 0; k < i; ++k) s = fmaf(lane_bcast(rowv[k], i), m[k], s);
-          const float dinv = fast_rcp(lane_bcast(rowv[i], i));
-          m[i] = ((col == i) ? 1.f : -s) * dinv;
-          __builtin_amdgcn_sched_barrier(0);
-        }
+        const int bad = diag_tile_factor(d, zt, lane);
+        if (bad != 0 && lane == 0) atomicCAS(&a.info[z * kInfoPerMat + a.info_slot], 0, o + J * kCT + bad);
         const int nv = (nb - J * kCT) < kCT ? (nb - J * kCT) : kCT;   // valid rows / cols of this tile
-        if (half == 0) {
-          // W_JJ^T = M, [i][k] = M[i][k]: lane k holds column k
+        // zt = M with W_JJ = M^T.  LDS: Wt[i][k] = W_JJ[k][i] = M[i][k];  Wrow[i][k] = W_JJ[i][k] = M[k][i]
+        float* wr = Wrow + J * kCTileF;
 #pragma unroll
-          for (int i = 0; i < 32; ++i) Wt[i * kCPitch + col] = m[i];
-          // W_JJ, [c][i] = M[i][c]: lane c writes its 32 values contiguously
-          float* wr = Wrow + J * kCTileF + col * kCPitch;
+        for (int v = 0; v < 16; ++v) Wt[acc_row(v, lane) * kCPitch + col] = zt[v];
 #pragma unroll
-          for (int q = 0; q < 8; ++q) {
-            f32x4 v4 = {m[4 * q], m[4 * q + 1], m[4 * q + 2], m[4 * q + 3]};
-            *reinterpret_cast<f32x4*>(wr + 4 * q) = v4;
-          }
-          // global: T_JJ[j][i] = L[i][j];  W_JJ[c][i] = M[i][c]
-          if (col < nv) {
-            float* tcol = tg + (int64_t)(J * kCT) * r + J * kCT + col;
+        for (int q = 0; q < 4; ++q) {
+          f32x4 v4 = {zt[4 * q], zt[4 * q + 1], zt[4 * q + 2], zt[4 * q + 3]};
+          *reinterpret_cast<f32x4*>(wr + col * kCPitch + 8 * q + 4 * half) = v4;
+          // global W_JJ[c][rows] (row c of W = column c of M), 4 consecutive entries
+          if (col < nv && 8 * q + 4 * half < nv)
+            *reinterpret_cast<f32x4*>(wg + (int64_t)(J * kCT + col) * r + J * kCT + 8 * q + 4 * half) = v4;
+        }
+        if (col < nv) {
 #pragma unroll
-            for (int j = 0; j < 32; ++j)
-              if (j < nv) tcol[(int64_t)j * r] = rowv[j];
-            float* wrow = wg + (int64_t)(J * kCT + col) * r + J * kCT;
-#pragma unroll
-            for (int q = 0; q < 8; ++q)
-              if (4 * q < nv) {
-                f32x4 v4 = {m[4 * q], m[4 * q + 1], m[4 * q + 2], m[4 * q + 3]};
-                *reinterpret_cast<f32x4*>(wrow + 4 * q) = v4;
-              }
-          }
+          for (int v = 0; v < 16; ++v)
+            if (acc_row(v, lane) < nv) tg[(int64_t)(J * kCT + acc_row(v, lane)) * r + J * kCT + col] = d[v];
         }
       }
     }
@@ -324,7 +389,7 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
           res = mma6(ap, bp, res);
         }
         acc[s] = res;
-        store_tile_transposed(panel + K * kCTileF, res, lane);
+        store_presplit(panel + K * kPTile, res, lane);
         const int nvr = (nb - J * kCT) < kCT ? (nb - J * kCT) : kCT;
         if (K * kCT + col < nb) {
 #pragma unroll
@@ -343,14 +408,14 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
 #pragma unroll
         for (int kk = 0; kk < 2; ++kk) {
           u32x4 ap[3], bp[3];
-          lds_operand(panel + I * kCTileF, lane, kk, ap);
-          lds_operand(panel + K * kCTileF, lane, kk, bp);
+          load_presplit(panel + I * kPTile, lane, kk, ap);
+          load_presplit(panel + K * kPTile, lane, kk, bp);
           negate3(ap);
           acc[s] = mma6(ap, bp, acc[s]);
         }
       }
     }
-    // the next (a) writes Wt / Dtmp only after every wave is done with this step's (b);
+    // the next (a) writes Wt only after every wave is done with this step's (b);
     // the next (b) writes `panel` only after the barrier that follows (a).
   }
   OD_TICK(40);
@@ -358,14 +423,11 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
   OD_TICK(41);
 
   // ================================ inverse ================================
-  // Wave w builds block columns K = w, 7 - w (in that order the long and the short one pair up).
+  // Wave w builds block columns K = 7 - w and w (the long and the short one pair up).
   for (int pass = 0; pass < 2; ++pass) {
     const int K = pass == 0 ? (kCNT - 1 - wave) : wave;
     if (K >= nt) continue;
     f32x16 wcol[kCNT];        // W(I, K), I <= K
-    // W(K, K) from LDS in accumulator layout
-#pragma unroll
-    for (int v = 0; v < 16; ++v) wcol[kCNT - 1][v] = 0.f;
 #pragma unroll
     for (int Ii = kCNT - 1; Ii >= 0; --Ii) {
       if (Ii > K) continue;
@@ -411,14 +473,6 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
     }
   }
   OD_TICK(42);
-  // lower block triangle of T and W inside this block: zero (tiles strictly below the diagonal)
-  for (int idx = tid; idx < nb * nb; idx += 256) {
-    const int i = idx / nb, j = idx % nb;
-    if ((i / kCT) > (j / kCT)) {
-      tg[(int64_t)i * r + j] = 0.f;
-      wg[(int64_t)i * r + j] = 0.f;
-    }
-  }
 }
 
 }  // namespace od

@@ -76,10 +76,9 @@ hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, co
 // per matrix does everything; above, `gram` receives the reduced matrix (destroyed) and the
 // factorisation is blocked, `tmp` being r x r scratch.  A non-positive or non-finite pivot
 // writes its 1-based column to info[mat * kInfoPerMat + info_slot] (first failure wins) and
-// the factorisation goes on with that pivot replaced by 1.  With scal != nullptr also writes
-// the power-of-two scale of the tall matrix (trace_rows x r) whose Gram matrix this is.
+// the factorisation goes on with that pivot replaced by 1.
 hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr part, int splits, WsArr t, WsArr w, WsArr tmp, int* info,
-                          int info_slot, float* scal, int trace_rows, hipStream_t st);
+                          int info_slot, hipStream_t st);
 
 // First-order second pass: from the Gram partials of a nearly orthonormal matrix writes
 // T2 = I + Phi(E), W2 = I - Phi(E) and max |E| into scal[mat][scal_slot] (must be zeroed);

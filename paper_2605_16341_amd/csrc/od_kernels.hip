@@ -824,12 +824,12 @@ static hipError_t sgemm(int nb, const SgemmArgs& g, bool a_kc, int exact, hipStr
 }
 
 hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr part, int splits, WsArr t, WsArr w, WsArr tmp, int* info,
-                          int info_slot, float* scal, int trace_rows, hipStream_t st) {
+                          int info_slot, hipStream_t st) {
   hipError_t e = allow_lds(k_chol256, kCholLds);
   if (e != hipSuccess) return e;
   const int nblk = (r + kLeaf - 1) / kLeaf;
   CholArgs ca = {};
-  ca.t = t; ca.w = w; ca.r = r; ca.info = info; ca.info_slot = info_slot; ca.scal = scal; ca.trace_rows = trace_rows;
+  ca.t = t; ca.w = w; ca.r = r; ca.info = info; ca.info_slot = info_slot;
   // ordered reduction of the split partial sums on many workgroups first: the factorisation
   // below runs on one workgroup per matrix and should not spend its time summing
   if ((e = launch_reduce(nb, part, splits, (int64_t)r * r, gram, st)) != hipSuccess) return e;
@@ -840,8 +840,6 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr part, int splits, WsA
     OD_CHECK_LAUNCH();
     return hipSuccess;
   }
-  if (scal != nullptr && (e = launch_scale_from_trace(nb, trace_rows, r, gram, scal, st)) != hipSuccess) return e;
-  ca.scal = nullptr;
   // lower block triangles of T and W are never written below; clear them once
   for (int z = 0; z < nb; ++z) {
     if ((e = launch_fill_f32(t.base + (int64_t)z * t.stride, (int64_t)r * r, 0.f, st)) != hipSuccess) return e;
