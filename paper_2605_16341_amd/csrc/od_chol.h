@@ -336,42 +336,50 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
   OD_TICK(1);
 
   // ================================ factorisation ================================
-  for (int J = 0; J < nt; ++J) {
-    OD_TICK(2 + 4 * J);
-    // ---- (a) diagonal tile
-    {
-      // tile (J, J) is entry t = (7 - J)(8 - J) / 2 of the enumeration
-      const int t = (7 - J) * (8 - J) / 2;
-      if ((t & 3) == wave) {
-        const int slot = t >> 2;
-        f32x16 d, zt;
+  // (a) for tile (J, J): factor, invert, publish W_JJ (LDS and global) and T_JJ (global)
+  auto do_diag = [&](int J) {
+    const int t = (7 - J) * (8 - J) / 2;      // position of (J, J) in the enumeration
+    const int slot = t >> 2;
+    f32x16 d, zt;
 #pragma unroll
-        for (int s = 0; s < kCSlots; ++s)
-          if (s == slot) d = acc[s];
-        const int bad = diag_tile_factor(d, zt, lane);
-        if (bad != 0 && lane == 0) atomicCAS(&a.info[z * kInfoPerMat + a.info_slot], 0, o + J * kCT + bad);
-        const int nv = (nb - J * kCT) < kCT ? (nb - J * kCT) : kCT;   // valid rows / cols of this tile
-        // zt = M with W_JJ = M^T.  LDS: Wt[i][k] = W_JJ[k][i] = M[i][k];  Wrow[i][k] = W_JJ[i][k] = M[k][i]
-        float* wr = Wrow + J * kCTileF;
+    for (int s = 0; s < kCSlots; ++s)
+      if (s == slot) d = acc[s];
+    const int bad = diag_tile_factor(d, zt, lane);
+    if (bad != 0 && lane == 0) atomicCAS(&a.info[z * kInfoPerMat + a.info_slot], 0, o + J * kCT + bad);
+    const int nv = (nb - J * kCT) < kCT ? (nb - J * kCT) : kCT;   // valid rows / cols of this tile
+    // zt = M with W_JJ = M^T.  LDS: Wt[i][k] = W_JJ[k][i] = M[i][k];  Wrow[i][k] = W_JJ[i][k] = M[k][i]
+    float* wr = Wrow + J * kCTileF;
 #pragma unroll
-        for (int v = 0; v < 16; ++v) Wt[acc_row(v, lane) * kCPitch + col] = zt[v];
+    for (int v = 0; v < 16; ++v) Wt[acc_row(v, lane) * kCPitch + col] = zt[v];
 #pragma unroll
-        for (int q = 0; q < 4; ++q) {
-          f32x4 v4 = {zt[4 * q], zt[4 * q + 1], zt[4 * q + 2], zt[4 * q + 3]};
-          *reinterpret_cast<f32x4*>(wr + col * kCPitch + 8 * q + 4 * half) = v4;
-          // global W_JJ[c][rows] (row c of W = column c of M), 4 consecutive entries
-          if (col < nv && 8 * q + 4 * half < nv)
-            *reinterpret_cast<f32x4*>(wg + (int64_t)(J * kCT + col) * r + J * kCT + 8 * q + 4 * half) = v4;
-        }
-        if (col < nv) {
-#pragma unroll
-          for (int v = 0; v < 16; ++v)
-            if (acc_row(v, lane) < nv) tg[(int64_t)(J * kCT + acc_row(v, lane)) * r + J * kCT + col] = d[v];
-        }
-      }
+    for (int q = 0; q < 4; ++q) {
+      f32x4 v4 = {zt[4 * q], zt[4 * q + 1], zt[4 * q + 2], zt[4 * q + 3]};
+      *reinterpret_cast<f32x4*>(wr + col * kCPitch + 8 * q + 4 * half) = v4;
+      // global W_JJ[c][rows] (row c of W = column c of M), 4 consecutive entries
+      if (col < nv && 8 * q + 4 * half < nv)
+        *reinterpret_cast<f32x4*>(wg + (int64_t)(J * kCT + col) * r + J * kCT + 8 * q + 4 * half) = v4;
     }
-    OD_TICK(3 + 4 * J);
-    __syncthreads();
+    if (col < nv) {
+#pragma unroll
+      for (int v = 0; v < 16; ++v)
+        if (acc_row(v, lane) < nv) tg[(int64_t)(J * kCT + acc_row(v, lane)) * r + J * kCT + col] = d[v];
+    }
+  };
+  // (c) for one owned tile: S(I, K) -= T(J, I)^T T(J, K)
+  auto update_tile = [&](f32x16& tile, int I, int K) {
+#pragma unroll
+    for (int kk = 0; kk < 2; ++kk) {
+      u32x4 ap[3], bp[3];
+      load_presplit(panel + I * kPTile, lane, kk, ap);
+      load_presplit(panel + K * kPTile, lane, kk, bp);
+      negate3(ap);
+      tile = mma6(ap, bp, tile);
+    }
+  };
+
+  if (((7 * 8 / 2) & 3) == wave) do_diag(0);
+  __syncthreads();
+  for (int J = 0; J < nt; ++J) {
     OD_TICK(4 + 4 * J);
     // ---- (b) row panel: T(J, K) = W_JJ^T S(J, K), K > J
 #pragma unroll
@@ -400,26 +408,27 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
     }
     __syncthreads();
     OD_TICK(5 + 4 * J);
-    // ---- (c) trailing update: S(I, K) -= T(J, I)^T T(J, K), J < I <= K
+    // ---- (c) trailing update, J < I <= K.  The owner of the next diagonal tile updates it
+    // first and factors it at once, while the other waves finish their updates.
+    const int tn = (6 - J) * (7 - J) / 2;           // position of (J + 1, J + 1)
+    const bool next_mine = (J + 1 < nt) && ((tn & 3) == wave);
+    if (next_mine) {
+#pragma unroll
+      for (int s = 0; s < kCSlots; ++s)
+        if (s == (tn >> 2)) update_tile(acc[s], J + 1, J + 1);
+      do_diag(J + 1);
+    }
+    OD_TICK(6 + 4 * J);
 #pragma unroll
     for (int s = 0; s < kCSlots; ++s) {
       const int t = s * 4 + wave, I = kTileI[t], K = kTileK[t];
-      if (I > J && K < nt) {
-#pragma unroll
-        for (int kk = 0; kk < 2; ++kk) {
-          u32x4 ap[3], bp[3];
-          load_presplit(panel + I * kPTile, lane, kk, ap);
-          load_presplit(panel + K * kPTile, lane, kk, bp);
-          negate3(ap);
-          acc[s] = mma6(ap, bp, acc[s]);
-        }
-      }
+      if (I > J && K < nt && !(next_mine && t == tn)) update_tile(acc[s], I, K);
     }
-    // the next (a) writes Wt only after every wave is done with this step's (b);
-    // the next (b) writes `panel` only after the barrier that follows (a).
+    OD_TICK(7 + 4 * J);
+    // next (b) reads Wt (written above) and rewrites `panel` (read above)
+    __syncthreads();
   }
-  OD_TICK(40);
-  __syncthreads();     // all of T is in global memory and visible to this workgroup
+  OD_TICK(40);     // the loop's last barrier also makes all of T (global) visible to this workgroup
   OD_TICK(41);
 
   // ================================ inverse ================================
