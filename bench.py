@@ -25,7 +25,12 @@ MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense fp16 / bf16 matrix cores, publishe
 
 # HBM traffic per launch measured with rocprofv3 --pmc (FETCH_SIZE, WRITE_SIZE scaled by a
 # copy kernel of known size); see profiles/.  Keyed by (workload, phase); bytes per launch.
-MEASURED_TRAFFIC = {}
+MEASURED_TRAFFIC = {
+    # profiles/orthdion_step_C2_hbm_counters.txt: 2.000 * FETCH_SIZE + 1.000 * WRITE_SIZE, bytes
+    ("C2", "efx"): 272325296,
+    ("C2", "back"): 186615888,
+    ("C2", "proj"): 185151616,
+}
 
 
 def parse_args():
@@ -39,6 +44,8 @@ def parse_args():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-seconds", type=float, default=12.0)
     ap.add_argument("--pool", type=int, default=4, help="distinct gradients per matrix cycled through")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 1 GiB device copy (torch) so that a counter run can be scaled by it")
     return ap.parse_args()
 
 
@@ -205,6 +212,15 @@ def main():
     if any(info):
         print(f"bench.py: numerical breakdown flagged during warmup: {info}", file=sys.stderr)
         sys.exit(3)
+
+    if args.calibrate_copy:
+        # 256 Mi floats read + 256 Mi floats written: the known-size copy the HBM counters are scaled by
+        src = torch.ones(256 * 1024 * 1024, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     # ---------------- timed region: K steps, dominant kernel bracketed by HIP events
     K = args.steps

@@ -43,7 +43,7 @@ from typing import Dict, Optional, Tuple
 import numpy as np
 
 __all__ = ["thin_qr_positive", "col_norm", "ef_coefficients", "OrthDionOracle",
-           "bf16_bits_to_f64", "f64_to_bf16_bits", "rel_fro"]
+           "bf16_bits_to_f64", "f64_to_bf16_bits", "rel_fro", "effective_rank", "diagnostics", "rank_policy"]
 
 
 # ---------------------------------------------------------------- storage helpers
@@ -208,3 +208,59 @@ class OrthDionOracle:
             x_cur = o["X_bits"] if self.x_bf16 else o["X"]
             m_cur, q_cur = o["M"], o["Q"]
         return outs
+
+
+# ---------------------------------------------------------------- diagnostics and rank policy
+
+def effective_rank(r: np.ndarray) -> float:
+    """Estimated effective rank of App. B.2 / Sec. 6: exp(-sum p log p) with
+    p_i = ||R[:, i]||_2 / sum_j ||R[:, j]||_2 (terms with p_i = 0 contribute 0)."""
+    r = np.asarray(r, dtype=np.float64)
+    lengths = np.sqrt(np.sum(r * r, axis=0))
+    total = float(np.sum(lengths))
+    if total <= 0.0:
+        return 0.0
+    p = lengths / total
+    nz = p > 0.0
+    return float(np.exp(-np.sum(p[nz] * np.log(p[nz]))))
+
+
+def diagnostics(step_out: Dict[str, np.ndarray], m_prev, g) -> Dict[str, float]:
+    """Per-step scalars the paper logs, from one step's intermediates:
+      b_norm, r_norm       ||B||_F and ||R||_F = ||P^T B||_F
+      tracking_error       ||(I - P P^T) B||_F / ||B||_F            (Sec. 6', App. J key quantities)
+      residual_ratio       ||M_prev||_F / ||G||_F  (R-norm ratio)   (Sec. 6', App. J)
+      inner                <B, P Q^T>                               (Lemma 4.2; = trace(T_Q) for QR)
+      nu                   sigma_1(Q), the dual-norm factor         (Prop. 3.1, Lemma 4.1)
+      erank                estimated effective rank of R            (Sec. 6, App. B.2)
+    """
+    g = bf16_bits_to_f64(g) if np.asarray(g).dtype == np.uint16 else np.asarray(g, dtype=np.float64)
+    m_prev = np.asarray(m_prev, dtype=np.float64)
+    b, p, r, q = step_out["B"], step_out["P"], step_out["R"], step_out["Q"]
+    b_norm = float(np.linalg.norm(b))
+    resid = b - p @ (p.T @ b)
+    gn = float(np.linalg.norm(g))
+    return {
+        "b_norm": b_norm,
+        "r_norm": float(np.linalg.norm(r)),
+        "tracking_error": float(np.linalg.norm(resid)) / b_norm if b_norm > 0 else 0.0,
+        "residual_ratio": float(np.linalg.norm(m_prev)) / gn if gn > 0 else 0.0,
+        "inner": float(np.sum(b * (p @ q.T))),
+        "nu": float(np.linalg.norm(q, 2)),
+        "erank": effective_rank(r),
+    }
+
+
+def rank_policy(e_t: float, r_t: int, ema_prev: float, r_min: int, r_max: int, alpha: float,
+                gamma: float) -> Tuple[float, int]:
+    """Ada-Orth-Dion rank selection (App. B.2, Alg. 2): EMA of the effective-rank estimate,
+    buffer multiplier, ceiling, clip to [r_min, r_max], multiple of 8.  Reading: "rounded to
+    multiple of 8" rounds up (the multiplier is a safety margin) and the result is clipped
+    again so that it never leaves [r_min, r_max] (both taken to be multiples of 8).
+    Returns (new EMA, next rank)."""
+    ema = alpha * float(e_t) + (1.0 - alpha) * float(ema_prev)
+    target = int(np.ceil(gamma * ema))
+    nxt = min(max(target, int(r_min)), int(r_max))
+    nxt = ((nxt + 7) // 8) * 8
+    nxt = min(max(nxt, int(r_min)), int(r_max))
+    return ema, nxt

@@ -1,0 +1,85 @@
+"""Pins for the oracle's diagnostics (Prop. 3.1, Lemma 4.2, Sec. 6', App. J) and the adaptive
+rank policy (App. B.2, Alg. 2): closed forms, brute force and hand-worked values.  CPU only."""
+import math
+
+import numpy as np
+import pytest
+
+from oracle.orthdion_oracle import OrthDionOracle, diagnostics, effective_rank, rank_policy
+from test_oracle_pins import jacobi_svd, rand_problem
+
+
+def test_effective_rank_closed_forms():
+    eye = np.eye(6)
+    assert abs(effective_rank(eye[:, :4] * 3.0) - 4.0) < 1e-12          # equal lengths -> r
+    one = np.zeros((5, 3)); one[:, 1] = 2.0
+    assert abs(effective_rank(one) - 1.0) < 1e-12                       # one nonzero column -> 1
+    two = np.zeros((5, 4)); two[0, 0] = 1.0; two[1, 1] = 1.0
+    assert abs(effective_rank(two) - 2.0) < 1e-12
+    # lengths (2, 1, 1): p = (1/2, 1/4, 1/4), entropy = 1.5 ln 2
+    m = np.zeros((3, 3)); m[0, 0] = 2.0; m[1, 1] = 1.0; m[2, 2] = -1.0
+    assert abs(effective_rank(m) - 2.0 ** 1.5) < 1e-12
+    assert effective_rank(np.zeros((4, 2))) == 0.0
+    # scale invariance and column-order invariance
+    rng = np.random.default_rng(0)
+    r = rng.standard_normal((20, 7))
+    assert abs(effective_rank(r) - effective_rank(5.0 * r[:, ::-1])) < 1e-12
+    assert 1.0 <= effective_rank(r) <= 7.0
+
+
+def test_diagnostics_against_brute_force():
+    x, g, mom, q = rand_problem(31, 14, 11, 4)
+    for variant in ("qr", "colnorm"):
+        o = OrthDionOracle(variant=variant).step(x, g, mom, q)
+        d = diagnostics(o, mom, g)
+        b, p, r, qq = o["B"], o["P"], o["R"], o["Q"]
+        assert abs(d["b_norm"] - math.sqrt(sum(v * v for v in b.ravel()))) < 1e-10
+        # Pythagoras: ||B||^2 = ||P^T B||^2 + ||(I - P P^T) B||^2
+        assert abs(d["tracking_error"] ** 2 - (1.0 - d["r_norm"] ** 2 / d["b_norm"] ** 2)) < 1e-12
+        assert abs(d["residual_ratio"] - np.linalg.norm(mom) / np.linalg.norm(g)) < 1e-12
+        inner = sum(b[i, j] * sum(p[i, c] * qq[j, c] for c in range(4)) for i in range(14) for j in range(11))
+        assert abs(d["inner"] - inner) < 1e-10
+        _, sig, _ = jacobi_svd(qq)
+        assert abs(d["nu"] - sig[0]) < 1e-10
+        if variant == "qr":
+            assert abs(d["nu"] - 1.0) < 1e-12                                   # Lemma 4.1
+            assert abs(d["inner"] - np.trace(o["T_Q"])) < 1e-10                 # Lemma 4.2
+        else:
+            assert 1.0 <= d["nu"] <= 2.0 + 1e-12                                # Prop. 3.1, sqrt(r) = 2
+            assert abs(d["inner"] - np.sum(np.linalg.norm(r, axis=0))) < 1e-10  # <B, P Qbar^T> = sum of lengths
+        assert abs(d["erank"] - effective_rank(r)) < 1e-12
+
+
+def test_diagnostics_special_cases():
+    rng = np.random.default_rng(32)
+    m, n, r = 9, 8, 3
+    u, _ = np.linalg.qr(rng.standard_normal((m, r)))
+    v, _ = np.linalg.qr(rng.standard_normal((n, r)))
+    g = (u * np.array([4.0, 2.0, 1.0])) @ v.T
+    zero = np.zeros((m, n))
+    q0, _ = np.linalg.qr(rng.standard_normal((n, r)))
+    o = OrthDionOracle(variant="colnorm").step(zero, g, zero, q0)
+    d = diagnostics(o, zero, g)
+    assert d["tracking_error"] < 1e-7 and d["residual_ratio"] == 0.0      # exactly rank r: nothing is lost
+    # warm start = V_r: columns of R orthogonal, ColNorm is a partial isometry (nu = 1) and the
+    # column lengths are the singular values: erank = exp(entropy of (4, 2, 1) / 7)
+    o = OrthDionOracle(variant="colnorm").step(zero, g, zero, v)
+    d = diagnostics(o, zero, g)
+    p = np.array([4.0, 2.0, 1.0]) / 7.0
+    assert abs(d["nu"] - 1.0) < 1e-9
+    assert abs(d["erank"] - math.exp(-np.sum(p * np.log(p)))) < 1e-9
+    assert abs(d["inner"] - 7.0) < 1e-9                                   # Ky Fan norm: the polar factor attains it
+
+
+def test_rank_policy_hand_worked():
+    # Alg. 2: ema = 0.5*100 + 0.5*120 = 110; target = ceil(1.1*110) = 121; clip to [8, 384]; up to 128
+    ema, nxt = rank_policy(100.0, 384, 120.0, 8, 384, 0.5, 1.1)
+    assert abs(ema - 110.0) < 1e-12 and nxt == 128
+    # exact multiple stays; small estimates clip to r_min; large to r_max
+    assert rank_policy(80.0, 96, 80.0, 8, 384, 1.0, 1.0) == (80.0, 80)
+    assert rank_policy(1.0, 96, 1.0, 16, 384, 0.3, 1.1)[1] == 16
+    assert rank_policy(900.0, 96, 900.0, 16, 384, 0.3, 1.425)[1] == 384
+    # rounding up never leaves the bounds
+    assert rank_policy(379.0, 384, 379.0, 8, 380, 1.0, 1.0)[1] == 380
+    # alpha = 0 keeps the previous EMA
+    assert rank_policy(5.0, 64, 200.0, 8, 384, 0.0, 1.1) == (200.0, 224)
