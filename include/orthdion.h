@@ -152,6 +152,61 @@ typedef enum {
 int orthdion_profile_begin(orthdion_handle h, uint32_t phase_mask, int32_t max_steps);
 int orthdion_profile_end(orthdion_handle h, float* ms_per_phase, int32_t* count_per_phase);
 
+/* ---- Optional per-step diagnostics (quantities the paper logs: Sec. 4.3 tracking error,
+ * Sec. 6.3 R-norm ratio, Prop. 3.1 / Lemma 4.1 dual-norm factor nu, Lemma 4.2 inner product,
+ * App. B.2 estimated effective rank).  Off by default; when on, every orthdion_step also
+ * enqueues a few extra kernels (one more pass over M and G, one over R, a Gram matrix of
+ * the new Q and 128 power iterations on it) that fill a table in the workspace.
+ *   orthdion_set_diagnostics  enable != 0 switches them on for the following steps.
+ *   orthdion_get_diagnostics  copies the table of the most recent step to the host array
+ *                             out_host[nmat][ORTHDION_NDIAG] (matrix order of
+ *                             orthdion_create) and synchronises `stream` (the step's stream).
+ *                             ORTHDION_E_NO_STEP when the last step ran without diagnostics.
+ * Columns of the table (fp32; sums of squares are accumulated in fp64):
+ *   B_NORM          ||M_prev + G||_F
+ *   R_NORM          ||R||_F = ||P^T B||_F
+ *   TRACKING_ERROR  ||(I - P P^T) B||_F / ||B||_F, evaluated as sqrt(||B||^2 - ||R||^2) / ||B||
+ *                   (P has orthonormal columns); absolute accuracy about 1e-3 in FAST precision
+ *   RESIDUAL_RATIO  ||M_prev||_F / ||G||_F (0 when G = 0)
+ *   INNER           <B, P Q^T>: trace of orth(R)'s triangular factor (QR), sum of the column
+ *                   lengths of R (ColNorm)
+ *   NU              sigma_1(Q_new), from power iteration on Q^T Q (a lower estimate, relative
+ *                   error (lambda_2 / lambda_1)^256)
+ *   ERANK           exp(-sum p_i log p_i), p_i = ||R[:, i]|| / sum_j ||R[:, j]||
+ *   G_NORM          ||G||_F                                                              */
+typedef enum {
+  ORTHDION_DIAG_B_NORM = 0,
+  ORTHDION_DIAG_R_NORM = 1,
+  ORTHDION_DIAG_TRACKING_ERROR = 2,
+  ORTHDION_DIAG_RESIDUAL_RATIO = 3,
+  ORTHDION_DIAG_INNER = 4,
+  ORTHDION_DIAG_NU = 5,
+  ORTHDION_DIAG_ERANK = 6,
+  ORTHDION_DIAG_G_NORM = 7,
+  ORTHDION_NDIAG = 8
+} orthdion_diag;
+int orthdion_set_diagnostics(orthdion_handle h, int32_t enable);
+int orthdion_get_diagnostics(orthdion_handle h, float* out_host, void* stream);
+
+/* ---- Adaptive rank (App. B.2, Alg. 2).  Host-only arithmetic:
+ *   ema_out = alpha * e_t + (1 - alpha) * ema_prev
+ *   r_next  = clip(ceil(gamma * ema_out), r_min, r_max), rounded up to a multiple of 8 and
+ *             clipped again (the paper leaves the rounding direction open).
+ * e_t is the ERANK diagnostic of the step just taken.  r_min and r_max must be multiples of
+ * 8 with 8 <= r_min <= r_max; alpha in [0, 1]; gamma > 0; else ORTHDION_E_INVALID_ARG. */
+int orthdion_rank_policy(float e_t, float ema_prev, int32_t r_min, int32_t r_max, float alpha, float gamma,
+                         float* ema_out, int32_t* r_next);
+
+/* Rank change of the warm-start factor (Alg. 2: "truncate or pad"): q_new (n x r_new,
+ * ld r_new, device) receives the leading min(r_old, r_new) columns of q_old (n x r_old,
+ * ld r_old, device); when r_new > r_old the remaining columns are copied from `pad`
+ * (n x (r_new - r_old), row-major, device; the caller draws them, e.g. N(0, 1/n); NULL is
+ * an error then, since zero columns would make the next projection rank deficient).  The
+ * buffers must not overlap.  Only enqueues work on `stream`.  A handle has fixed ranks: after
+ * a rank change create a new handle for the new shapes (host-side work only). */
+int orthdion_resize_q(const float* q_old, int64_t n, int32_t r_old, float* q_new, int32_t r_new,
+                      const float* pad, void* stream);
+
 const char* orthdion_strerror(int status);
 
 int orthdion_destroy(orthdion_handle h);

@@ -43,7 +43,8 @@ from typing import Dict, Optional, Tuple
 import numpy as np
 
 __all__ = ["thin_qr_positive", "col_norm", "ef_coefficients", "OrthDionOracle",
-           "bf16_bits_to_f64", "f64_to_bf16_bits", "rel_fro", "effective_rank", "diagnostics", "rank_policy"]
+           "bf16_bits_to_f64", "f64_to_bf16_bits", "rel_fro", "effective_rank", "diagnostics", "rank_policy",
+           "resize_right_factor"]
 
 
 # ---------------------------------------------------------------- storage helpers
@@ -264,3 +265,17 @@ def rank_policy(e_t: float, r_t: int, ema_prev: float, r_min: int, r_max: int, a
     nxt = ((nxt + 7) // 8) * 8
     nxt = min(max(nxt, int(r_min)), int(r_max))
     return ema, nxt
+
+
+def resize_right_factor(q: np.ndarray, r_new: int, pad: Optional[np.ndarray] = None) -> np.ndarray:
+    """Rank change of the warm-start factor (App. B.2, Alg. 2, "truncate or pad").  Reading:
+    truncation keeps the leading r_new columns; growth appends the columns of ``pad``
+    (n x (r_new - r_old)), which the caller draws -- the paper does not say with what the
+    factor is padded, and zero columns would make the next projection rank deficient."""
+    q = np.asarray(q)
+    n, r_old = q.shape
+    if r_new <= r_old:
+        return q[:, :r_new].copy()
+    if pad is None or pad.shape != (n, r_new - r_old):
+        raise ValueError("growing the rank needs pad of shape (n, r_new - r_old)")
+    return np.concatenate([q, np.asarray(pad, dtype=q.dtype)], axis=1)

@@ -26,7 +26,12 @@ ORTHDION_PREC_AUTO, ORTHDION_PREC_FAST, ORTHDION_PREC_EXACT = 0, 1, 2
 
 EXPORTS = ["orthdion_create", "orthdion_workspace_bytes", "orthdion_set_lr", "orthdion_set_mu",
            "orthdion_set_variant", "orthdion_step", "orthdion_get_info", "orthdion_workspace_layout",
-           "orthdion_profile_begin", "orthdion_profile_end", "orthdion_strerror", "orthdion_destroy"]
+           "orthdion_profile_begin", "orthdion_profile_end", "orthdion_set_diagnostics",
+           "orthdion_get_diagnostics", "orthdion_rank_policy", "orthdion_resize_q", "orthdion_strerror",
+           "orthdion_destroy"]
+
+DIAG = ["b_norm", "r_norm", "tracking_error", "residual_ratio", "inner", "nu", "erank", "g_norm"]
+ORTHDION_NDIAG = len(DIAG)
 
 PHASES = ["stats", "proj", "proj_reduce", "orth_left", "back", "back_reduce", "orth_right", "efx"]
 ORTHDION_NPHASE = len(PHASES)
@@ -96,6 +101,16 @@ def load() -> ctypes.CDLL:
     lib.orthdion_profile_begin.restype = ctypes.c_int
     lib.orthdion_profile_end.argtypes = [vp, ctypes.POINTER(ctypes.c_float), ctypes.POINTER(ctypes.c_int32)]
     lib.orthdion_profile_end.restype = ctypes.c_int
+    lib.orthdion_set_diagnostics.argtypes = [vp, ctypes.c_int32]
+    lib.orthdion_set_diagnostics.restype = ctypes.c_int
+    lib.orthdion_get_diagnostics.argtypes = [vp, ctypes.POINTER(ctypes.c_float), vp]
+    lib.orthdion_get_diagnostics.restype = ctypes.c_int
+    lib.orthdion_rank_policy.argtypes = [ctypes.c_float, ctypes.c_float, ctypes.c_int32, ctypes.c_int32,
+                                         ctypes.c_float, ctypes.c_float, ctypes.POINTER(ctypes.c_float),
+                                         ctypes.POINTER(ctypes.c_int32)]
+    lib.orthdion_rank_policy.restype = ctypes.c_int
+    lib.orthdion_resize_q.argtypes = [vp, ctypes.c_int64, ctypes.c_int32, vp, ctypes.c_int32, vp, vp]
+    lib.orthdion_resize_q.restype = ctypes.c_int
     lib.orthdion_strerror.argtypes = [ctypes.c_int]
     lib.orthdion_strerror.restype = ctypes.c_char_p
     lib.orthdion_destroy.argtypes = [vp]
@@ -192,6 +207,31 @@ def orthdion_profile_end(handle: int) -> dict:
     return {PHASES[i]: (float(ms[i]), int(cnt[i])) for i in range(ORTHDION_NPHASE) if cnt[i] > 0}
 
 
+def orthdion_set_diagnostics(handle: int, enable: bool) -> None:
+    _check(load().orthdion_set_diagnostics(handle, 1 if enable else 0))
+
+
+def orthdion_get_diagnostics(handle: int, nmat: int, stream: int = 0) -> List[dict]:
+    """One {name: value} dict per matrix for the most recent step (names in DIAG)."""
+    out = (ctypes.c_float * (nmat * ORTHDION_NDIAG))()
+    _check(load().orthdion_get_diagnostics(handle, out, ctypes.c_void_p(stream)))
+    return [{DIAG[k]: float(out[i * ORTHDION_NDIAG + k]) for k in range(ORTHDION_NDIAG)} for i in range(nmat)]
+
+
+def orthdion_rank_policy(e_t: float, ema_prev: float, r_min: int, r_max: int, alpha: float, gamma: float):
+    """(new EMA, next rank) of the adaptive-rank rule."""
+    ema, nxt = ctypes.c_float(), ctypes.c_int32()
+    _check(load().orthdion_rank_policy(float(e_t), float(ema_prev), int(r_min), int(r_max), float(alpha),
+                                       float(gamma), ctypes.byref(ema), ctypes.byref(nxt)))
+    return float(ema.value), int(nxt.value)
+
+
+def orthdion_resize_q(q_old: int, n: int, r_old: int, q_new: int, r_new: int, pad: int = 0, stream: int = 0) -> None:
+    """Device addresses as ints; `pad` may be 0 only when the rank does not grow."""
+    _check(load().orthdion_resize_q(ctypes.c_void_p(q_old), int(n), int(r_old), ctypes.c_void_p(q_new), int(r_new),
+                                    ctypes.c_void_p(pad or None), ctypes.c_void_p(stream)))
+
+
 def orthdion_destroy(handle: int) -> None:
     _check(load().orthdion_destroy(handle))
 
@@ -227,6 +267,13 @@ class OrthDion:
     def info(self, stream=None) -> List[int]:
         st = stream if stream is not None else self._torch.cuda.current_stream().cuda_stream
         return orthdion_get_info(self.handle, self.nmat, st)
+
+    def set_diagnostics(self, enable: bool) -> None:
+        orthdion_set_diagnostics(self.handle, enable)
+
+    def diagnostics(self, stream=None) -> List[dict]:
+        st = stream if stream is not None else self._torch.cuda.current_stream().cuda_stream
+        return orthdion_get_diagnostics(self.handle, self.nmat, st)
 
     def debug_factors(self, index: int) -> dict:
         """P, R and the triangular factors the last step left in the workspace (copies)."""

@@ -51,8 +51,9 @@ struct orthdion_ctx {
   orthdion_config cfg;
   std::vector<Batch> batches;
   std::vector<int> batch_of, slot_of;     // per matrix
-  size_t off_scal, off_info, ws_bytes;
+  size_t off_scal, off_info, off_diag, off_dacc, off_dpart, ws_bytes;
   void* last_ws;
+  bool diag_on = false, diag_valid = false;
   // optional phase timing with HIP events (host resources only)
   bool prof_on = false;
   unsigned prof_mask = 0;
@@ -142,6 +143,9 @@ extern "C" int orthdion_create(orthdion_handle* out, const orthdion_matdesc* mat
   size_t off = 0;
   h->off_scal = off; off = align_up(off + (size_t)nmat * od::kScalPerMat * sizeof(float));
   h->off_info = off; off = align_up(off + (size_t)nmat * od::kInfoPerMat * sizeof(int));
+  h->off_diag = off; off = align_up(off + (size_t)nmat * od::kDiagPerMat * sizeof(float));
+  h->off_dacc = off; off = align_up(off + (size_t)nmat * od::kDaccPerMat * sizeof(double));
+  h->off_dpart = off; off = align_up(off + (size_t)nmat * od::kDiagBlocks * 4 * sizeof(double));
   int slot_base = 0;
   for (Batch& b : h->batches) {
     ClassDims& d = b.d;
@@ -262,6 +266,11 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
   OD_TRY(od::launch_fill_int(info_all, (int64_t)nmat * od::kInfoPerMat, 0, st));
   OD_TRY(od::launch_fill_f32(scal_all, (int64_t)nmat * od::kScalPerMat, 0.f, st));
   h->last_ws = workspace;
+  const bool diag = h->diag_on;
+  h->diag_valid = diag;
+  float* diag_all = reinterpret_cast<float*>(ws + h->off_diag);
+  double* dacc_all = reinterpret_cast<double*>(ws + h->off_dacc);
+  double* dpart_all = reinterpret_cast<double*>(ws + h->off_dpart);
 
 #define OD_PHASE_BEGIN(ph)                                                   \
   do {                                                                       \
@@ -293,6 +302,10 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     HalfArr rh{reinterpret_cast<uint16_t*>(ws + b.off_rh), b.st_r}, qh{reinterpret_cast<uint16_t*>(ws + b.off_qh), b.st_r};
     HalfArr qht{reinterpret_cast<uint16_t*>(ws + b.off_qht), b.st_r};
 
+    double* dacc = dacc_all + (size_t)b.slot_base * od::kDaccPerMat;
+    double* dpart = dpart_all + (size_t)b.slot_base * od::kDiagBlocks * 4;
+    if (diag) OD_TRY(od::launch_diag_norms(d, ptrs, dpart, st));
+
     // Alg. 1 lines 1-2: P_raw = (M + G) Q, then P = orth(P_raw)
     OD_PHASE_BEGIN(ORTHDION_PHASE_STATS);
     if (fast) OD_TRY(od::launch_stats(d, ptrs, scal, qht, st));
@@ -316,6 +329,7 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     if (fast) OD_TRY(od::launch_reduce_r(d, part, b.splits_back, ra, rh, scal, st));
     else OD_TRY(od::launch_reduce(d.nb, part, b.splits_back, (int64_t)d.n * d.r, ra, st));
     OD_PHASE_END(ORTHDION_PHASE_BACK_REDUCE);
+    if (diag) OD_TRY(od::launch_diag_cols(d.nb, d.n, d.r, ra, part, b.slabs, dacc, st));
     // line 4: Q = orth(R) or ColNorm(R), written to the callers' Q (Q_prev is no longer needed)
     OD_PHASE_BEGIN(ORTHDION_PHASE_ORTH_RIGHT);
     if (h->cfg.variant == ORTHDION_QR) {
@@ -326,6 +340,19 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
       OD_TRY(od::launch_colnorm(d.nb, d.n, d.r, ra, ptrs, part, b.slabs, colsq, scal, info, fast ? qh : none, st));
     }
     OD_PHASE_END(ORTHDION_PHASE_ORTH_RIGHT);
+    if (diag) {
+      // nu = sigma_1(Q_new): Gram matrix of the new right factor, then power iteration
+      WsArr rb{reinterpret_cast<float*>(ws + b.off_rb), b.st_r};
+      WsArr gram{reinterpret_cast<float*>(ws + b.off_gram), b.st_rr}, tmp{reinterpret_cast<float*>(ws + b.off_tmp), b.st_rr};
+      WsArr tq1{reinterpret_cast<float*>(ws + b.off_tq1), b.st_rr}, tq2{reinterpret_cast<float*>(ws + b.off_tq2), b.st_rr};
+      if (h->cfg.variant == ORTHDION_QR) OD_TRY(od::launch_diag_trace(d.nb, d.r, tq1, tq2, dacc, st));
+      OD_TRY(od::launch_gather_q(d.nb, d.n, d.r, ptrs, rb, st));
+      OD_TRY(od::launch_gram(d.nb, d.n, d.r, rb, part, b.splits_gram_q, 1, st));
+      OD_TRY(od::launch_reduce(d.nb, part, b.splits_gram_q, (int64_t)d.r * d.r, gram, st));
+      OD_TRY(od::launch_power(d.nb, d.r, gram, tmp, 128, dacc, st));
+      OD_TRY(od::launch_diag_final(d.nb, dpart, dacc, h->cfg.variant == ORTHDION_COLNORM ? 1 : 0,
+                                   diag_all + (size_t)b.slot_base * od::kDiagPerMat, st));
+    }
     // lines 5-7: parameter update and error feedback in one pass
     OD_PHASE_BEGIN(ORTHDION_PHASE_EFX);
     if (fast) OD_TRY(od::launch_efx_h(d, ptrs, scal, ph, rh, qh, a_coef, b_coef, h->cfg.lr, st));
@@ -401,6 +428,64 @@ extern "C" int orthdion_get_info(orthdion_handle h, int32_t* info_host, void* st
     else if (w[2] != 0) v = -w[2];
     info_host[i] = v;
   }
+  return ORTHDION_OK;
+}
+
+extern "C" int orthdion_set_diagnostics(orthdion_handle h, int32_t enable) {
+  if (!h) return ORTHDION_E_NULL_PTR;
+  for (const Batch& b : h->batches)
+    if (enable && b.d.r > 2048) return ORTHDION_E_BAD_SHAPE;     // power iteration keeps a vector of r floats in LDS
+  h->diag_on = enable != 0;
+  return ORTHDION_OK;
+}
+
+extern "C" int orthdion_get_diagnostics(orthdion_handle h, float* out_host, void* stream) {
+  if (!h || !out_host) return ORTHDION_E_NULL_PTR;
+  if (!h->last_ws || !h->diag_valid) return ORTHDION_E_NO_STEP;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const int nmat = (int)h->mats.size();
+  std::vector<float> raw((size_t)nmat * od::kDiagPerMat);
+  const char* ws = reinterpret_cast<const char*>(h->last_ws);
+  OD_TRY(hipMemcpyAsync(raw.data(), ws + h->off_diag, raw.size() * sizeof(float), hipMemcpyDeviceToHost, st));
+  OD_TRY(hipStreamSynchronize(st));
+  for (int i = 0; i < nmat; ++i) {
+    const Batch& b = h->batches[h->batch_of[i]];
+    const float* w = raw.data() + (size_t)(b.slot_base + h->slot_of[i]) * od::kDiagPerMat;
+    for (int k = 0; k < od::kDiagPerMat; ++k) out_host[(size_t)i * ORTHDION_NDIAG + k] = w[k];
+  }
+  return ORTHDION_OK;
+}
+
+extern "C" int orthdion_rank_policy(float e_t, float ema_prev, int32_t r_min, int32_t r_max, float alpha, float gamma,
+                                    float* ema_out, int32_t* r_next) {
+  if (!ema_out || !r_next) return ORTHDION_E_NULL_PTR;
+  if (r_min < 8 || r_max < r_min || r_min % 8 || r_max % 8) return ORTHDION_E_INVALID_ARG;
+  if (!std::isfinite(e_t) || !std::isfinite(ema_prev) || e_t < 0.f || ema_prev < 0.f) return ORTHDION_E_INVALID_ARG;
+  if (!(alpha >= 0.f && alpha <= 1.f) || !(gamma > 0.f) || !std::isfinite(gamma)) return ORTHDION_E_INVALID_ARG;
+  // Alg. 2 in double precision: EMA, buffer multiplier, ceiling, clip, multiple of 8
+  const double ema = (double)alpha * (double)e_t + (1.0 - (double)alpha) * (double)ema_prev;
+  double target = std::ceil((double)gamma * ema);
+  if (target < (double)r_min) target = (double)r_min;
+  if (target > (double)r_max) target = (double)r_max;
+  int32_t nxt = ((int32_t)target + 7) / 8 * 8;
+  if (nxt < r_min) nxt = r_min;
+  if (nxt > r_max) nxt = r_max;
+  *ema_out = (float)ema;
+  *r_next = nxt;
+  return ORTHDION_OK;
+}
+
+extern "C" int orthdion_resize_q(const float* q_old, int64_t n, int32_t r_old, float* q_new, int32_t r_new,
+                                 const float* pad, void* stream) {
+  if (!q_old || !q_new) return ORTHDION_E_NULL_PTR;
+  if (n < 8 || n % 8 || n >= (1 << 24) || r_old < 8 || r_new < 8 || r_old % 8 || r_new % 8 || r_old > n || r_new > n)
+    return ORTHDION_E_BAD_SHAPE;
+  if (r_new > r_old && !pad) return ORTHDION_E_NULL_PTR;
+  if (reinterpret_cast<uintptr_t>(q_old) % 16 || reinterpret_cast<uintptr_t>(q_new) % 16 ||
+      reinterpret_cast<uintptr_t>(pad) % 16)
+    return ORTHDION_E_MISALIGNED;
+  (void)hipGetLastError();
+  OD_TRY(od::launch_resize_q(q_old, n, r_old, q_new, r_new, pad, reinterpret_cast<hipStream_t>(stream)));
   return ORTHDION_OK;
 }
 

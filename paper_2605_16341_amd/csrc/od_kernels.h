@@ -102,6 +102,28 @@ hipError_t launch_efx(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const 
 hipError_t launch_efx_h(const ClassDims& d, const MatPtrs& ptrs, const float* scal, HalfArr ph, HalfArr rh, HalfArr qh,
                         float a_coef, float b_coef, float lr, hipStream_t st);
 
+// ---- optional diagnostics (od_diag.hip) ----
+constexpr int kDiagPerMat = 8;     // floats reported per matrix
+constexpr int kDaccPerMat = 8;     // fp64 accumulators per matrix: [3] ||R||^2, [4] sum of column lengths of R,
+                                   // [5] sum of len * log(len), [6] trace of the right triangular factor, [7] lambda_max
+constexpr int kDiagBlocks = 128;   // workgroups (partial triples of 4 doubles) per matrix of the norm pass
+
+// dpart[mat][kDiagBlocks][4] = partial sums of squares of M, G, M + G
+hipError_t launch_diag_norms(const ClassDims& d, const MatPtrs& ptrs, double* dpart, hipStream_t st);
+// column lengths of R (n x r, ld r) -> dacc[mat][3..5]; `part` needs slabs * r floats per matrix
+hipError_t launch_diag_cols(int nb, int n, int r, WsArr rr, WsArr part, int slabs, double* dacc, hipStream_t st);
+// dacc[mat][6] = sum_i t1[i][i] * t2[i][i]
+hipError_t launch_diag_trace(int nb, int r, WsArr t1, WsArr t2, double* dacc, hipStream_t st);
+// out[mat] = callers' Q (n x r)
+hipError_t launch_gather_q(int nb, int n, int r, const MatPtrs& ptrs, WsArr out, hipStream_t st);
+// dacc[mat][7] = largest eigenvalue of the symmetric PSD r x r matrix `gram` after `iters` power
+// iterations; xbuf needs 2 r floats per matrix (used for r > 512)
+hipError_t launch_power(int nb, int r, WsArr gram, WsArr xbuf, int iters, double* dacc, hipStream_t st);
+// diag[mat][0..7] = ||B||, ||R||, tracking error, ||M_prev|| / ||G||, <B, P Q^T>, nu, effective rank, ||G||
+hipError_t launch_diag_final(int nb, const double* dpart, const double* dacc, int colnorm, float* diag, hipStream_t st);
+// q_new (n x r_new) = leading min(r_old, r_new) columns of q_old, then columns of pad (n x (r_new - r_old))
+hipError_t launch_resize_q(const float* q_old, int64_t n, int r_old, float* q_new, int r_new, const float* pad, hipStream_t st);
+
 hipError_t launch_fill_int(int* p, int64_t count, int value, hipStream_t st);
 hipError_t launch_fill_f32(float* p, int64_t count, float value, hipStream_t st);
 

@@ -83,3 +83,49 @@ def test_rank_policy_hand_worked():
     assert rank_policy(379.0, 384, 379.0, 8, 380, 1.0, 1.0)[1] == 380
     # alpha = 0 keeps the previous EMA
     assert rank_policy(5.0, 64, 200.0, 8, 384, 0.0, 1.1) == (200.0, 224)
+
+
+def test_resize_right_factor_small():
+    from oracle.orthdion_oracle import resize_right_factor
+    q = np.arange(12.0).reshape(4, 3)
+    assert resize_right_factor(q, 2).tolist() == [[0, 1], [3, 4], [6, 7], [9, 10]]
+    assert resize_right_factor(q, 3).tolist() == q.tolist()
+    pad = -np.ones((4, 2))
+    out = resize_right_factor(q, 5, pad)
+    assert out.shape == (4, 5) and out[:, :3].tolist() == q.tolist() and out[:, 3:].tolist() == pad.tolist()
+    with pytest.raises(ValueError):
+        resize_right_factor(q, 5)
+
+
+def test_rank_policy_c_abi_matches_oracle():
+    """The host-only entry point against the oracle on a grid and on the hand-worked cases."""
+    from paper_2605_16341_amd import binding
+    assert binding.orthdion_rank_policy(100.0, 120.0, 8, 384, 0.5, 1.1)[1] == 128
+    rng = np.random.default_rng(5)
+    for _ in range(500):
+        e = float(np.float32(rng.uniform(0.0, 500.0)))
+        prev = float(np.float32(rng.uniform(0.0, 500.0)))
+        alpha = float(np.float32(rng.uniform(0.0, 1.0)))
+        gamma = float(np.float32(rng.choice([1.0, 1.1, 1.425])))
+        r_min = 8 * int(rng.integers(1, 8))
+        r_max = r_min + 8 * int(rng.integers(0, 60))
+        ema_o, nxt_o = rank_policy(e, 0, prev, r_min, r_max, alpha, gamma)
+        ema_c, nxt_c = binding.orthdion_rank_policy(e, prev, r_min, r_max, alpha, gamma)
+        assert abs(ema_c - ema_o) <= 1e-6 * max(1.0, abs(ema_o))
+        assert nxt_c == nxt_o
+    for bad in [(1.0, 1.0, 4, 64, 0.5, 1.1), (1.0, 1.0, 16, 8, 0.5, 1.1), (1.0, 1.0, 8, 60, 0.5, 1.1),
+                (1.0, 1.0, 8, 64, 1.5, 1.1), (1.0, 1.0, 8, 64, 0.5, 0.0), (float("nan"), 1.0, 8, 64, 0.5, 1.1)]:
+        with pytest.raises(binding.OrthDionError):
+            binding.orthdion_rank_policy(*bad)
+
+
+def test_resize_q_argument_errors():
+    from paper_2605_16341_amd import binding
+    with pytest.raises(binding.OrthDionError):
+        binding.orthdion_resize_q(0, 64, 16, 256, 8)                 # null source
+    with pytest.raises(binding.OrthDionError):
+        binding.orthdion_resize_q(256, 64, 16, 512, 12)              # rank not a multiple of 8
+    with pytest.raises(binding.OrthDionError):
+        binding.orthdion_resize_q(256, 64, 16, 512, 32)              # growth without pad
+    with pytest.raises(binding.OrthDionError):
+        binding.orthdion_resize_q(256, 64, 16, 516, 8)               # misaligned destination
