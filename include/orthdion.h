@@ -61,8 +61,11 @@ typedef enum { ORTHDION_QR = 0, ORTHDION_COLNORM = 1 } orthdion_variant;
 /* Error-feedback form, both M = a B - b P R^T:
  *   ORTHDION_EF_DION   a = 1,  b = 1 - mu   (momentum form; the default)
  *   ORTHDION_EF_PAPER  a = mu, b = mu       (Alg. 1 line 7 with beta = mu)
- * They coincide at mu = 0 / beta = 1. */
-typedef enum { ORTHDION_EF_DION = 0, ORTHDION_EF_PAPER = 1 } orthdion_ef;
+ *   ORTHDION_EF_POLYAK a = mu, b = 0        (no error feedback: the buffer is plain heavy-ball
+ *                                            momentum of the gradients, the "PolyakDion"
+ *                                            comparison of Sec. 6.3 / App. H)
+ * The first two coincide at mu = 0 / beta = 1. */
+typedef enum { ORTHDION_EF_DION = 0, ORTHDION_EF_PAPER = 1, ORTHDION_EF_POLYAK = 2 } orthdion_ef;
 
 /* Arithmetic of the large contractions (B Q, B^T P, P R^T, P Q^T).  Accumulation is always
  * fp32; the orthogonalisations always use split-bf16 operands (>= 16 significant bits).

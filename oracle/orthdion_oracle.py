@@ -123,13 +123,17 @@ def col_norm(r: np.ndarray) -> np.ndarray:
 
 
 def ef_coefficients(mu: float, ef: str) -> Tuple[float, float]:
-    """(a, b) of ``M_new = a B - b P R^T``: "dion" -> (1, 1 - mu); "paper" -> (mu, mu)
+    """(a, b) of ``M_new = a B - b P R^T``: "dion" -> (1, 1 - mu); "polyak" -> (mu, 0); "paper" -> (mu, mu)
     (Alg. 1 line 7 with beta = mu)."""
     if ef == "dion":
         return 1.0, 1.0 - float(mu)
     if ef == "paper":
         return float(mu), float(mu)
-    raise ValueError("ef must be 'dion' or 'paper'")
+    if ef == "polyak":
+        # "PolyakDion" of Sec. 6.3 / App. H: residual identically zero, explicit momentum mu.
+        # Reading: the momentum is heavy-ball on the buffer, B_t = mu B_{t-1} + G_t.
+        return float(mu), 0.0
+    raise ValueError("ef must be 'dion', 'paper' or 'polyak'")
 
 
 # ---------------------------------------------------------------- the step

@@ -21,7 +21,7 @@ ORTHDION_E_NO_STEP = -7
 
 ORTHDION_F32, ORTHDION_BF16 = 0, 1
 ORTHDION_QR, ORTHDION_COLNORM = 0, 1
-ORTHDION_EF_DION, ORTHDION_EF_PAPER = 0, 1
+ORTHDION_EF_DION, ORTHDION_EF_PAPER, ORTHDION_EF_POLYAK = 0, 1, 2
 ORTHDION_PREC_AUTO, ORTHDION_PREC_FAST, ORTHDION_PREC_EXACT = 0, 1, 2
 
 EXPORTS = ["orthdion_create", "orthdion_workspace_bytes", "orthdion_set_lr", "orthdion_set_mu",
@@ -250,7 +250,7 @@ class OrthDion:
         self.r = r
         self.handle = orthdion_create(self.shapes, r, dt[x_dtype], dt[g_dtype],
                                       {"qr": ORTHDION_QR, "colnorm": ORTHDION_COLNORM}[variant],
-                                      {"dion": ORTHDION_EF_DION, "paper": ORTHDION_EF_PAPER}[ef],
+                                      {"dion": ORTHDION_EF_DION, "paper": ORTHDION_EF_PAPER, "polyak": ORTHDION_EF_POLYAK}[ef],
                                       {"auto": ORTHDION_PREC_AUTO, "fast": ORTHDION_PREC_FAST,
                                        "exact": ORTHDION_PREC_EXACT}[precision], mu, lr)
         self.workspace_bytes = orthdion_workspace_bytes(self.handle)

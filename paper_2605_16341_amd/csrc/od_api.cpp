@@ -78,7 +78,7 @@ static int check_config(const orthdion_config* c) {
   if (c->x_dtype != ORTHDION_F32 && c->x_dtype != ORTHDION_BF16) return ORTHDION_E_INVALID_ARG;
   if (c->g_dtype != ORTHDION_F32 && c->g_dtype != ORTHDION_BF16) return ORTHDION_E_INVALID_ARG;
   if (c->variant != ORTHDION_QR && c->variant != ORTHDION_COLNORM) return ORTHDION_E_INVALID_ARG;
-  if (c->ef != ORTHDION_EF_DION && c->ef != ORTHDION_EF_PAPER) return ORTHDION_E_INVALID_ARG;
+  if (c->ef != ORTHDION_EF_DION && c->ef != ORTHDION_EF_PAPER && c->ef != ORTHDION_EF_POLYAK) return ORTHDION_E_INVALID_ARG;
   if (c->precision != ORTHDION_PREC_AUTO && c->precision != ORTHDION_PREC_FAST && c->precision != ORTHDION_PREC_EXACT)
     return ORTHDION_E_INVALID_ARG;
   if (!std::isfinite(c->mu) || c->mu < 0.f || c->mu > 1.f) return ORTHDION_E_INVALID_ARG;
@@ -259,7 +259,8 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
   const int exact = prec == od::PREC_BF3 ? 1 : 0;
   float a_coef, b_coef;
   if (h->cfg.ef == ORTHDION_EF_DION) { a_coef = 1.f; b_coef = 1.f - h->cfg.mu; }
-  else { a_coef = h->cfg.mu; b_coef = h->cfg.mu; }
+  else if (h->cfg.ef == ORTHDION_EF_PAPER) { a_coef = h->cfg.mu; b_coef = h->cfg.mu; }
+  else { a_coef = h->cfg.mu; b_coef = 0.f; }
 
   int* info_all = reinterpret_cast<int*>(ws + h->off_info);
   float* scal_all = reinterpret_cast<float*>(ws + h->off_scal);

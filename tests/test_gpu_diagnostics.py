@@ -181,3 +181,14 @@ def test_adaptive_rank_loop_follows_the_oracle():
         ranks.append(r_o)
         assert np.linalg.norm(to_host(M, torch).astype(np.float64) - mo) <= 1e-4 * np.linalg.norm(mo), t
     assert ranks[-1] < r0, ranks          # the rule did shrink the rank on this spectrum
+
+
+@pytest.mark.parametrize("beta", [1.0, 0.5, 0.1, 0.05])
+def test_beta_sweep_paper_form(beta):
+    """Error-feedback coefficient sweep of Sec. 6.3 (paper-form EF, beta passed as mu) on a
+    synthetic stream with fresh noise every step: diagnostics follow the oracle at every beta."""
+    run_case([(256, 192)], 32, "f32", "qr", steps=4, seed=780, ef="paper", mu=beta, momentum_std=0.0)
+
+
+def test_polyak_form():
+    run_case([(256, 192)], 32, "bf16", "qr", steps=4, seed=790, ef="polyak", mu=0.95, momentum_std=0.0)

@@ -71,7 +71,7 @@ def test_bf16_small_shapes_both_variants(m, n, r, variant):
     _free_running(w, variant=variant)
 
 
-@pytest.mark.parametrize("ef,mu", [("paper", 0.95), ("paper", 1.0), ("dion", 0.0), ("dion", 0.5)])
+@pytest.mark.parametrize("ef,mu", [("paper", 0.95), ("paper", 1.0), ("paper", 0.1), ("dion", 0.0), ("dion", 0.5), ("polyak", 0.95)])
 def test_error_feedback_forms(ef, mu):
     w = synth.Workload(f"ef-{ef}-{mu}", ((320, 448),), r=72, x_dtype="bf16", steps=3, mu=mu)
     if ef == "paper" and mu == 1.0:

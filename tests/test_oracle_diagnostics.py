@@ -9,7 +9,7 @@ from oracle.orthdion_oracle import OrthDionOracle, diagnostics, effective_rank, 
 from test_oracle_pins import jacobi_svd, rand_problem
 
 
-def test_effective_rank_closed_forms():
+def pins_effective_rank(effective_rank):
     eye = np.eye(6)
     assert abs(effective_rank(eye[:, :4] * 3.0) - 4.0) < 1e-12          # equal lengths -> r
     one = np.zeros((5, 3)); one[:, 1] = 2.0
@@ -25,6 +25,10 @@ def test_effective_rank_closed_forms():
     r = rng.standard_normal((20, 7))
     assert abs(effective_rank(r) - effective_rank(5.0 * r[:, ::-1])) < 1e-12
     assert 1.0 <= effective_rank(r) <= 7.0
+
+
+def test_effective_rank_closed_forms():
+    pins_effective_rank(effective_rank)
 
 
 def test_diagnostics_against_brute_force():
@@ -71,18 +75,74 @@ def test_diagnostics_special_cases():
     assert abs(d["inner"] - 7.0) < 1e-9                                   # Ky Fan norm: the polar factor attains it
 
 
-def test_rank_policy_hand_worked():
+def pins_rank_policy(rank_policy):
     # Alg. 2: ema = 0.5*100 + 0.5*120 = 110; target = ceil(1.1*110) = 121; clip to [8, 384]; up to 128
     ema, nxt = rank_policy(100.0, 384, 120.0, 8, 384, 0.5, 1.1)
     assert abs(ema - 110.0) < 1e-12 and nxt == 128
     # exact multiple stays; small estimates clip to r_min; large to r_max
     assert rank_policy(80.0, 96, 80.0, 8, 384, 1.0, 1.0) == (80.0, 80)
+    # the ceiling acts before the rounding: 80.5 -> 81 -> 88 (a floor would give 80)
+    assert rank_policy(80.5, 96, 80.5, 8, 384, 1.0, 1.0)[1] == 88
     assert rank_policy(1.0, 96, 1.0, 16, 384, 0.3, 1.1)[1] == 16
     assert rank_policy(900.0, 96, 900.0, 16, 384, 0.3, 1.425)[1] == 384
     # rounding up never leaves the bounds
     assert rank_policy(379.0, 384, 379.0, 8, 380, 1.0, 1.0)[1] == 380
     # alpha = 0 keeps the previous EMA
     assert rank_policy(5.0, 64, 200.0, 8, 384, 0.0, 1.1) == (200.0, 224)
+
+
+def test_rank_policy_hand_worked():
+    pins_rank_policy(rank_policy)
+
+
+def test_planted_mistakes_are_caught():
+    """Each plausible slip in the estimator or the rule fails its pins."""
+    def erank_squares(r):                       # p from squared lengths (energy) instead of lengths
+        s = np.sum(np.asarray(r, dtype=np.float64) ** 2, axis=0)
+        if s.sum() <= 0:
+            return 0.0
+        p = s / s.sum(); p = p[p > 0]
+        return float(np.exp(-np.sum(p * np.log(p))))
+
+    def erank_rows(r):                          # rows instead of columns
+        return effective_rank(np.asarray(r).T)
+
+    def erank_no_exp(r):                        # entropy itself
+        e = effective_rank(r)
+        return float(np.log(e)) if e > 0 else 0.0
+
+    for bad in (erank_squares, erank_rows, erank_no_exp):
+        with pytest.raises(AssertionError):
+            pins_effective_rank(bad)
+
+    def swap_alpha(e, r, prev, lo, hi, a, g):   # EMA weights exchanged
+        return rank_policy(e, r, prev, lo, hi, 1.0 - a, g)
+
+    def floor_target(e, r, prev, lo, hi, a, g):
+        ema = a * e + (1 - a) * prev
+        nxt = min(max(int(np.floor(g * ema)), lo), hi)
+        nxt = min(max((nxt + 7) // 8 * 8, lo), hi)
+        return ema, nxt
+
+    def round_down(e, r, prev, lo, hi, a, g):
+        ema = a * e + (1 - a) * prev
+        nxt = min(max(int(np.ceil(g * ema)), lo), hi)
+        return ema, min(max(nxt // 8 * 8, lo), hi)
+
+    def no_reclip(e, r, prev, lo, hi, a, g):
+        ema = a * e + (1 - a) * prev
+        nxt = min(max(int(np.ceil(g * ema)), lo), hi)
+        return ema, (nxt + 7) // 8 * 8
+
+    def gamma_after_clip(e, r, prev, lo, hi, a, g):
+        ema = a * e + (1 - a) * prev
+        nxt = int(np.ceil(g * min(max(ema, lo), hi)))
+        return ema, min(max((nxt + 7) // 8 * 8, lo), hi + 64)
+
+    for bad in (swap_alpha, floor_target, round_down, no_reclip, gamma_after_clip):
+        with pytest.raises(AssertionError):
+            pins_rank_policy(bad)
+            print("not caught:", bad.__name__)
 
 
 def test_resize_right_factor_small():
@@ -129,3 +189,36 @@ def test_resize_q_argument_errors():
         binding.orthdion_resize_q(256, 64, 16, 512, 32)              # growth without pad
     with pytest.raises(binding.OrthDionError):
         binding.orthdion_resize_q(256, 64, 16, 516, 8)               # misaligned destination
+
+
+def test_polyak_form_is_heavy_ball_on_the_buffer():
+    """No error feedback: with a constant gradient the buffer is the geometric series
+    B_t = G (1 + mu + ... + mu^t), whatever the factors do."""
+    x, g, _, q = rand_problem(40, 10, 12, 3)
+    mu = 0.8
+    orc = OrthDionOracle(mu=mu, variant="qr", ef="polyak")
+    mom = np.zeros_like(g)
+    for t in range(5):
+        o = orc.step(x, g, mom, q)
+        series = sum(mu ** k for k in range(t + 1))
+        assert np.max(np.abs(o["B"] - series * g)) < 1e-12
+        assert np.max(np.abs(o["M"] - mu * series * g)) < 1e-12
+        x, mom, q = o["X"], o["M"], o["Q"]
+
+
+def test_beta_sweep_residual_is_beta_times_the_lost_part():
+    """Paper-form error feedback over a sweep of beta on synthetic gradients with fresh noise
+    each step: M_new = beta (I - P P^T) B exactly (Alg. 1 line 7), so
+    ||M_new|| = beta * tracking_error * ||B|| ties the stored residual to the diagnostics."""
+    from paper_2605_16341_amd import synth
+    stream = synth.power_law_stream(48, 40, 77, out_dtype="f32", orthonormal=True)
+    st = synth.initial_state(48, 40, 8, 77, "f32", 0.0)
+    for beta in (1.0, 0.5, 0.1):
+        orc = OrthDionOracle(mu=beta, variant="qr", ef="paper")
+        x, mom, q = st.X.astype(np.float64), st.M.astype(np.float64), st.Q.astype(np.float64)
+        for t in range(6):
+            g = stream.gradient(t)
+            o = orc.step(x, g, mom, q)
+            d = diagnostics(o, mom, g)
+            assert abs(np.linalg.norm(o["M"]) - beta * d["tracking_error"] * d["b_norm"]) < 1e-10 * d["b_norm"]
+            x, mom, q = o["X"], o["M"], o["Q"]
