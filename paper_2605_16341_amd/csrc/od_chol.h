@@ -49,7 +49,9 @@ constexpr int kPTile = 3 * kPPlane;    // bytes per pre-split tile
 // LDS: Wt[2] fp32 (W_JJ^T of even / odd steps) | panel[8] pre-split T(J, K)^T | vpanel[8] pre-split V(J, I)
 constexpr int kCholOffPanel = 2 * kCTileF * 4;
 constexpr int kCholOffVPanel = kCholOffPanel + kCNT * kPTile;
-constexpr int kCholLds = kCholOffVPanel + kCNT * kPTile;
+constexpr int kCholOffSync = kCholOffVPanel + kCNT * kPTile;   // published[8] | next_ready[8] (ints)
+constexpr int kCholLds = kCholOffSync + 2 * kCNT * 4;
+constexpr int kCholSpinLimit = 1 << 22;  // bound of every wait below (never reached: the producers do not wait)
 
 #ifdef OD_CHOL_TIMING
 #define OD_TICK(slot) do { if (lane == 0) a.dbg[(z * 4 + wave) * 64 + (slot)] = wall_clock64(); } while (0)
@@ -152,6 +154,22 @@ OD_DEV void load_presplit(const char* tile, int lane, int kk, u32x4* parts) {
   for (int s = 0; s < 3; ++s) parts[s] = *reinterpret_cast<const u32x4*>(p + s * kPPlane);
 }
 
+// Producer / consumer hand-off between the waves of the workgroup through LDS words.  The
+// producer's earlier LDS writes are complete before the word changes; a consumer that has
+// seen the value may read them.  Producers never wait on consumers, so every wait ends; it
+// is bounded anyway so that a wave can always run to the end of the kernel.
+OD_DEV void lds_signal_add(int* word, int lane) {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+  if (lane == 0) __hip_atomic_fetch_add(word, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+}
+OD_DEV void lds_wait_ge(int* word, int target) {
+  for (int spins = 0; spins < kCholSpinLimit; ++spins) {
+    if (__hip_atomic_load(word, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= target) break;
+    __builtin_amdgcn_s_sleep(1);
+  }
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
+
 // ---------------------------------------------------------------------------------------
 // Diagonal tile: in-place upper Cholesky factor of the symmetric tile `d` and, in `zt`, the
 // inverse of its transpose (M = L^-1, lower triangular), both in accumulator layout.
@@ -171,9 +189,13 @@ OD_DEV f32x16 mfma_f32_k2(float a, float b, f32x16 c) {
   return __builtin_amdgcn_mfma_f32_32x32x2f32(a, b, c, 0, 0, 0);
 }
 
-OD_DEV int diag_tile_factor(f32x16& d, f32x16& zt, int lane) {
+OD_DEV int diag_tile_factor(f32x16& d_io, f32x16& zt_out, int lane) {
   const int c = lane & 31, h = lane >> 5;
   int bad = 0;
+  // `d` and `zt` are only ever changed by the matrix-core updates; the finished rows are
+  // collected on the side (a finished row of `d` / `zt` itself is never read again)
+  f32x16 d = d_io, zt;
+  float tfin[16], zfin[16];
 #pragma unroll
   for (int v = 0; v < 16; ++v) zt[v] = (acc_row(v, lane) == c) ? 1.f : 0.f;
 #pragma unroll
@@ -239,12 +261,16 @@ OD_DEV int diag_tile_factor(f32x16& d, f32x16& zt, int lane) {
       d = mfma_f32_k2(-t23v, t23v, d);
       zt = mfma_f32_k2(-t23v, z23v, zt);
     }
-    // the rows of this group are final: put them (back) in place
-    if (h == hh) {
+    // the rows of this group are final (register 4q + e of lane half hh; the other half's
+    // turn for these registers comes with the next group)
 #pragma unroll
-      for (int e = 0; e < 4; ++e) { d[4 * q + e] = tn[e]; zt[4 * q + e] = zn[e]; }
+    for (int e = 0; e < 4; ++e) {
+      if (hh == 0) { tfin[4 * q + e] = tn[e]; zfin[4 * q + e] = zn[e]; }
+      else if (h == 1) { tfin[4 * q + e] = tn[e]; zfin[4 * q + e] = zn[e]; }
     }
   }
+#pragma unroll
+  for (int v = 0; v < 16; ++v) { d_io[v] = tfin[v]; zt_out[v] = zfin[v]; }
   return bad;
 }
 
@@ -253,6 +279,8 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
   float* Wt = reinterpret_cast<float*>(lds_raw);                         // W_JJ^T, [i][k], buffer J & 1
   char* panel = lds_raw + kCholOffPanel;                                 // T(J, K)^T pre-split, one tile per K
   char* vpanel = lds_raw + kCholOffVPanel;                               // V(J, I) pre-split, one tile per I
+  int* published = reinterpret_cast<int*>(lds_raw + kCholOffSync);       // tiles of step J published so far
+  int* next_ready = published + kCNT;                                    // T(J, J+1) of step J published
 
   const int z = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -266,6 +294,7 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
   float* tg = a.t.base + (int64_t)z * a.t.stride + off;
   float* wg = a.w.base + (int64_t)z * a.w.stride + off;
   const int col = lane & 31, half = lane >> 5;
+  if (tid < 2 * kCNT) published[tid] = 0;
   OD_TICK(0);
 
   // ---- tiles strictly below the diagonal of T and W are zero and written by nobody else:
@@ -357,79 +386,94 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
     }
   };
 
+  // (b) for one owned tile of step J: T(J, K) = W_JJ^T S(J, K) (row tile) or V(J, I) = -W_JJ^T S'(J, I)
+  // (column tile), written out and published.  fp32 products (32x32x2): step (q, e) contracts
+  // over k = 8q + e (lower lane half) and 8q + 4 + e (upper half), which is exactly the row an
+  // accumulator lane keeps in register 4q + e, so the k-side operand needs no data movement
+  // and nothing is split.
+  auto panel_tile = [&](f32x16& tile, const f32x4 (&mrow)[4], int J, int I, int K, bool row_tile) {
+    const int nvr = (nb - J * kCT) < kCT ? (nb - J * kCT) : kCT;
+    // two independent accumulation chains keep the matrix core busy back to back
+    f32x16 res, res2;
+#pragma unroll
+    for (int v = 0; v < 16; ++v) { res[v] = 0.f; res2[v] = 0.f; }
+#pragma unroll
+    for (int q = 0; q < 4; q += 2)
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        res = mfma_f32_k2(mrow[q][e], tile[4 * q + e], res);
+        res2 = mfma_f32_k2(mrow[q + 1][e], tile[4 * q + 4 + e], res2);
+      }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) res[v] = row_tile ? (res[v] + res2[v]) : -(res[v] + res2[v]);
+    if (row_tile) {
+      store_presplit(panel + K * kPTile, res, lane);
+      if (K == J + 1) lds_signal_add(next_ready + J, lane);
+      lds_signal_add(published + J, lane);
+      // block orders are multiples of 8, so rows 8q .. 8q+7 are valid or not together
+      if (K * kCT + col < nb) {
+        float* tp = tg + (int64_t)(J * kCT + 4 * half) * r + K * kCT + col;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (8 * q < nvr) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) tp[(int64_t)(8 * q + e) * r] = res[4 * q + e];
+          }
+        }
+      }
+#pragma unroll
+      for (int v = 0; v < 16; ++v) tile[v] = 0.f;       // from now on the sum S'(K, J)
+    } else {
+      store_presplit(vpanel + I * kPTile, res, lane);
+      lds_signal_add(published + J, lane);
+      // W(I*32 + c, J*32 + i) = V(J, I)(i, c): four consecutive columns per store
+      if (I * kCT + col < nb) {
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          if (8 * q < nvr) {
+            const f32x4 v4 = {res[4 * q], res[4 * q + 1], res[4 * q + 2], res[4 * q + 3]};
+            *reinterpret_cast<f32x4*>(wg + (int64_t)(I * kCT + col) * r + J * kCT + 8 * q + 4 * half) = v4;
+          }
+        }
+      }
+    }
+  };
+
   if (wave == 0) do_diag(0);
   lds_barrier();
   for (int J = 0; J < nt; ++J) {
     OD_TICK(4 + 4 * J);
-    // ---- (b) row J of T and row J of V:  T(J, K) = W_JJ^T S(J, K),  V(J, I) = -W_JJ^T S'(J, I)
+    // ---- (b) row J of T and row J of V; the tile the next diagonal step waits for goes first
     const float* wt = Wt + (J & 1) * kCTileF;
-    const int nvr = (nb - J * kCT) < kCT ? (nb - J * kCT) : kCT;
-    // fp32 products (32x32x2): step (q, e) contracts over k = 8q + e (lower lane half) and
-    // 8q + 4 + e (upper half), which is exactly the row an accumulator lane keeps in register
-    // 4q + e, so the k-side operand needs no data movement and nothing is split
     f32x4 mrow[4];
 #pragma unroll
     for (int q = 0; q < 4; ++q) mrow[q] = *reinterpret_cast<const f32x4*>(wt + col * kCPitch + 8 * q + 4 * half);
 #pragma unroll
     for (int s = 0; s < kCSlots; ++s) {
       const int I = (int)(ownI >> (4 * s)) & 15, K = (int)(ownK >> (4 * s)) & 15;
-      const bool row_tile = I == J && K > J && K < nt, col_tile = K == J && I < J;
-      if (row_tile || col_tile) {
-        // two independent accumulation chains keep the matrix core busy back to back
-        f32x16 res, res2;
-#pragma unroll
-        for (int v = 0; v < 16; ++v) { res[v] = 0.f; res2[v] = 0.f; }
-#pragma unroll
-        for (int q = 0; q < 4; q += 2)
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            res = mfma_f32_k2(mrow[q][e], acc[s][4 * q + e], res);
-            res2 = mfma_f32_k2(mrow[q + 1][e], acc[s][4 * q + 4 + e], res2);
-          }
-#pragma unroll
-        for (int v = 0; v < 16; ++v) res[v] = col_tile ? -(res[v] + res2[v]) : (res[v] + res2[v]);
-        if (row_tile) {
-          store_presplit(panel + K * kPTile, res, lane);
-          // block orders are multiples of 8, so rows 8q .. 8q+7 are valid or not together
-          if (K * kCT + col < nb) {
-            float* tp = tg + (int64_t)(J * kCT + 4 * half) * r + K * kCT + col;
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              if (8 * q < nvr) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) tp[(int64_t)(8 * q + e) * r] = res[4 * q + e];
-              }
-            }
-          }
-#pragma unroll
-          for (int v = 0; v < 16; ++v) acc[s][v] = 0.f;       // from now on the sum S'(K, J)
-        } else {
-          store_presplit(vpanel + I * kPTile, res, lane);
-          // W(I*32 + c, J*32 + i) = V(J, I)(i, c): four consecutive columns per store
-          if (I * kCT + col < nb) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-              if (8 * q < nvr) {
-                const f32x4 v4 = {res[4 * q], res[4 * q + 1], res[4 * q + 2], res[4 * q + 3]};
-                *reinterpret_cast<f32x4*>(wg + (int64_t)(I * kCT + col) * r + J * kCT + 8 * q + 4 * half) = v4;
-              }
-            }
-          }
-        }
-      }
+      if (I == J && K == J + 1 && K < nt) panel_tile(acc[s], mrow, J, I, K, true);
     }
-    lds_barrier();
-    OD_TICK(5 + 4 * J);
-    // ---- (c) S(I, K) -= T(J, I)^T T(J, K) for J < I <= K;  S'(K, I) += T(J, K)^T V(J, I) for
-    // I <= J < K.  Wave 0 updates the next diagonal tile first and factors it at once.
+#pragma unroll
+    for (int s = 0; s < kCSlots; ++s) {
+      const int I = (int)(ownI >> (4 * s)) & 15, K = (int)(ownK >> (4 * s)) & 15;
+      const bool row_tile = I == J && K > J + 1 && K < nt, col_tile = K == J && I < J;
+      if (row_tile || col_tile) panel_tile(acc[s], mrow, J, I, K, row_tile);
+    }
+    // ---- wave 0: as soon as T(J, J+1) is there, update the next diagonal tile and factor
+    // it, while the other waves finish (b) and do (c)
     const bool ahead = wave == 0 && J + 1 < nt;
     if (ahead) {
+      lds_wait_ge(next_ready + J, 1);
 #pragma unroll
       for (int s = 0; s < kCNT; ++s)
         if (s == J + 1) lds_product(acc[s], panel + (J + 1) * kPTile, panel + (J + 1) * kPTile, true);
       do_diag(J + 1);
     }
     OD_TICK(6 + 4 * J);
+    // ---- (c) once all nt - 1 tiles of the step are published:
+    // S(I, K) -= T(J, I)^T T(J, K) for J < I <= K;  S'(K, I) += T(J, K)^T V(J, I) for I <= J < K
+    lds_wait_ge(published + J, nt - 1);
+    OD_TICK(5 + 4 * J);
 #pragma unroll
     for (int s = 0; s < kCSlots; ++s) {
       const int I = (int)(ownI >> (4 * s)) & 15, K = (int)(ownK >> (4 * s)) & 15;
@@ -439,7 +483,7 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
       }
     }
     OD_TICK(7 + 4 * J);
-    // next (b) reads the other Wt buffer (written above) and rewrites the panels (read above)
+    // the next step rewrites the panels and the other Wt buffer
     lds_barrier();
   }
   OD_TICK(40);
