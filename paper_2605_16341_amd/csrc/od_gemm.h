@@ -178,6 +178,54 @@ OD_DEV void gemm_mainloop(const SrcA& a, const SrcB& b, int m0, int n0, int kbeg
   }
 }
 
+// The same loop with the global loads of PF steps in flight (PF register stages per
+// operand).  For short K loops on small grids, where a workgroup cannot hide the load
+// latency behind other workgroups: the loads of step i + PF are issued before the
+// matrix-core work of step i.
+template <class T, class Num, class DirA, class SrcA, class DirB, class SrcB, int PF>
+OD_DEV void gemm_mainloop_deep(const SrcA& a, const SrcB& b, int m0, int n0, int kbeg, int kend,
+                               float scaleA, float scaleB, char* lds, f32x16 (&acc)[T::FM][T::FN]) {
+  typedef typename LoaderFor<DirA, SrcA, T::MT, T::KT, T::PITCH, T::THREADS>::type LA;
+  typedef typename LoaderFor<DirB, SrcB, T::NT, T::KT, T::PITCH, T::THREADS>::type LB;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int wm = wave / T::WN, wn = wave % T::WN;
+  constexpr int BUF = Num::PARTS * (T::PLANE_A + T::PLANE_B);
+  constexpr int OFF_B = Num::PARTS * T::PLANE_A;
+  if (kbeg >= kend) return;
+  const int nsteps = (kend - kbeg + T::KT - 1) / T::KT;
+  LA la[PF];
+  LB lb[PF];
+#pragma unroll
+  for (int p = 0; p < PF; ++p) {
+    if (p < nsteps) {
+      la[p].load(a, m0, kbeg + p * T::KT, tid);
+      lb[p].load(b, n0, kbeg + p * T::KT, tid);
+    }
+  }
+  la[0].template store<Num>(lds, T::PLANE_A, scaleA, tid);
+  lb[0].template store<Num>(lds + OFF_B, T::PLANE_B, scaleB, tid);
+  __syncthreads();
+  for (int i0 = 0; i0 < nsteps; i0 += PF) {
+#pragma unroll
+    for (int j = 0; j < PF; ++j) {
+      const int i = i0 + j;                    // step i lives in register stage j
+      if (i < nsteps) {
+        const int buf = i & 1;
+        if (i + PF < nsteps) {                 // stage j went to LDS one step ago: refill it
+          la[j].load(a, m0, kbeg + (i + PF) * T::KT, tid);
+          lb[j].load(b, n0, kbeg + (i + PF) * T::KT, tid);
+        }
+        mma_step<T, Num>(lds + buf * BUF, lds + buf * BUF + OFF_B, acc, wm, wn, lane);
+        if (i + 1 < nsteps) {
+          la[(j + 1) % PF].template store<Num>(lds + (buf ^ 1) * BUF, T::PLANE_A, scaleA, tid);
+          lb[(j + 1) % PF].template store<Num>(lds + (buf ^ 1) * BUF + OFF_B, T::PLANE_B, scaleB, tid);
+        }
+        __syncthreads();
+      }
+    }
+  }
+}
+
 template <class T>
 OD_DEV void zero_acc(f32x16 (&acc)[T::FM][T::FN]) {
 #pragma unroll

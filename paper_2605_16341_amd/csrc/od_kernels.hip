@@ -18,6 +18,7 @@ static_assert(kMaxBatchHost == kMaxBatch, "batch limit");
 typedef Tile<128, 256, 32, 2, 2> TileWide;     // r > 128: wave tile 64 x 128
 typedef Tile<128, 128, 32, 2, 2> TileSquare;   // wave tile 64 x 64
 typedef Tile<128, 64, 32, 4, 1> TileNarrow;    // r <= 64: wave tile 32 x 64
+typedef Tile<64, 64, 32, 2, 2> TileSmall;      // wave tile 32 x 32: small problems that need many workgroups
 
 constexpr float kUnitScale = 1024.f;           // scale of orthonormal / unit-column factors in fp16
 
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(T::THREADS) void k_gram(int rows, int r, WsArr a, W
   const int kbeg = split_begin(rows, splits, T::KT, split, &kend);
   f32x16 acc[T::FM][T::FN];
   zero_acc<T>(acc);
-  gemm_mainloop<T, Num, KS, SrcF32, KS, SrcF32>(s, s, tm * T::MT, tn * T::NT, kbeg, kend, 1.f, 1.f, lds, acc);
+  gemm_mainloop_deep<T, Num, KS, SrcF32, KS, SrcF32, 3>(s, s, tm * T::MT, tn * T::NT, kbeg, kend, 1.f, 1.f, lds, acc);
   float* out = part.base + (int64_t)z * part.stride + (int64_t)split * r * r;
   for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
     if (row < r && col < r) out[(int64_t)row * r + col] = v;
@@ -253,7 +254,7 @@ __global__ __launch_bounds__(T::THREADS) void k_apply(int rows, int r, WsArr a, 
   if (kend > r) kend = r;
   f32x16 acc[T::FM][T::FN];
   zero_acc<T>(acc);
-  gemm_mainloop<T, Num, KC, SrcF32, KS, SrcF32>(sa, sw, tm * T::MT, tn * T::NT, 0, kend, 1.f, 1.f, lds, acc);
+  gemm_mainloop_deep<T, Num, KC, SrcF32, KS, SrcF32, 3>(sa, sw, tm * T::MT, tn * T::NT, 0, kend, 1.f, 1.f, lds, acc);
   float* dst = to_q ? ptrs.Q[z] : out.base + (int64_t)z * out.stride;
   for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
     if (row < rows && col < r) dst[(int64_t)row * r + col] = v;
@@ -775,9 +776,8 @@ hipError_t launch_reduce_r(const ClassDims& d, WsArr part, int splits, WsArr out
   return hipSuccess;
 }
 
-template <class Num>
-static hipError_t gram_t(int nb, int rows, int r, WsArr a, WsArr part, int splits, hipStream_t st) {
-  typedef TileSquare T;
+template <class T, class Num>
+static hipError_t gram_tt(int nb, int rows, int r, WsArr a, WsArr part, int splits, hipStream_t st) {
   constexpr int lds = T::template lds_bytes<Num>();
   hipError_t e = allow_lds(k_gram<T, Num>, lds);
   if (e != hipSuccess) return e;
@@ -786,13 +786,19 @@ static hipError_t gram_t(int nb, int rows, int r, WsArr a, WsArr part, int split
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
+template <class Num>
+static hipError_t gram_t(int nb, int rows, int r, WsArr a, WsArr part, int splits, hipStream_t st) {
+  // few large tiles leave most of the chip idle: use small ones until the grid fills it
+  const int big = ((r + 127) / 128) * ((r + 127) / 128) * splits * nb;
+  if (big < 512) return gram_tt<TileSmall, Num>(nb, rows, r, a, part, splits, st);
+  return gram_tt<TileSquare, Num>(nb, rows, r, a, part, splits, st);
+}
 hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits, int exact, hipStream_t st) {
   return exact ? gram_t<NumBF<3>>(nb, rows, r, a, part, splits, st) : gram_t<NumBF<2>>(nb, rows, r, a, part, splits, st);
 }
 
-template <class Num>
-static hipError_t apply_t(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
-  typedef TileSquare T;
+template <class T, class Num>
+static hipError_t apply_tt(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
   constexpr int lds = T::template lds_bytes<Num>();
   hipError_t e = allow_lds(k_apply<T, Num>, lds);
   if (e != hipSuccess) return e;
@@ -801,6 +807,12 @@ static hipError_t apply_t(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, 
   hipLaunchKernelGGL((k_apply<T, Num>), grid, dim3(T::THREADS), lds, st, rows, r, a, w, out, ptrs ? *ptrs : none, ptrs ? 1 : 0, hn, ht);
   OD_CHECK_LAUNCH();
   return hipSuccess;
+}
+template <class Num>
+static hipError_t apply_t(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
+  const int big = ((rows + 127) / 128) * ((r + 127) / 128) * nb;
+  if (big < 512) return apply_tt<TileSmall, Num>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
+  return apply_tt<TileSquare, Num>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
 }
 hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs, HalfArr hn, HalfArr ht, int exact, hipStream_t st) {
   return exact ? apply_t<NumBF<3>>(nb, rows, r, a, w, out, q_ptrs, hn, ht, st) : apply_t<NumBF<2>>(nb, rows, r, a, w, out, q_ptrs, hn, ht, st);
