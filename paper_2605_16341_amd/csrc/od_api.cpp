@@ -264,8 +264,10 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
 
   int* info_all = reinterpret_cast<int*>(ws + h->off_info);
   float* scal_all = reinterpret_cast<float*>(ws + h->off_scal);
-  OD_TRY(od::launch_fill_int(info_all, (int64_t)nmat * od::kInfoPerMat, 0, st));
-  OD_TRY(od::launch_fill_f32(scal_all, (int64_t)nmat * od::kScalPerMat, 0.f, st));
+  if (prec != od::PREC_F16) {     // in fast precision the first kernel of every batch clears its own words
+    OD_TRY(od::launch_fill_int(info_all, (int64_t)nmat * od::kInfoPerMat, 0, st));
+    OD_TRY(od::launch_fill_f32(scal_all, (int64_t)nmat * od::kScalPerMat, 0.f, st));
+  }
   h->last_ws = workspace;
   const bool diag = h->diag_on;
   h->diag_valid = diag;
@@ -309,7 +311,7 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
 
     // Alg. 1 lines 1-2: P_raw = (M + G) Q, then P = orth(P_raw)
     OD_PHASE_BEGIN(ORTHDION_PHASE_STATS);
-    if (fast) OD_TRY(od::launch_stats(d, ptrs, scal, qht, st));
+    if (fast) OD_TRY(od::launch_stats(d, ptrs, scal, info, qht, st));
     OD_PHASE_END(ORTHDION_PHASE_STATS);
     OD_PHASE_BEGIN(ORTHDION_PHASE_PROJ);
     OD_TRY(od::launch_proj(d, ptrs, prec, scal, part, b.splits_proj, qht, st));

@@ -48,8 +48,10 @@ constexpr int kScalSample = 8;
 // breakdown column (1-based, 0 = none), [2] zero-column flag of ColNorm, [3] spare
 constexpr int kInfoPerMat = 4;
 
-// sampled sums of squares of B (for its fp16 scale) and Q as pre-scaled fp16, transposed [r][n]
-hipError_t launch_stats(const ClassDims& d, const MatPtrs& ptrs, float* scal, HalfArr qht, hipStream_t st);
+// first kernel of a step in fast precision: clears the matrices' scale words [0..7] and flag
+// words, samples sums of squares of B (for its fp16 scale) and writes Q as pre-scaled fp16,
+// transposed [r][n]
+hipError_t launch_stats(const ClassDims& d, const MatPtrs& ptrs, float* scal, int* info, HalfArr qht, hipStream_t st);
 
 // P_raw partials: part[split][m][r] = (M+G)[:, k-range] * Q[k-range, :]
 hipError_t launch_proj(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal,

@@ -49,8 +49,8 @@ OD_DEV float pow2_scale_for_rms(float ms) {
 constexpr int kStatRows = 32;      // sampled rows per matrix, one workgroup each
 
 template <class GSrc>
-__global__ __launch_bounds__(256) void k_stats(ClassDims d, MatPtrs ptrs, float* scal) {
-  const int z = blockIdx.y, tid = threadIdx.x;
+OD_DEV void stats_block(const ClassDims& d, const MatPtrs& ptrs, float* scal, int z) {
+  const int tid = threadIdx.x;
   SrcSum<GSrc> b = make_b_source<GSrc>(d, ptrs, z);
   const int nrows = d.m < kStatRows ? d.m : kStatRows;
   float acc = 0.f;
@@ -75,10 +75,10 @@ __global__ __launch_bounds__(256) void k_stats(ClassDims d, MatPtrs ptrs, float*
 }
 
 // Q (n x r fp32, the caller's state) -> pre-scaled fp16, transposed to [r][n]
-__global__ __launch_bounds__(256) void k_prep_q(ClassDims d, MatPtrs ptrs, HalfArr qht) {
+OD_DEV void prep_q_block(const ClassDims& d, const MatPtrs& ptrs, HalfArr qht, int z, int bx, int by) {
   __shared__ uint16_t tile[64][66];
-  const int z = blockIdx.z, tid = threadIdx.x;
-  const int k0 = blockIdx.x * 64, c0 = blockIdx.y * 64;       // k over n, c over r
+  const int tid = threadIdx.x;
+  const int k0 = bx * 64, c0 = by * 64;       // k over n, c over r
   const float* q = ptrs.Q[z];
   uint16_t* out = qht.base + (int64_t)z * qht.stride;
   for (int idx = tid; idx < 64 * 16; idx += 256) {            // 64 rows (k) x 16 groups of 4 columns
@@ -99,6 +99,24 @@ __global__ __launch_bounds__(256) void k_prep_q(ClassDims d, MatPtrs ptrs, HalfA
                  (uint32_t)tile[cc][kg + 2] | ((uint32_t)tile[cc][kg + 3] << 16)};
       *reinterpret_cast<u32x2*>(out + (int64_t)(c0 + cc) * d.n + k0 + kg) = h;
     }
+  }
+}
+
+// First kernel of a step in fast precision, one launch for three small jobs: workgroups
+// 0 .. kStatRows-1 of a matrix sample the scale of B (the first of them also clears the
+// matrix's flag and scale words), the others convert Q.
+template <class GSrc>
+__global__ __launch_bounds__(256) void k_prologue(ClassDims d, MatPtrs ptrs, float* scal, int* info, HalfArr qht) {
+  const int z = blockIdx.y, bx = blockIdx.x;
+  if (bx < kStatRows) {
+    if (bx == 0) {
+      if (threadIdx.x < kScalSample) scal[z * kScalPerMat + threadIdx.x] = 0.f;
+      if (threadIdx.x < kInfoPerMat) info[z * kInfoPerMat + threadIdx.x] = 0;
+    }
+    stats_block<GSrc>(d, ptrs, scal, z);
+  } else {
+    const int t = bx - kStatRows, tiles_k = (d.n + 63) / 64;
+    prep_q_block(d, ptrs, qht, z, t % tiles_k, t / tiles_k);
   }
 }
 
@@ -191,7 +209,8 @@ __global__ __launch_bounds__(256) void k_reduce(WsArr part, int splits, int64_t 
   const int64_t n4 = count / 4;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
     f32x4 s = reinterpret_cast<const f32x4*>(src)[i];
-    for (int k = 1; k < splits; ++k) {
+#pragma unroll 8
+    for (int k = 1; k < splits; ++k) {       // unrolled: the loads of eight partials are in flight together
       f32x4 v = reinterpret_cast<const f32x4*>(src + (int64_t)k * count)[i];
       s += v;
     }
@@ -209,6 +228,7 @@ __global__ __launch_bounds__(256) void k_reduce_r(ClassDims d, WsArr part, int s
   const float sr = r_scale(d, scal, z);
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
     f32x4 s = reinterpret_cast<const f32x4*>(src)[i];
+#pragma unroll 8
     for (int k = 1; k < splits; ++k) s += reinterpret_cast<const f32x4*>(src + (int64_t)k * count)[i];
     reinterpret_cast<f32x4*>(dst)[i] = s;
     u32x2 h = {pack_f16_sat(s[0] * sr, s[1] * sr), pack_f16_sat(s[2] * sr, s[3] * sr)};
@@ -362,18 +382,28 @@ __global__ __launch_bounds__(256) void k_corr(int r, WsArr part, int splits, WsA
   float* wp = w2.base + (int64_t)z * w2.stride;
   const int64_t count = (int64_t)r * r;
   float emax = 0.f;
-  for (int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x; idx < count; idx += (int64_t)gridDim.x * 256) {
-    const int i = (int)(idx / r), j = (int)(idx % r);
-    float g = 0.f;
-    for (int sp = 0; sp < splits; ++sp) g += src[(int64_t)sp * count + idx];
-    const float e = (i == j) ? g - 1.f : g;
-    emax = fmaxf(emax, fabsf(e));
-    float phi = 0.f;
-    if (j > i) phi = e;
-    else if (j == i) phi = 0.5f * e;
-    const float id = (i == j) ? 1.f : 0.f;
-    tp[idx] = id + phi;
-    wp[idx] = id - phi;
+  // four consecutive entries of one row per thread (r is a multiple of 8)
+  for (int64_t i4 = (int64_t)blockIdx.x * 256 + threadIdx.x; i4 < count / 4; i4 += (int64_t)gridDim.x * 256) {
+    const int64_t idx = i4 * 4;
+    const int i = (int)(idx / r), j0 = (int)(idx % r);
+    f32x4 g = reinterpret_cast<const f32x4*>(src)[i4];
+#pragma unroll 8
+    for (int sp = 1; sp < splits; ++sp) g += reinterpret_cast<const f32x4*>(src + (int64_t)sp * count)[i4];
+    f32x4 to, wo;
+#pragma unroll
+    for (int c = 0; c < 4; ++c) {
+      const int j = j0 + c;
+      const float e = (i == j) ? g[c] - 1.f : g[c];
+      emax = fmaxf(emax, fabsf(e));
+      float phi = 0.f;
+      if (j > i) phi = e;
+      else if (j == i) phi = 0.5f * e;
+      const float id = (i == j) ? 1.f : 0.f;
+      to[c] = id + phi;
+      wo[c] = id - phi;
+    }
+    reinterpret_cast<f32x4*>(tp)[i4] = to;
+    reinterpret_cast<f32x4*>(wp)[i4] = wo;
   }
   __shared__ float red[256];
   red[threadIdx.x] = emax;
@@ -706,11 +736,10 @@ hipError_t launch_fill_f32(float* p, int64_t count, float v, hipStream_t st) {
   return hipSuccess;
 }
 
-hipError_t launch_stats(const ClassDims& d, const MatPtrs& ptrs, float* scal, HalfArr qht, hipStream_t st) {
-  if (d.g_bf16) hipLaunchKernelGGL(k_stats<SrcBF16>, dim3(kStatRows, d.nb), dim3(256), 0, st, d, ptrs, scal);
-  else hipLaunchKernelGGL(k_stats<SrcF32>, dim3(kStatRows, d.nb), dim3(256), 0, st, d, ptrs, scal);
-  OD_CHECK_LAUNCH();
-  hipLaunchKernelGGL(k_prep_q, dim3((d.n + 63) / 64, (d.r + 63) / 64, d.nb), dim3(256), 0, st, d, ptrs, qht);
+hipError_t launch_stats(const ClassDims& d, const MatPtrs& ptrs, float* scal, int* info, HalfArr qht, hipStream_t st) {
+  const dim3 grid(kStatRows + ((d.n + 63) / 64) * ((d.r + 63) / 64), d.nb);
+  if (d.g_bf16) hipLaunchKernelGGL(k_prologue<SrcBF16>, grid, dim3(256), 0, st, d, ptrs, scal, info, qht);
+  else hipLaunchKernelGGL(k_prologue<SrcF32>, grid, dim3(256), 0, st, d, ptrs, scal, info, qht);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -896,7 +925,7 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr part, int splits, WsA
 hipError_t launch_corr(int nb, int r, WsArr part, int splits, WsArr t2, WsArr w2, float* scal, int scal_slot, int* info,
                        int info_slot, hipStream_t st) {
   int64_t count = (int64_t)r * r;
-  int blocks = (int)((count + 255) / 256);
+  int blocks = (int)((count / 4 + 255) / 256);
   if (blocks > 1024) blocks = 1024;
   hipLaunchKernelGGL(k_corr, dim3(blocks, nb), dim3(256), 0, st, r, part, splits, t2, w2, scal, scal_slot, info, info_slot);
   OD_CHECK_LAUNCH();
