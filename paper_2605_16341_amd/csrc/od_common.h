@@ -118,6 +118,8 @@ struct NumBF {
 // ---------------------------------------------------------------------------------
 struct SrcF32 {
   static constexpr bool PACKED = false;
+  static constexpr bool HAS_LOAD1 = true;
+  OD_DEV float load1(int r, int c) const { return (r < R && c < C) ? p[(int64_t)r * ld + c] : 0.f; }
   const float* p;
   int R, C;
   int64_t ld;
@@ -151,6 +153,7 @@ struct SrcF32 {
 
 struct SrcBF16 {
   static constexpr bool PACKED = false;
+  static constexpr bool HAS_LOAD1 = false;
   const uint16_t* p;
   int R, C;
   int64_t ld;
@@ -178,6 +181,7 @@ struct SrcBF16 {
 // copies them to LDS untouched.  Only read along k (load8).
 struct SrcH16 {
   static constexpr bool PACKED = true;
+  static constexpr bool HAS_LOAD1 = false;
   const uint16_t* p;
   int R, C;
   int64_t ld;
@@ -210,6 +214,7 @@ OD_DEV uint32_t pack_f16_sat(float lo, float hi) {
 template <class GSrc>
 struct SrcSum {
   static constexpr bool PACKED = false;
+  static constexpr bool HAS_LOAD1 = false;
   SrcF32 m;
   GSrc g;
   struct Raw8 { SrcF32::Raw8 a; typename GSrc::Raw8 b; };

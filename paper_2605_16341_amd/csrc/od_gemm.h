@@ -11,6 +11,8 @@
 // and written to the other LDS buffer after it, so one barrier per step suffices.
 #pragma once
 
+#include <type_traits>
+
 #include "od_common.h"
 
 namespace od {
@@ -104,15 +106,57 @@ struct LoadKS {
   }
 };
 
+// LoadKS for tiles so small that four-row items would leave most threads without work:
+// one operand row and 8 consecutive k per item, eight scalar loads (adjacent lanes read
+// adjacent rows, so a wave instruction still covers whole 256-byte segments).
+template <class Src, int ROWS, int KT, int PITCH, int THREADS>
+struct LoadKS1 {
+  static constexpr int KG = KT / 8, ITEMS = ROWS * KG, PER = (ITEMS + THREADS - 1) / THREADS;
+  float raw[PER][8];
+  OD_DEV void load(const Src& s, int row0, int k0, int tid) {
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      int item = tid + p * THREADS;
+      if (ITEMS % THREADS == 0 || item < ITEMS) {
+        int row = item % ROWS, kg = item / ROWS;
+#pragma unroll
+        for (int kk = 0; kk < 8; ++kk) raw[p][kk] = s.load1(k0 + kg * 8 + kk, row0 + row);
+      }
+    }
+  }
+  template <class Num>
+  OD_DEV void store(char* lds, int plane, float scale, int tid) const {
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      int item = tid + p * THREADS;
+      if (ITEMS % THREADS == 0 || item < ITEMS) {
+        int row = item % ROWS, kg = item / ROWS;
+        u32x4 w[Num::PARTS];
+        Num::pack(raw[p], scale, w);
+        char* dst = lds + row * PITCH + kg * 16;
+#pragma unroll
+        for (int s = 0; s < Num::PARTS; ++s) *reinterpret_cast<u32x4*>(dst + s * plane) = w[s];
+      }
+    }
+  }
+};
+
 // Loader selection by direction tag.
 struct KC {};
 struct KS {};
+struct KSF {};
 template <class Dir, class Src, int ROWS, int KT, int PITCH, int THREADS>
 struct LoaderFor;
 template <class Src, int ROWS, int KT, int PITCH, int THREADS>
 struct LoaderFor<KC, Src, ROWS, KT, PITCH, THREADS> { typedef LoadKC<Src, ROWS, KT, PITCH, THREADS> type; };
 template <class Src, int ROWS, int KT, int PITCH, int THREADS>
 struct LoaderFor<KS, Src, ROWS, KT, PITCH, THREADS> { typedef LoadKS<Src, ROWS, KT, PITCH, THREADS> type; };
+// KSF: like KS, but the one-row loader wherever four-row items would not occupy every thread
+template <class Src, int ROWS, int KT, int PITCH, int THREADS>
+struct LoaderFor<KSF, Src, ROWS, KT, PITCH, THREADS> {
+  static constexpr bool kFine = Src::HAS_LOAD1 && (ROWS / 4) * (KT / 8) < THREADS;
+  typedef typename std::conditional<kFine, LoadKS1<Src, ROWS, KT, PITCH, THREADS>, LoadKS<Src, ROWS, KT, PITCH, THREADS>>::type type;
+};
 
 // One KT-deep step of matrix-core work from the LDS tiles.
 template <class T, class Num>

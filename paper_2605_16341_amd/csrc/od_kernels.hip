@@ -18,7 +18,7 @@ static_assert(kMaxBatchHost == kMaxBatch, "batch limit");
 typedef Tile<128, 256, 32, 2, 2> TileWide;     // r > 128: wave tile 64 x 128
 typedef Tile<128, 128, 32, 2, 2> TileSquare;   // wave tile 64 x 64
 typedef Tile<128, 64, 32, 4, 1> TileNarrow;    // r <= 64: wave tile 32 x 64
-typedef Tile<64, 64, 32, 2, 2> TileSmall;      // wave tile 32 x 32: small problems that need many workgroups
+typedef Tile<64, 64, 64, 2, 2> TileSmall;      // wave tile 32 x 32: small problems that need many workgroups
 
 constexpr float kUnitScale = 1024.f;           // scale of orthonormal / unit-column factors in fp16
 
@@ -250,7 +250,7 @@ __global__ __launch_bounds__(T::THREADS) void k_gram(int rows, int r, WsArr a, W
   const int kbeg = split_begin(rows, splits, T::KT, split, &kend);
   f32x16 acc[T::FM][T::FN];
   zero_acc<T>(acc);
-  gemm_mainloop_deep<T, Num, KS, SrcF32, KS, SrcF32, 3>(s, s, tm * T::MT, tn * T::NT, kbeg, kend, 1.f, 1.f, lds, acc);
+  gemm_mainloop_deep<T, Num, KSF, SrcF32, KSF, SrcF32, 3>(s, s, tm * T::MT, tn * T::NT, kbeg, kend, 1.f, 1.f, lds, acc);
   float* out = part.base + (int64_t)z * part.stride + (int64_t)split * r * r;
   for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
     if (row < r && col < r) out[(int64_t)row * r + col] = v;
