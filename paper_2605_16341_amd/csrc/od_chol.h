@@ -4,27 +4,30 @@
 // Used by the CholeskyQR orthogonalisation (orth() of Alg. 1 lines 2 and 4): T is the
 // triangular factor of the thin QR, W turns the triangular solve into a product.
 //
-// Layout of the computation
-//   * The block is cut into 32 x 32 tiles; only tiles (I, K) with I <= K are kept, each as a
-//     matrix-core accumulator (16 registers per lane: register v of lane l is row
-//     8 (v / 4) + 4 (l / 32) + v % 4, column l % 32) owned by one wave, so the trailing
-//     matrix never leaves the register file.  Wave 0 owns the eight diagonal tiles (the
-//     serial chain), waves 1..3 share the others so that every row and column is spread.
-//   * Step J, (a): wave 0 factors the diagonal tile in place, four rows at a time.
+// Layout of the computation (7 waves: wave 3 runs the serial chain of diagonal tiles alone
+// on its SIMD, the other six are workers)
+//   * The block is cut into 32 x 32 tiles; the tiles (I, K) with I < K are kept as
+//     matrix-core accumulators (16 registers per lane: register v of lane l is row
+//     8 (v / 4) + 4 (l / 32) + v % 4, column l % 32), spread over the workers so that every
+//     row and column of tiles is shared out evenly.  The diagonal tiles wait in LDS.
+//   * Step J, (a): the diagonal wave factors tile (J, J) in place, four rows at a time.
 //     The 4 x 4 diagonal block is gathered with readlane, factored and inverted in scalar
 //     (wave-uniform) arithmetic; the new rows are a 4 x 4 product inside each lane; the
 //     rank-4 trailing update of the tile is two fp32 matrix-core products (32x32x2).  The
 //     same operations applied to an identity tile give the inverse of the tile's factor.
-//     (b): owners of the tiles (J, K) form T(J, K) = W_JJ^T S(J, K) on the matrix cores, the
-//     accumulator tile serving directly as the k-side operand, write it out and publish it
-//     to LDS already split into three bf16 terms in the operand's register order.
-//     (c): every remaining tile gets S(I, K) -= T(J, I)^T T(J, K) from those LDS operands;
-//     wave 0 updates and factors the next diagonal tile first (look-ahead).
+//     (b): the owner of tile (J, K) forms T(J, K) = W_JJ^T S(J, K) on the matrix cores (the
+//     accumulator tile serves directly as the k-side operand), writes it out, publishes it
+//     to LDS already split into three bf16 terms in the operand's register order, and
+//     subtracts T(J, K)^T T(J, K) from the waiting diagonal tile (K, K).  Tile (J, J+1) goes
+//     first: as soon as it is done the diagonal wave starts on (J+1, J+1) while the workers
+//     finish (b) and do (c).
+//     (c): every remaining tile gets S(I, K) -= T(J, I)^T T(J, K) from those LDS operands.
 //   * The inverse is built alongside, right-looking, as V = W^T (lower triangular): once
 //     T(I, K) has left its accumulator the same registers collect
 //     S'(K, I) = sum_{I <= L < K} T(L, K)^T V(L, I) in the (c) phases, and in (b) of step K
 //     V(K, I) = -W_KK^T S'(K, I) is written out and published to LDS for the rows below.
-//   * Barriers wait for LDS traffic only, so the global stores of finished tiles never stall
+//   * Waves hand tiles over through LDS words (signal / bounded wait); the one barrier per
+//     step waits for LDS traffic only, so the global stores of finished tiles never stall
 //     the loop.  Panel and inverse products use three-way split bf16 operands (six
 //     products, 24 significant bits).
 #pragma once
@@ -40,7 +43,9 @@ constexpr int kCholMax = 256;          // largest block one workgroup factors
 constexpr int kCT = 32;                // tile size
 constexpr int kCNT = kCholMax / kCT;   // 8 tiles per side
 constexpr int kCTiles = kCNT * (kCNT + 1) / 2;   // 36
-constexpr int kCSlots = kCTiles / 4;   // 9 tiles per wave
+constexpr int kCholThreads = 448;      // 7 waves
+constexpr int kCholDiagWave = 3;       // alone on its SIMD (waves 0..2 and 4..6 pair up on the other three)
+constexpr int kCSlots = 6;             // off-diagonal tiles per worker (28 over 6 workers: 4 to 6)
 constexpr int kCPitch = 36;            // floats per row of an fp32 LDS tile (16-byte aligned, conflict free)
 constexpr int kCTileF = kCT * kCPitch; // floats per fp32 LDS tile
 constexpr int kPPitch = 80;            // bytes per row of a pre-split operand tile (32 bf16 + pad)
@@ -54,7 +59,7 @@ constexpr int kCholLds = kCholOffSync + 2 * kCNT * 4;
 constexpr int kCholSpinLimit = 1 << 22;  // bound of every wait below (never reached: the producers do not wait)
 
 #ifdef OD_CHOL_TIMING
-#define OD_TICK(slot) do { if (lane == 0) a.dbg[(z * 4 + wave) * 64 + (slot)] = wall_clock64(); } while (0)
+#define OD_TICK(slot) do { if (lane == 0) a.dbg[(z * 8 + wave) * 64 + (slot)] = wall_clock64(); } while (0)
 #else
 #define OD_TICK(slot) do { } while (0)
 #endif
@@ -73,13 +78,34 @@ struct CholArgs {
 #endif
 };
 
-// tile (I, K) of slot s of wave w, four bits per slot (kept in scalar registers: a table
-// in memory would cost a dependent load per use)
-OD_DEV uint64_t own_rows(int wave) {
-  return wave == 0 ? 0x76543210ull : wave == 1 ? 0x543221100ull : wave == 2 ? 0x643321100ull : 0x543221100ull;
+// tile (I, K), I < K, of slot s of worker u, four bits per slot, 15 = no tile (kept in scalar
+// registers: a table in memory would cost a dependent load per use).  Tile (I, K) belongs
+// to worker (I + K) mod 6.
+OD_DEV uint64_t own_rows(int u) {
+  return u == 0 ? 0xff5210ull : u == 1 ? 0x632100ull : u == 2 ? 0xff3210ull : u == 3 ? 0xf43210ull : u == 4 ? 0xff4310ull : u == 5 ? 0xf54210ull : 0xffffffull;
 }
-OD_DEV uint64_t own_cols(int wave) {
-  return wave == 0 ? 0x776543210ull : wave == 1 ? 0x756745263ull : wave == 2 ? 0x767456341ull : 0x675637452ull;
+OD_DEV uint64_t own_cols(int u) {
+  return u == 0 ? 0xff7456ull : u == 1 ? 0x745671ull : u == 2 ? 0xff5672ull : u == 3 ? 0xf56723ull : u == 4 ? 0xff6734ull : u == 5 ? 0xf67345ull : 0xffffffull;
+}
+
+// A diagonal tile waiting in LDS in accumulator layout: plane q holds registers 4q .. 4q+3
+// of every lane (16 bytes per lane, conflict free).
+OD_DEV f32x16 load_dtile(const char* p, int lane) {
+  f32x16 t;
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const f32x4 v = *reinterpret_cast<const f32x4*>(p + q * 1024 + lane * 16);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) t[4 * q + e] = v[e];
+  }
+  return t;
+}
+OD_DEV void store_dtile(char* p, const f32x16& t, int lane) {
+#pragma unroll
+  for (int q = 0; q < 4; ++q) {
+    const f32x4 v = {t[4 * q], t[4 * q + 1], t[4 * q + 2], t[4 * q + 3]};
+    *reinterpret_cast<f32x4*>(p + q * 1024 + lane * 16) = v;
+  }
 }
 
 // workgroup barrier that orders LDS traffic only (outstanding global stores keep flying)
@@ -274,17 +300,20 @@ OD_DEV int diag_tile_factor(f32x16& d_io, f32x16& zt_out, int lane) {
   return bad;
 }
 
-__global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
+__global__ __launch_bounds__(kCholThreads) void k_chol256(CholArgs a) {
   extern __shared__ __align__(16) char lds_raw[];
   float* Wt = reinterpret_cast<float*>(lds_raw);                         // W_JJ^T, [i][k], buffer J & 1
   char* panel = lds_raw + kCholOffPanel;                                 // T(J, K)^T pre-split, one tile per K
-  char* vpanel = lds_raw + kCholOffVPanel;                               // V(J, I) pre-split, one tile per I
+  char* vpanel = lds_raw + kCholOffVPanel;                               // V(J, I) pre-split, one tile per I; before
+                                                                         // step I-1 ends: the waiting tile (I, I)
   int* published = reinterpret_cast<int*>(lds_raw + kCholOffSync);       // tiles of step J published so far
-  int* next_ready = published + kCNT;                                    // T(J, J+1) of step J published
+  int* next_ready = published + kCNT;                                    // tile (J+1, J+1) ready for its factorisation
 
   const int z = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const uint64_t ownI = own_rows(wave), ownK = own_cols(wave);
+  const bool diag_wave = wave == kCholDiagWave;
+  const int worker = diag_wave ? 6 : (wave < kCholDiagWave ? wave : wave - 1);
+  const uint64_t ownI = own_rows(worker), ownK = own_cols(worker);
   const int r = a.r;
   const int o = a.blk * kCholMax;
   const int nb = (r - o) < kCholMax ? (r - o) : kCholMax;     // order of this block
@@ -299,25 +328,25 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
 
   // ---- tiles strictly below the diagonal of T and W are zero and written by nobody else:
   // one tile per iteration (256 threads x 16 bytes = one 32 x 32 tile)
-  for (int I = 1; I < nt; ++I)
-  for (int K = 0; K < I; ++K) {
-    const int gi = I * kCT + (tid >> 3), gj = K * kCT + (tid & 7) * 4;
-    if (gi < nb && gj < nb) {
-      const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
-      *reinterpret_cast<f32x4*>(tg + (int64_t)gi * r + gj) = zero;
-      *reinterpret_cast<f32x4*>(wg + (int64_t)gi * r + gj) = zero;
-    }
+  if (tid < 256) {
+    for (int I = 1; I < nt; ++I)
+      for (int K = 0; K < I; ++K) {
+        const int gi = I * kCT + (tid >> 3), gj = K * kCT + (tid & 7) * 4;
+        if (gi < nb && gj < nb) {
+          const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+          *reinterpret_cast<f32x4*>(tg + (int64_t)gi * r + gj) = zero;
+          *reinterpret_cast<f32x4*>(wg + (int64_t)gi * r + gj) = zero;
+        }
+      }
   }
 
-  // ---- load: every owner reads its tiles straight into accumulator layout through the
-  // transposed element (the matrix is symmetric): lane column c needs rows 8q + 4h + {0..3}
-  // of its column, which are four consecutive entries of row c of the mirrored tile.
-  // Addresses are clamped into the block, so all loads are unconditional and in flight
-  // together; identity outside the block.
-  f32x16 acc[kCSlots];
-#pragma unroll
-  for (int s = 0; s < kCSlots; ++s) {
-    const int I = (int)(ownI >> (4 * s)) & 15, K = (int)(ownK >> (4 * s)) & 15;
+  // ---- load: every tile is read straight into accumulator layout through the transposed
+  // element (the matrix is symmetric): lane column c needs rows 8q + 4h + {0..3} of its
+  // column, which are four consecutive entries of row c of the mirrored tile.  Addresses are
+  // clamped into the block, so all loads are unconditional and in flight together; identity
+  // outside the block.
+  auto load_tile = [&](int I, int K) {
+    f32x16 t;
     const int gj = K * kCT + col, gjc = gj < nb ? gj : nb - 1;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {
@@ -326,27 +355,31 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
       f32x4 v4 = *reinterpret_cast<const f32x4*>(p);
       for (int sp = 1; sp < a.splits; ++sp) v4 += *reinterpret_cast<const f32x4*>(p + (int64_t)sp * a.split_stride);
 #pragma unroll
-      for (int e = 0; e < 4; ++e) acc[s][4 * q + e] = v4[e];
+      for (int e = 0; e < 4; ++e) t[4 * q + e] = v4[e];
     }
-  }
+#pragma unroll
+    for (int v = 0; v < 16; ++v) {
+      const int gi = I * kCT + acc_row(v, lane);
+      if (gi >= nb || gj >= nb) t[v] = (gi == gj) ? 1.f : 0.f;
+    }
+    return t;
+  };
+  f32x16 acc[kCSlots];
 #pragma unroll
   for (int s = 0; s < kCSlots; ++s) {
     const int I = (int)(ownI >> (4 * s)) & 15, K = (int)(ownK >> (4 * s)) & 15;
+    if (K < nt) acc[s] = load_tile(I, K);
+    else {
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-      const int gi = I * kCT + acc_row(v, lane), gj = K * kCT + col;
-      if (gi >= nb || gj >= nb) acc[s][v] = (gi == gj) ? 1.f : 0.f;
+      for (int v = 0; v < 16; ++v) acc[s][v] = 0.f;
     }
   }
   OD_TICK(1);
 
   // ================================ factorisation ================================
-  // (a) wave 0, tile (J, J) in slot J: factor, invert, write T_JJ and W_JJ, publish W_JJ^T
-  auto do_diag = [&](int J) {
-    f32x16 d, zt;
-#pragma unroll
-    for (int s = 0; s < kCNT; ++s)
-      if (s == J) d = acc[s];
+  // (a) tile (J, J): factor, invert, write T_JJ and W_JJ, publish W_JJ^T
+  auto do_diag = [&](int J, f32x16 d) {
+    f32x16 zt;
     const int bad = diag_tile_factor(d, zt, lane);
     if (bad != 0 && lane == 0) atomicCAS(&a.info[z * kInfoPerMat + a.info_slot], 0, o + J * kCT + bad);
     const int nv = (nb - J * kCT) < kCT ? (nb - J * kCT) : kCT;   // valid rows / cols of this tile
@@ -385,7 +418,6 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
       tile = mma6(ap, bp, tile);
     }
   };
-
   // (b) for one owned tile of step J: T(J, K) = W_JJ^T S(J, K) (row tile) or V(J, I) = -W_JJ^T S'(J, I)
   // (column tile), written out and published.  fp32 products (32x32x2): step (q, e) contracts
   // over k = 8q + e (lower lane half) and 8q + 4 + e (upper half), which is exactly the row an
@@ -407,9 +439,6 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
 #pragma unroll
     for (int v = 0; v < 16; ++v) res[v] = row_tile ? (res[v] + res2[v]) : -(res[v] + res2[v]);
     if (row_tile) {
-      store_presplit(panel + K * kPTile, res, lane);
-      if (K == J + 1) lds_signal_add(next_ready + J, lane);
-      lds_signal_add(published + J, lane);
       // block orders are multiples of 8, so rows 8q .. 8q+7 are valid or not together
       if (K * kCT + col < nb) {
         float* tp = tg + (int64_t)(J * kCT + 4 * half) * r + K * kCT + col;
@@ -421,8 +450,16 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
           }
         }
       }
+      store_presplit(panel + K * kPTile, res, lane);
 #pragma unroll
       for (int v = 0; v < 16; ++v) tile[v] = 0.f;       // from now on the sum S'(K, J)
+      // the waiting diagonal tile (K, K) -= T(J, K)^T T(J, K), operands read back from the panel
+      char* dk = vpanel + K * kPTile;
+      f32x16 dt = load_dtile(dk, lane);
+      lds_product(dt, panel + K * kPTile, panel + K * kPTile, true);
+      store_dtile(dk, dt, lane);
+      if (K == J + 1) lds_signal_add(next_ready + J, lane);
+      lds_signal_add(published + J, lane);
     } else {
       store_presplit(vpanel + I * kPTile, res, lane);
       lds_signal_add(published + J, lane);
@@ -439,47 +476,51 @@ __global__ __launch_bounds__(256) void k_chol256(CholArgs a) {
     }
   };
 
-  if (wave == 0) do_diag(0);
+  if (diag_wave) {
+    // the diagonal tiles: (0, 0) is factored at once, the others wait in LDS for their updates
+    for (int I = 1; I < nt; ++I) store_dtile(vpanel + I * kPTile, load_tile(I, I), lane);
+    do_diag(0, load_tile(0, 0));
+  }
   lds_barrier();
   for (int J = 0; J < nt; ++J) {
     OD_TICK(4 + 4 * J);
-    // ---- (b) row J of T and row J of V; the tile the next diagonal step waits for goes first
-    const float* wt = Wt + (J & 1) * kCTileF;
-    f32x4 mrow[4];
+    if (diag_wave) {
+      // ---- as soon as tile (J+1, J+1) has its last update, factor it
+      if (J + 1 < nt) {
+        lds_wait_ge(next_ready + J, 1);
+        OD_TICK(5 + 4 * J);
+        do_diag(J + 1, load_dtile(vpanel + (J + 1) * kPTile, lane));
+      }
+      OD_TICK(6 + 4 * J);
+    } else {
+      // ---- (b) row J of T and row J of V; the tile the diagonal wave waits for goes first
+      const float* wt = Wt + (J & 1) * kCTileF;
+      f32x4 mrow[4];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) mrow[q] = *reinterpret_cast<const f32x4*>(wt + col * kCPitch + 8 * q + 4 * half);
+      for (int q = 0; q < 4; ++q) mrow[q] = *reinterpret_cast<const f32x4*>(wt + col * kCPitch + 8 * q + 4 * half);
 #pragma unroll
-    for (int s = 0; s < kCSlots; ++s) {
-      const int I = (int)(ownI >> (4 * s)) & 15, K = (int)(ownK >> (4 * s)) & 15;
-      if (I == J && K == J + 1 && K < nt) panel_tile(acc[s], mrow, J, I, K, true);
-    }
+      for (int s = 0; s < kCSlots; ++s) {
+        const int I = (int)(ownI >> (4 * s)) & 15, K = (int)(ownK >> (4 * s)) & 15;
+        if (I == J && K == J + 1 && K < nt) panel_tile(acc[s], mrow, J, I, K, true);
+      }
 #pragma unroll
-    for (int s = 0; s < kCSlots; ++s) {
-      const int I = (int)(ownI >> (4 * s)) & 15, K = (int)(ownK >> (4 * s)) & 15;
-      const bool row_tile = I == J && K > J + 1 && K < nt, col_tile = K == J && I < J;
-      if (row_tile || col_tile) panel_tile(acc[s], mrow, J, I, K, row_tile);
-    }
-    // ---- wave 0: as soon as T(J, J+1) is there, update the next diagonal tile and factor
-    // it, while the other waves finish (b) and do (c)
-    const bool ahead = wave == 0 && J + 1 < nt;
-    if (ahead) {
-      lds_wait_ge(next_ready + J, 1);
+      for (int s = 0; s < kCSlots; ++s) {
+        const int I = (int)(ownI >> (4 * s)) & 15, K = (int)(ownK >> (4 * s)) & 15;
+        const bool row_tile = I == J && K > J + 1 && K < nt, col_tile = K == J && I < J;
+        if (row_tile || col_tile) panel_tile(acc[s], mrow, J, I, K, row_tile);
+      }
+      OD_TICK(5 + 4 * J);
+      // ---- (c) once all nt - 1 tiles of the step are published:
+      // S(I, K) -= T(J, I)^T T(J, K) for J < I < K;  S'(K, I) += T(J, K)^T V(J, I) for I <= J < K
+      lds_wait_ge(published + J, nt - 1);
+      OD_TICK(6 + 4 * J);
 #pragma unroll
-      for (int s = 0; s < kCNT; ++s)
-        if (s == J + 1) lds_product(acc[s], panel + (J + 1) * kPTile, panel + (J + 1) * kPTile, true);
-      do_diag(J + 1);
-    }
-    OD_TICK(6 + 4 * J);
-    // ---- (c) once all nt - 1 tiles of the step are published:
-    // S(I, K) -= T(J, I)^T T(J, K) for J < I <= K;  S'(K, I) += T(J, K)^T V(J, I) for I <= J < K
-    lds_wait_ge(published + J, nt - 1);
-    OD_TICK(5 + 4 * J);
-#pragma unroll
-    for (int s = 0; s < kCSlots; ++s) {
-      const int I = (int)(ownI >> (4 * s)) & 15, K = (int)(ownK >> (4 * s)) & 15;
-      if (K > J && K < nt && !(ahead && I == J + 1 && K == J + 1)) {
-        if (I > J) lds_product(acc[s], panel + I * kPTile, panel + K * kPTile, true);
-        else lds_product(acc[s], panel + K * kPTile, vpanel + I * kPTile, false);
+      for (int s = 0; s < kCSlots; ++s) {
+        const int I = (int)(ownI >> (4 * s)) & 15, K = (int)(ownK >> (4 * s)) & 15;
+        if (K > J && K < nt) {
+          if (I > J) lds_product(acc[s], panel + I * kPTile, panel + K * kPTile, true);
+          else lds_product(acc[s], panel + K * kPTile, vpanel + I * kPTile, false);
+        }
       }
     }
     OD_TICK(7 + 4 * J);

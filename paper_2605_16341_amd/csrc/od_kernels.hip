@@ -877,7 +877,7 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr part, int splits, WsA
   ca.src = gram; ca.splits = 1; ca.split_stride = 0;
   if (nblk == 1) {
     ca.blk = 0;
-    hipLaunchKernelGGL(k_chol256, dim3(nb), dim3(256), kCholLds, st, ca);
+    hipLaunchKernelGGL(k_chol256, dim3(nb), dim3(kCholThreads), kCholLds, st, ca);
     OD_CHECK_LAUNCH();
     return hipSuccess;
   }
@@ -889,7 +889,7 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr part, int splits, WsA
   const int exact = 1;
   for (int p = 0; p < nblk; ++p) {
     ca.blk = p;
-    hipLaunchKernelGGL(k_chol256, dim3(nb), dim3(256), kCholLds, st, ca);
+    hipLaunchKernelGGL(k_chol256, dim3(nb), dim3(kCholThreads), kCholLds, st, ca);
     OD_CHECK_LAUNCH();
     if (p + 1 == nblk) break;
     const int o = p * kLeaf, o1 = (p + 1) * kLeaf, rest = r - o1;
