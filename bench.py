@@ -240,6 +240,7 @@ def main():
         print(f"bench.py: numerical breakdown flagged: {info}", file=sys.stderr)
         sys.exit(3)
 
+    fast_path = args.precision == "fast" or (args.precision == "auto" and w.x_dtype == "bf16")
     dom_ms_per_step = dom[0] / K                   # all launches of the kernel in one step
     launches_per_step = dom[1] // K
     nbytes, flops = algorithmic_work(w, dominant)
@@ -266,7 +267,7 @@ def main():
                    "elements": w.elements},
         "roofline": {"bound": "hbm" if hbm_bound else "mfma", "achieved": achieved, "peak": peak, "unit": unit,
                      "frac": achieved / peak, "traffic": traffic, "kernel": {"proj": "k_proj", "back": "k_back",
-                                                                              "efx": "k_efx"}[dominant],
+                                                                              "efx": "k_efx_h" if fast_path else "k_efx"}[dominant],
                      "kernel_ms_per_launch": dom_ms_per_step / max(launches_per_step, 1),
                      "launches_per_step": launches_per_step,
                      "algorithmic_bytes_per_step": nbytes, "algorithmic_flops_per_step": flops},

@@ -135,7 +135,9 @@ int orthdion_workspace_layout(orthdion_handle h, int32_t index, size_t* off_p, s
 
 /* Optional timing of the phases of orthdion_step with HIP events recorded on the step's
  * own stream (host-side resources only; do not use while the stream is being captured into
- * a graph).  A phase with one kernel (PROJ, BACK, EFX) is exactly that kernel's launch.
+ * a graph).  A phase with one kernel (PROJ, BACK, EFX) is timed by that dispatch's own start
+ * and stop time stamps (the figure a kernel trace reports), the others between two recorded
+ * events.
  *   orthdion_profile_begin  brackets every phase whose bit (1u << phase) is set in
  *                           phase_mask, for the next max_steps calls of orthdion_step.
  *   orthdion_profile_end    waits for the recorded events, then writes, per phase, the summed

@@ -284,6 +284,14 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     if (hipEvent_t* e_ = prof_slot(h, bi, ph, 1)) OD_TRY(hipEventRecord(*e_, st)); \
   } while (0)
 
+  // phases that are one kernel: the kernel's own start / stop time stamps
+#define OD_PHASE_KERNEL(ph)                                                  \
+  do {                                                                       \
+    hipEvent_t* e0_ = prof_slot(h, bi, ph, 0);                               \
+    hipEvent_t* e1_ = prof_slot(h, bi, ph, 1);                               \
+    if (e0_ && e1_) od::time_next_launch(*e0_, *e1_);                        \
+  } while (0)
+
   for (int bi = 0; bi < (int)h->batches.size(); ++bi) {
     const Batch& b = h->batches[bi];
     const ClassDims& d = b.d;
@@ -313,9 +321,8 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     OD_PHASE_BEGIN(ORTHDION_PHASE_STATS);
     if (fast) OD_TRY(od::launch_stats(d, ptrs, scal, info, qht, st));
     OD_PHASE_END(ORTHDION_PHASE_STATS);
-    OD_PHASE_BEGIN(ORTHDION_PHASE_PROJ);
+    OD_PHASE_KERNEL(ORTHDION_PHASE_PROJ);
     OD_TRY(od::launch_proj(d, ptrs, prec, scal, part, b.splits_proj, qht, st));
-    OD_PHASE_END(ORTHDION_PHASE_PROJ);
     OD_PHASE_BEGIN(ORTHDION_PHASE_PROJ_REDUCE);
     OD_TRY(od::launch_reduce(d.nb, part, b.splits_proj, (int64_t)d.m * d.r, pa, st));
     OD_PHASE_END(ORTHDION_PHASE_PROJ_REDUCE);
@@ -325,9 +332,8 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     if (rc != ORTHDION_OK) return rc;
     OD_PHASE_END(ORTHDION_PHASE_ORTH_LEFT);
     // line 3: R = (M + G)^T P
-    OD_PHASE_BEGIN(ORTHDION_PHASE_BACK);
+    OD_PHASE_KERNEL(ORTHDION_PHASE_BACK);
     OD_TRY(od::launch_back(d, ptrs, prec, scal, pa, part, b.splits_back, pht, st));
-    OD_PHASE_END(ORTHDION_PHASE_BACK);
     OD_PHASE_BEGIN(ORTHDION_PHASE_BACK_REDUCE);
     if (fast) OD_TRY(od::launch_reduce_r(d, part, b.splits_back, ra, rh, scal, st));
     else OD_TRY(od::launch_reduce(d.nb, part, b.splits_back, (int64_t)d.n * d.r, ra, st));
@@ -357,10 +363,9 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
                                    diag_all + (size_t)b.slot_base * od::kDiagPerMat, st));
     }
     // lines 5-7: parameter update and error feedback in one pass
-    OD_PHASE_BEGIN(ORTHDION_PHASE_EFX);
+    OD_PHASE_KERNEL(ORTHDION_PHASE_EFX);
     if (fast) OD_TRY(od::launch_efx_h(d, ptrs, scal, ph, rh, qh, a_coef, b_coef, h->cfg.lr, st));
     else OD_TRY(od::launch_efx(d, ptrs, prec, scal, pa, ra, a_coef, b_coef, h->cfg.lr, st));
-    OD_PHASE_END(ORTHDION_PHASE_EFX);
   }
   if (h->prof_on && h->prof_steps < h->prof_max_steps) h->prof_steps++;
   return ORTHDION_OK;

@@ -126,6 +126,10 @@ hipError_t launch_diag_final(int nb, const double* dpart, const double* dacc, in
 // q_new (n x r_new) = leading min(r_old, r_new) columns of q_old, then columns of pad (n x (r_new - r_old))
 hipError_t launch_resize_q(const float* q_old, int64_t n, int r_old, float* q_new, int r_new, const float* pad, hipStream_t st);
 
+// The next launch_proj / launch_back / launch_efx / launch_efx_h of this thread records the
+// start and stop time stamps of its kernel in the two events (one shot).
+void time_next_launch(hipEvent_t start, hipEvent_t stop);
+
 hipError_t launch_fill_int(int* p, int64_t count, int value, hipStream_t st);
 hipError_t launch_fill_f32(float* p, int64_t count, float value, hipStream_t st);
 

@@ -5,6 +5,8 @@
 // ColNorm(R) (line 4), X -= lr P Q^T (lines 5-6), M = a B - b P R^T (line 7).
 #include "od_kernels.h"
 
+#include <hip/hip_ext.h>
+
 #include "od_chol.h"
 #include "od_gemm.h"
 
@@ -712,6 +714,23 @@ __global__ __launch_bounds__(512, 2) void k_efx_h(ClassDims d, MatPtrs ptrs, con
     if (e_ != hipSuccess) return e_;            \
   } while (0)
 
+// One-shot timing of the next streaming kernel (projection, back-projection, error feedback):
+// the events receive the start and stop time stamps of the dispatch itself, without the
+// gaps around separately recorded events.
+static thread_local hipEvent_t g_time_start = nullptr, g_time_stop = nullptr;
+void time_next_launch(hipEvent_t start, hipEvent_t stop) { g_time_start = start; g_time_stop = stop; }
+
+template <class K, class... Args>
+static void launch_timed(K kernel, dim3 grid, dim3 block, int lds, hipStream_t st, Args... args) {
+  if (g_time_start != nullptr) {
+    hipExtLaunchKernelGGL(kernel, grid, block, (uint32_t)lds, st, g_time_start, g_time_stop, 0u, args...);
+    g_time_start = nullptr;
+    g_time_stop = nullptr;
+  } else {
+    hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
+  }
+}
+
 template <class K>
 static hipError_t allow_lds(K kernel, int bytes) {
   if (bytes > 64 * 1024) return hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize, bytes);
@@ -750,7 +769,7 @@ static hipError_t proj_t(const ClassDims& d, const MatPtrs& ptrs, const float* s
   hipError_t e = allow_lds(k_proj<T, Num, GSrc>, lds);
   if (e != hipSuccess) return e;
   dim3 grid(((d.m + T::MT - 1) / T::MT) * ((d.r + T::NT - 1) / T::NT), splits, d.nb);
-  hipLaunchKernelGGL((k_proj<T, Num, GSrc>), grid, dim3(T::THREADS), lds, st, d, ptrs, scal, part, splits, qht);
+  launch_timed(k_proj<T, Num, GSrc>, grid, dim3(T::THREADS), lds, st, d, ptrs, scal, part, splits, qht);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -771,7 +790,7 @@ static hipError_t back_t(const ClassDims& d, const MatPtrs& ptrs, const float* s
   hipError_t e = allow_lds(k_back<T, Num, GSrc>, lds);
   if (e != hipSuccess) return e;
   dim3 grid(((d.n + T::MT - 1) / T::MT) * ((d.r + T::NT - 1) / T::NT), splits, d.nb);
-  hipLaunchKernelGGL((k_back<T, Num, GSrc>), grid, dim3(T::THREADS), lds, st, d, ptrs, scal, p, part, splits, pht);
+  launch_timed(k_back<T, Num, GSrc>, grid, dim3(T::THREADS), lds, st, d, ptrs, scal, p, part, splits, pht);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -960,7 +979,7 @@ static hipError_t efx_t(const ClassDims& d, const MatPtrs& ptrs, const float* sc
   hipError_t e = allow_lds(k_efx<T, Num, XBF, GBF>, lds);
   if (e != hipSuccess) return e;
   dim3 grid(((d.m + T::NT - 1) / T::NT) * ((d.n + T::MT - 1) / T::MT), 1, d.nb);
-  hipLaunchKernelGGL((k_efx<T, Num, XBF, GBF>), grid, dim3(T::THREADS), lds, st, d, ptrs, scal, p, rr, a_coef, b_coef, lr);
+  launch_timed(k_efx<T, Num, XBF, GBF>, grid, dim3(T::THREADS), lds, st, d, ptrs, scal, p, rr, a_coef, b_coef, lr);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -977,7 +996,7 @@ static hipError_t efx_h_t(const ClassDims& d, const MatPtrs& ptrs, const float* 
                           float a_coef, float b_coef, float lr, hipStream_t st) {
   constexpr int lds = 2 * 3 * 128 * 80;
   dim3 grid(((d.m + 127) / 128) * ((d.n + 127) / 128), 1, d.nb);
-  hipLaunchKernelGGL((k_efx_h<XBF, GBF>), grid, dim3(512), lds, st, d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr);
+  launch_timed(k_efx_h<XBF, GBF>, grid, dim3(512), lds, st, d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
