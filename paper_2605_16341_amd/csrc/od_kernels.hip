@@ -355,7 +355,7 @@ __global__ __launch_bounds__(T::THREADS) void k_sgemm(SgemmArgs g) {
   SrcF32 sb = sub_view(bp, g.r, g.b_k0 + o, g.b_c0 + o, g.Kc, g.Nc);
   f32x16 acc[T::FM][T::FN];
   zero_acc<T>(acc);
-  gemm_mainloop<T, Num, DirA, SrcF32, KS, SrcF32>(sa, sb, tm * T::MT, tn * T::NT, 0, g.Kc, 1.f, 1.f, lds, acc);
+  gemm_mainloop_deep<T, Num, DirA, SrcF32, KSF, SrcF32, 3>(sa, sb, tm * T::MT, tn * T::NT, 0, g.Kc, 1.f, 1.f, lds, acc);
   const int cr = g.c_r0 + o, cc = g.c_c0 + o;
   for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
     if (row < g.Mc && col < g.Nc && cr + row < g.r && cc + col < g.r) {
@@ -866,9 +866,8 @@ hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, co
   return exact ? apply_t<NumBF<3>>(nb, rows, r, a, w, out, q_ptrs, hn, ht, st) : apply_t<NumBF<2>>(nb, rows, r, a, w, out, q_ptrs, hn, ht, st);
 }
 
-template <class Num, class DirA>
-static hipError_t sgemm_t(int nb, const SgemmArgs& g, hipStream_t st) {
-  typedef TileSquare T;
+template <class T, class Num, class DirA>
+static hipError_t sgemm_tt(int nb, const SgemmArgs& g, hipStream_t st) {
   constexpr int lds = T::template lds_bytes<Num>();
   hipError_t e = allow_lds(k_sgemm<T, Num, DirA>, lds);
   if (e != hipSuccess) return e;
@@ -877,10 +876,16 @@ static hipError_t sgemm_t(int nb, const SgemmArgs& g, hipStream_t st) {
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
+template <class Num, class DirA>
+static hipError_t sgemm_t(int nb, const SgemmArgs& g, hipStream_t st) {
+  const int big = ((g.Mc + 127) / 128) * ((g.Nc + 127) / 128) * nb * g.nq;
+  if (big < 512) return sgemm_tt<TileSmall, Num, DirA>(nb, g, st);
+  return sgemm_tt<TileSquare, Num, DirA>(nb, g, st);
+}
 static hipError_t sgemm(int nb, const SgemmArgs& g, bool a_kc, int exact, hipStream_t st) {
   if (g.Mc <= 0 || g.Nc <= 0 || g.Kc <= 0 || g.nq <= 0) return hipSuccess;
-  if (exact) return a_kc ? sgemm_t<NumBF<3>, KC>(nb, g, st) : sgemm_t<NumBF<3>, KS>(nb, g, st);
-  return a_kc ? sgemm_t<NumBF<2>, KC>(nb, g, st) : sgemm_t<NumBF<2>, KS>(nb, g, st);
+  if (exact) return a_kc ? sgemm_t<NumBF<3>, KC>(nb, g, st) : sgemm_t<NumBF<3>, KSF>(nb, g, st);
+  return a_kc ? sgemm_t<NumBF<2>, KC>(nb, g, st) : sgemm_t<NumBF<2>, KSF>(nb, g, st);
 }
 
 hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr part, int splits, WsArr t, WsArr w, WsArr tmp, int* info,
