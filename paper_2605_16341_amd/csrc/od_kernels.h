@@ -77,8 +77,8 @@ hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, co
 // W = T^-1, both upper triangular with zeros below the diagonal.  For r <= 256 one workgroup
 // per matrix does everything; above, `gram` receives the reduced matrix (destroyed) and the
 // factorisation is blocked, `tmp` being r x r scratch.  A non-positive or non-finite pivot
-// writes its 1-based column to info[mat * kInfoPerMat + info_slot] (first failure wins) and
-// the factorisation goes on with that pivot replaced by 1.
+// writes its 1-based column to info[mat * kInfoPerMat + info_slot] (first failure wins); the
+// factors of such a matrix are unspecified (they may hold NaN).
 hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr part, int splits, WsArr t, WsArr w, WsArr tmp, int* info,
                           int info_slot, hipStream_t st);
 
