@@ -155,7 +155,10 @@ extern "C" int orthdion_create(orthdion_handle* out, const orthdion_matdesc* mat
     const int64_t m = d.m, n = d.n, r = d.r;
     const int nt = r <= 64 ? 64 : (r <= 128 ? 128 : 256);
     const int64_t tiles_r = (r + nt - 1) / nt;
-    b.splits_proj = pick_splits(((m + 127) / 128) * tiles_r, d.nb, n, 128);
+    // the projection's fast-precision kernel for r > 128 works on 64-row panels: as many
+    // workgroups from half the splits, hence half the partial sums to write and add up
+    const int proj_rows = (resolve_prec(*cfg) == od::PREC_F16 && od::proj_uses_flat_tiles((int)m, (int)r, d.nb)) ? 64 : 128;
+    b.splits_proj = pick_splits(((m + proj_rows - 1) / proj_rows) * tiles_r, d.nb, n, 128);
     b.splits_back = pick_splits(((n + 127) / 128) * tiles_r, d.nb, m, 128);
     const int64_t gt = ((r + 127) / 128) * ((r + 127) / 128);
     b.splits_gram_p = pick_splits(gt, d.nb, m, 256);

@@ -53,6 +53,9 @@ constexpr int kInfoPerMat = 4;
 // transposed [r][n]
 hipError_t launch_stats(const ClassDims& d, const MatPtrs& ptrs, float* scal, int* info, HalfArr qht, hipStream_t st);
 
+// whether launch_proj (fast precision) works on 64-row tiles for this shape class: the
+// caller sizes the number of splits accordingly
+bool proj_uses_flat_tiles(int m, int r, int nb);
 // P_raw partials: part[split][m][r] = (M+G)[:, k-range] * Q[k-range, :]
 hipError_t launch_proj(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal,
                        WsArr part, int splits, HalfArr qht, hipStream_t st);

@@ -20,6 +20,7 @@ static_assert(kMaxBatchHost == kMaxBatch, "batch limit");
 typedef Tile<128, 256, 32, 2, 2> TileWide;     // r > 128: wave tile 64 x 128
 typedef Tile<128, 128, 32, 2, 2> TileSquare;   // wave tile 64 x 64
 typedef Tile<128, 64, 32, 4, 1> TileNarrow;    // r <= 64: wave tile 32 x 64
+typedef Tile<64, 256, 32, 2, 2> TileFlat;      // projection, r > 128: twice the row panels, half the splits (wave tile 32 x 128)
 typedef Tile<64, 64, 64, 2, 2> TileSmall;      // wave tile 32 x 32: small problems that need many workgroups
 
 constexpr float kUnitScale = 1024.f;           // scale of orthonormal / unit-column factors in fp16
@@ -773,11 +774,17 @@ static hipError_t proj_t(const ClassDims& d, const MatPtrs& ptrs, const float* s
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
+// Few wide tiles need many splits to fill the chip; 64-row tiles get there with half of them,
+// i.e. half the partial sums to write and to add up.  With enough tiles the wide one wins.
+bool proj_uses_flat_tiles(int m, int r, int nb) {
+  return r > 128 && (int64_t)((m + 127) / 128) * ((r + 255) / 256) * nb < 256;
+}
 template <class GSrc>
 static hipError_t proj_g(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr part, int splits, HalfArr qht, hipStream_t st) {
   if (prec == PREC_BF3) return proj_t<TileSquare, NumBF<3>, GSrc>(d, ptrs, scal, part, splits, qht, st);
   if (d.r <= 64) return proj_t<TileNarrow, NumF16, GSrc>(d, ptrs, scal, part, splits, qht, st);
   if (d.r <= 128) return proj_t<TileSquare, NumF16, GSrc>(d, ptrs, scal, part, splits, qht, st);
+  if (proj_uses_flat_tiles(d.m, d.r, d.nb)) return proj_t<TileFlat, NumF16, GSrc>(d, ptrs, scal, part, splits, qht, st);
   return proj_t<TileWide, NumF16, GSrc>(d, ptrs, scal, part, splits, qht, st);
 }
 hipError_t launch_proj(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr part, int splits, HalfArr qht, hipStream_t st) {
