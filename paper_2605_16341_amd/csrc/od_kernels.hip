@@ -264,7 +264,7 @@ __global__ __launch_bounds__(T::THREADS) void k_gram(int rows, int r, WsArr a, W
 // out = A W with W upper triangular (the triangular solve of CholeskyQR as a product
 // with the explicit inverse factor)
 // ------------------------------------------------------------------------------------
-template <class T, class Num>
+template <class T, class Num, bool DEEP>
 __global__ __launch_bounds__(T::THREADS) void k_apply(int rows, int r, WsArr a, WsArr w, WsArr out, MatPtrs ptrs, int to_q,
                                                       HalfArr hn, HalfArr ht) {
   extern __shared__ __align__(16) char lds[];
@@ -277,7 +277,8 @@ __global__ __launch_bounds__(T::THREADS) void k_apply(int rows, int r, WsArr a, 
   if (kend > r) kend = r;
   f32x16 acc[T::FM][T::FN];
   zero_acc<T>(acc);
-  gemm_mainloop_deep<T, Num, KC, SrcF32, KS, SrcF32, 3>(sa, sw, tm * T::MT, tn * T::NT, 0, kend, 1.f, 1.f, lds, acc);
+  if constexpr (DEEP) gemm_mainloop_deep<T, Num, KC, SrcF32, KS, SrcF32, 3>(sa, sw, tm * T::MT, tn * T::NT, 0, kend, 1.f, 1.f, lds, acc);
+  else gemm_mainloop<T, Num, KC, SrcF32, KS, SrcF32>(sa, sw, tm * T::MT, tn * T::NT, 0, kend, 1.f, 1.f, lds, acc);
   float* dst = to_q ? ptrs.Q[z] : out.base + (int64_t)z * out.stride;
   for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
     if (row < rows && col < r) dst[(int64_t)row * r + col] = v;
@@ -428,6 +429,17 @@ __global__ __launch_bounds__(256) void k_corr(int r, WsArr part, int splits, WsA
 // ------------------------------------------------------------------------------------
 // small helpers
 // ------------------------------------------------------------------------------------
+// zero the r x r matrices of two per-matrix workspace arrays, all matrices in one launch
+__global__ __launch_bounds__(256) void k_zero_pair(WsArr a, WsArr b, int64_t count) {
+  const int z = blockIdx.y;
+  f32x4* pa = reinterpret_cast<f32x4*>(a.base + (int64_t)z * a.stride);
+  f32x4* pb = reinterpret_cast<f32x4*>(b.base + (int64_t)z * b.stride);
+  const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
+  for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count / 4; i += (int64_t)gridDim.x * 256) {
+    pa[i] = zero;
+    pb[i] = zero;
+  }
+}
 __global__ __launch_bounds__(256) void k_fill_f32(float* p, int64_t count, float v) {
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < count; i += (int64_t)gridDim.x * 256) p[i] = v;
 }
@@ -852,22 +864,23 @@ hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits,
   return exact ? gram_t<NumBF<3>>(nb, rows, r, a, part, splits, st) : gram_t<NumBF<2>>(nb, rows, r, a, part, splits, st);
 }
 
-template <class T, class Num>
+template <class T, class Num, bool DEEP>
 static hipError_t apply_tt(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
   constexpr int lds = T::template lds_bytes<Num>();
-  hipError_t e = allow_lds(k_apply<T, Num>, lds);
+  hipError_t e = allow_lds(k_apply<T, Num, DEEP>, lds);
   if (e != hipSuccess) return e;
   MatPtrs none = {};
   dim3 grid(((rows + T::MT - 1) / T::MT) * ((r + T::NT - 1) / T::NT), 1, nb);
-  hipLaunchKernelGGL((k_apply<T, Num>), grid, dim3(T::THREADS), lds, st, rows, r, a, w, out, ptrs ? *ptrs : none, ptrs ? 1 : 0, hn, ht);
+  hipLaunchKernelGGL((k_apply<T, Num, DEEP>), grid, dim3(T::THREADS), lds, st, rows, r, a, w, out, ptrs ? *ptrs : none, ptrs ? 1 : 0, hn, ht);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
 template <class Num>
 static hipError_t apply_t(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
   const int big = ((rows + 127) / 128) * ((r + 127) / 128) * nb;
-  if (big < 512) return apply_tt<TileSmall, Num>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
-  return apply_tt<TileSquare, Num>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
+  if (big < 512) return apply_tt<TileSmall, Num, true>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
+  if (Num::PARTS <= 2 && r >= 256) return apply_tt<TileWide, Num, false>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
+  return apply_tt<TileSquare, Num, false>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
 }
 hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs, HalfArr hn, HalfArr ht, int exact, hipStream_t st) {
   return exact ? apply_t<NumBF<3>>(nb, rows, r, a, w, out, q_ptrs, hn, ht, st) : apply_t<NumBF<2>>(nb, rows, r, a, w, out, q_ptrs, hn, ht, st);
@@ -913,9 +926,12 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr part, int splits, WsA
     return hipSuccess;
   }
   // lower block triangles of T and W are never written below; clear them once
-  for (int z = 0; z < nb; ++z) {
-    if ((e = launch_fill_f32(t.base + (int64_t)z * t.stride, (int64_t)r * r, 0.f, st)) != hipSuccess) return e;
-    if ((e = launch_fill_f32(w.base + (int64_t)z * w.stride, (int64_t)r * r, 0.f, st)) != hipSuccess) return e;
+  {
+    const int64_t count = (int64_t)r * r;          // a multiple of 64
+    int blocks = (int)((count / 4 + 255) / 256);
+    if (blocks > 256) blocks = 256;
+    hipLaunchKernelGGL(k_zero_pair, dim3(blocks, nb), dim3(256), 0, st, t, w, count);
+    OD_CHECK_LAUNCH();
   }
   const int exact = 1;
   for (int p = 0; p < nblk; ++p) {
