@@ -40,6 +40,16 @@ OD_DEV f32x16 mfma_32x32x16(u32x4 a, u32x4 b, f32x16 c) {
   }
 }
 
+// Workgroups are handed to the 8 XCDs (each with its own L2) round robin by their flattened
+// index.  This maps the hardware index to a logical one such that every XCD works on one
+// contiguous range of logical indices, so neighbours in tile order share an L2.
+OD_DEV int xcd_contiguous(int bid, int n) {
+  constexpr int kXcd = 8;
+  const int xcd = bid % kXcd, slot = bid / kXcd;
+  const int q = n / kXcd, rem = n % kXcd;
+  return xcd * q + (xcd < rem ? xcd : rem) + slot;
+}
+
 OD_DEV int acc_row(int v, int lane) { return 8 * (v >> 2) + 4 * (lane >> 5) + (v & 3); }
 OD_DEV int acc_col(int lane) { return lane & 31; }
 

@@ -148,7 +148,9 @@ template <class T, class Num, class GSrc>
 __global__ __launch_bounds__(T::THREADS, 2) void k_proj(ClassDims d, MatPtrs ptrs, const float* scal, WsArr part, int splits, HalfArr qht) {
   extern __shared__ __align__(16) char lds[];
   const int tiles_n = (d.r + T::NT - 1) / T::NT;
-  const int tn = blockIdx.x % tiles_n, tm = blockIdx.x / tiles_n;
+  // the column tiles of one row panel read the same part of B: keep them on one XCD
+  const int bid = tiles_n > 1 ? xcd_contiguous(blockIdx.x, gridDim.x) : blockIdx.x;
+  const int tn = bid % tiles_n, tm = bid / tiles_n;
   const int split = blockIdx.y, z = blockIdx.z;
   SrcSum<GSrc> a = make_b_source<GSrc>(d, ptrs, z);
   SrcF32 b{ptrs.Q[z], d.n, d.r, d.r};
