@@ -165,8 +165,8 @@ extern "C" int orthdion_create(orthdion_handle* out, const orthdion_matdesc* mat
     b.splits_gram_q = pick_splits(gt, d.nb, n, 256);
     if (b.splits_gram_p > 32) b.splits_gram_p = 32;
     if (b.splits_gram_q > 32) b.splits_gram_q = 32;
-    b.slabs = (int)((n + 511) / 512);
-    if (b.slabs > 64) b.slabs = 64;
+    b.slabs = (int)((n + 31) / 32);           // row slabs of the column-norm kernels: many, so the grid fills the chip
+    if (b.slabs > 256) b.slabs = 256;
     int64_t part = (int64_t)b.splits_proj * m * r;
     if ((int64_t)b.splits_back * n * r > part) part = (int64_t)b.splits_back * n * r;
     if ((int64_t)b.splits_gram_p * r * r > part) part = (int64_t)b.splits_gram_p * r * r;

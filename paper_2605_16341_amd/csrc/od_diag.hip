@@ -99,6 +99,7 @@ __global__ __launch_bounds__(256) void k_diag_cols_final(int r, WsArr part, int 
   double s2 = 0.0, sl = 0.0, sll = 0.0;
   for (int c = tid; c < r; c += 256) {
     double s = 0.0;
+#pragma unroll 8
     for (int k = 0; k < slabs; ++k) s += (double)part.base[(int64_t)z * part.stride + (int64_t)k * r + c];
     s2 += s;
     const double len = sqrt(s);

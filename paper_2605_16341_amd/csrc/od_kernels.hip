@@ -486,6 +486,7 @@ __global__ __launch_bounds__(256) void k_colsq_final(int n, int r, WsArr part, i
   float tot = 0.f;
   for (int c = tid; c < r; c += 256) {
     float s = 0.f;
+#pragma unroll 8
     for (int k = 0; k < slabs; ++k) s += part.base[(int64_t)z * part.stride + (int64_t)k * r + c];
     tot += s;
     float len = sqrtf(s);
