@@ -142,17 +142,23 @@ int orthdion_workspace_layout(orthdion_handle h, int32_t index, size_t* off_p, s
  *                           phase_mask, for the next max_steps calls of orthdion_step.
  *   orthdion_profile_end    waits for the recorded events, then writes, per phase, the summed
  *                           elapsed milliseconds and the number of intervals summed (steps x
- *                           shape-class batches) into two arrays of ORTHDION_NPHASE entries. */
+ *                           shape-class batches) into two arrays of ORTHDION_NPHASE entries.
+ * The two CHOL phases do not depend on m and n and run once for all matrices of one rank r,
+ * whatever their shape class: they contribute one interval per step and distinct rank. */
 typedef enum {
   ORTHDION_PHASE_STATS = 0,        /* sampled scale of B for the fp16 operand format      */
   ORTHDION_PHASE_PROJ = 1,         /* kernel: P_raw partials = (M + G) Q      (line 2)    */
   ORTHDION_PHASE_PROJ_REDUCE = 2,  /* second stage of the split contraction               */
-  ORTHDION_PHASE_ORTH_LEFT = 3,    /* P = orth(P_raw), CholeskyQR2            (line 2)    */
-  ORTHDION_PHASE_BACK = 4,         /* kernel: R partials = (M + G)^T P        (line 3)    */
-  ORTHDION_PHASE_BACK_REDUCE = 5,
-  ORTHDION_PHASE_ORTH_RIGHT = 6,   /* Q = orth(R) or ColNorm(R)               (line 4)    */
-  ORTHDION_PHASE_EFX = 7,          /* kernel: error feedback + update         (lines 5-7) */
-  ORTHDION_NPHASE = 8
+  ORTHDION_PHASE_GRAM_LEFT = 3,    /* Gram matrix of P_raw                    (line 2)    */
+  ORTHDION_PHASE_CHOL_LEFT = 4,    /* its Cholesky factor and inverse; see below          */
+  ORTHDION_PHASE_ORTH_LEFT = 5,    /* rest of P = orth(P_raw), CholeskyQR2    (line 2)    */
+  ORTHDION_PHASE_BACK = 6,         /* kernel: R partials = (M + G)^T P        (line 3)    */
+  ORTHDION_PHASE_BACK_REDUCE = 7,
+  ORTHDION_PHASE_GRAM_RIGHT = 8,   /* Gram matrix of R (QR variant only)      (line 4)    */
+  ORTHDION_PHASE_CHOL_RIGHT = 9,   /* its Cholesky factor and inverse (QR variant only)   */
+  ORTHDION_PHASE_ORTH_RIGHT = 10,  /* rest of Q = orth(R), or ColNorm(R)      (line 4)    */
+  ORTHDION_PHASE_EFX = 11,         /* kernel: error feedback + update         (lines 5-7) */
+  ORTHDION_NPHASE = 12
 } orthdion_phase;
 int orthdion_profile_begin(orthdion_handle h, uint32_t phase_mask, int32_t max_steps);
 int orthdion_profile_end(orthdion_handle h, float* ms_per_phase, int32_t* count_per_phase);

@@ -32,6 +32,17 @@ struct Batch {
   int64_t st_p, st_r, st_part, st_rr, st_colsq;
   int splits_proj, splits_back, splits_gram_p, splits_gram_q, slabs;
   int slot_base;                     // first row of this batch in the scal / info tables
+  int rank_class;
+};
+
+// All batches of one rank r.  The r x r work of the orthogonalisations (Cholesky factor and
+// inverse) does not depend on m and n, so it is launched once per rank class over all of its
+// matrices: the class owns the r x r arrays, every batch a contiguous range of slices.
+struct RankClass {
+  int r, count, slot_base;
+  int64_t st_rr;
+  std::vector<int> batches;
+  size_t off_gram, off_tp1, off_tp2, off_tq1, off_tq2, off_w, off_tmp;
 };
 
 int pick_splits(int64_t tiles, int nb, int64_t k, int kt_min) {
@@ -50,6 +61,7 @@ struct orthdion_ctx {
   std::vector<orthdion_matdesc> mats;
   orthdion_config cfg;
   std::vector<Batch> batches;
+  std::vector<RankClass> classes;
   std::vector<int> batch_of, slot_of;     // per matrix
   size_t off_scal, off_info, off_diag, off_dacc, off_dpart, ws_bytes;
   void* last_ws;
@@ -59,12 +71,14 @@ struct orthdion_ctx {
   unsigned prof_mask = 0;
   int prof_max_steps = 0, prof_steps = 0;
   std::vector<hipEvent_t> prof_events;    // [step][batch][phase][begin/end]
+  std::vector<char> prof_recorded;        // [step][batch][phase]: an interval was recorded
 };
 
 static hipEvent_t* prof_slot(orthdion_ctx* h, int batch, int phase, int end) {
   if (!h->prof_on || h->prof_steps >= h->prof_max_steps || !(h->prof_mask & (1u << phase))) return nullptr;
   size_t nb = h->batches.size();
   size_t idx = (((size_t)h->prof_steps * nb + (size_t)batch) * ORTHDION_NPHASE + (size_t)phase) * 2 + (size_t)end;
+  if (end) h->prof_recorded[idx / 2] = 1;
   return &h->prof_events[idx];
 }
 
@@ -146,12 +160,38 @@ extern "C" int orthdion_create(orthdion_handle* out, const orthdion_matdesc* mat
   h->off_diag = off; off = align_up(off + (size_t)nmat * od::kDiagPerMat * sizeof(float));
   h->off_dacc = off; off = align_up(off + (size_t)nmat * od::kDaccPerMat * sizeof(double));
   h->off_dpart = off; off = align_up(off + (size_t)nmat * od::kDiagBlocks * 4 * sizeof(double));
+  // rank classes in order of first appearance; table rows (slots) run class by class
+  for (size_t bi = 0; bi < h->batches.size(); ++bi) {
+    Batch& b = h->batches[bi];
+    b.d.nb = (int)b.members.size();
+    int found = -1;
+    for (size_t c = 0; c < h->classes.size(); ++c)
+      if (h->classes[c].r == b.d.r) found = (int)c;
+    if (found < 0) {
+      RankClass rc = {};
+      rc.r = b.d.r;
+      rc.st_rr = ((int64_t)b.d.r * b.d.r + 63) / 64 * 64;
+      h->classes.push_back(rc);
+      found = (int)h->classes.size() - 1;
+    }
+    b.rank_class = found;
+    h->classes[found].batches.push_back((int)bi);
+    h->classes[found].count += b.d.nb;
+  }
   int slot_base = 0;
+  for (RankClass& c : h->classes) {
+    c.slot_base = slot_base;
+    for (int bi : c.batches) {
+      h->batches[bi].slot_base = slot_base;
+      slot_base += h->batches[bi].d.nb;
+    }
+    auto take_rr = [&]() { size_t o = off; off = align_up(off + (size_t)c.st_rr * c.count * sizeof(float)); return o; };
+    c.off_gram = take_rr(); c.off_tp1 = take_rr(); c.off_tp2 = take_rr(); c.off_tq1 = take_rr(); c.off_tq2 = take_rr();
+    c.off_w = take_rr(); c.off_tmp = take_rr();
+  }
   for (Batch& b : h->batches) {
     ClassDims& d = b.d;
-    d.nb = (int)b.members.size();
-    b.slot_base = slot_base;
-    slot_base += d.nb;
+    const RankClass& rcl = h->classes[b.rank_class];
     const int64_t m = d.m, n = d.n, r = d.r;
     const int nt = r <= 64 ? 64 : (r <= 128 ? 128 : 256);
     const int64_t tiles_r = (r + nt - 1) / nt;
@@ -179,9 +219,12 @@ extern "C" int orthdion_create(orthdion_handle* out, const orthdion_matdesc* mat
     b.off_pa = take(b.st_p); b.off_pb = take(b.st_p);
     b.off_ra = take(b.st_r); b.off_rb = take(b.st_r);
     b.off_part = take(b.st_part);
-    b.off_gram = take(b.st_rr);
-    b.off_tp1 = take(b.st_rr); b.off_tp2 = take(b.st_rr); b.off_tq1 = take(b.st_rr); b.off_tq2 = take(b.st_rr);
-    b.off_w = take(b.st_rr); b.off_tmp = take(b.st_rr);
+    // this batch's slices of the class-owned r x r arrays
+    const size_t in_class = (size_t)(b.slot_base - rcl.slot_base) * (size_t)rcl.st_rr * sizeof(float);
+    b.off_gram = rcl.off_gram + in_class;
+    b.off_tp1 = rcl.off_tp1 + in_class; b.off_tp2 = rcl.off_tp2 + in_class;
+    b.off_tq1 = rcl.off_tq1 + in_class; b.off_tq2 = rcl.off_tq2 + in_class;
+    b.off_w = rcl.off_w + in_class; b.off_tmp = rcl.off_tmp + in_class;
     b.off_colsq = take(b.st_colsq);
     auto take_h = [&](int64_t stride) { size_t o = off; off = align_up(off + (size_t)stride * d.nb * sizeof(uint16_t)); return o; };
     b.off_ph = take_h(b.st_p); b.off_pht = take_h(b.st_p);
@@ -220,24 +263,46 @@ extern "C" int orthdion_set_variant(orthdion_handle h, orthdion_variant v) {
     if ((expr) != hipSuccess) return ORTHDION_E_HIP;  \
   } while (0)
 
-// orth() of `a0` (rows x r) by CholeskyQR2: pass 1 (Gram, Cholesky, a1 = a0 W1) and a
-// first-order second pass (Gram of a1, W2 = I - Phi(E), result = a1 W2 -> a0 | callers' Q).
-static int cholqr2(const Batch& b, char* ws, int rows, size_t off_a0, size_t off_a1, int64_t st_a, int splits,
-                   size_t off_t1, size_t off_t2, int info_slot, const MatPtrs* q_out, HalfArr hn, HalfArr ht, float* scal,
-                   int* info, int exact, hipStream_t st) {
+// orth() of `a0` (rows x r) by CholeskyQR2 comes in three pieces, so that the Cholesky step in
+// the middle can be launched once for every matrix of a rank:
+//   orth_gram : Gram matrix of a0, reduced into this batch's slices of the class array
+//   launch_cholinv over the rank class : T1, W1
+//   orth_finish: a1 = a0 W1, then a first-order second pass (Gram of a1, W2 = I - Phi(E),
+//                result = a1 W2 -> a0 | callers' Q).
+static int orth_gram(const Batch& b, char* ws, int rows, size_t off_a0, int64_t st_a, int splits, hipStream_t st) {
+  WsArr a0{reinterpret_cast<float*>(ws + off_a0), st_a};
+  WsArr part{reinterpret_cast<float*>(ws + b.off_part), b.st_part};
+  WsArr gram{reinterpret_cast<float*>(ws + b.off_gram), b.st_rr};
+  OD_TRY(od::launch_gram(b.d.nb, rows, b.d.r, a0, part, splits, 1, st));
+  // ordered reduction of the split partial sums on many workgroups: the factorisation runs on
+  // one workgroup per matrix and should not spend its time summing
+  OD_TRY(od::launch_reduce(b.d.nb, part, splits, (int64_t)b.d.r * b.d.r, gram, st));
+  return ORTHDION_OK;
+}
+
+static int orth_finish(const Batch& b, char* ws, int rows, size_t off_a0, size_t off_a1, int64_t st_a, int splits,
+                       size_t off_t2, int info_slot, const MatPtrs* q_out, HalfArr hn, HalfArr ht, float* scal,
+                       int* info, int exact, hipStream_t st) {
   const int nb = b.d.nb, r = b.d.r;
   WsArr a0{reinterpret_cast<float*>(ws + off_a0), st_a}, a1{reinterpret_cast<float*>(ws + off_a1), st_a};
   WsArr part{reinterpret_cast<float*>(ws + b.off_part), b.st_part};
-  WsArr gram{reinterpret_cast<float*>(ws + b.off_gram), b.st_rr};
-  WsArr w{reinterpret_cast<float*>(ws + b.off_w), b.st_rr}, tmp{reinterpret_cast<float*>(ws + b.off_tmp), b.st_rr};
-  WsArr t1{reinterpret_cast<float*>(ws + off_t1), b.st_rr}, t2{reinterpret_cast<float*>(ws + off_t2), b.st_rr};
-  OD_TRY(od::launch_gram(nb, rows, r, a0, part, splits, 1, st));
-  OD_TRY(od::launch_cholinv(nb, r, gram, part, splits, t1, w, tmp, info, info_slot, st));
+  WsArr w{reinterpret_cast<float*>(ws + b.off_w), b.st_rr};
+  WsArr t2{reinterpret_cast<float*>(ws + off_t2), b.st_rr};
   const HalfArr none{nullptr, 0};
   OD_TRY(od::launch_apply(nb, rows, r, a0, w, a1, nullptr, none, none, exact, st));
   OD_TRY(od::launch_gram(nb, rows, r, a1, part, splits, exact, st));
   OD_TRY(od::launch_corr(nb, r, part, splits, t2, w, scal, 2 + info_slot, info, info_slot, st));
   OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, hn, ht, exact, st));
+  return ORTHDION_OK;
+}
+
+// Cholesky factor and inverse for every matrix of a rank class; `off_t1` names the class array
+// that receives the factors (left or right side).
+static int class_cholinv(const RankClass& c, char* ws, size_t off_t1, int info_slot, int* info_all, hipStream_t st) {
+  WsArr gram{reinterpret_cast<float*>(ws + c.off_gram), c.st_rr};
+  WsArr w{reinterpret_cast<float*>(ws + c.off_w), c.st_rr}, tmp{reinterpret_cast<float*>(ws + c.off_tmp), c.st_rr};
+  WsArr t1{reinterpret_cast<float*>(ws + off_t1), c.st_rr};
+  OD_TRY(od::launch_cholinv(c.count, c.r, gram, t1, w, tmp, info_all + (size_t)c.slot_base * od::kInfoPerMat, info_slot, st));
   return ORTHDION_OK;
 }
 
@@ -295,61 +360,101 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     if (e0_ && e1_) od::time_next_launch(*e0_, *e1_);                        \
   } while (0)
 
-  for (int bi = 0; bi < (int)h->batches.size(); ++bi) {
+  // what every piece of a batch's work needs
+  struct BatchView {
+    MatPtrs ptrs;
+    float* scal; int* info;
+    WsArr pa, ra, part, colsq;
+    HalfArr ph, pht, rh, qh, qht;
+    double *dacc, *dpart;
+  };
+  const bool fast = prec == od::PREC_F16;
+  const HalfArr none{nullptr, 0};
+  auto view_of = [&](const Batch& b, BatchView& v) {
+    std::memset(&v.ptrs, 0, sizeof(v.ptrs));
+    for (int s = 0; s < b.d.nb; ++s) {
+      int i = b.members[s];
+      v.ptrs.X[s] = X[i]; v.ptrs.G[s] = G[i]; v.ptrs.M[s] = M[i]; v.ptrs.Q[s] = Q[i];
+    }
+    v.scal = scal_all + (size_t)b.slot_base * od::kScalPerMat;
+    v.info = info_all + (size_t)b.slot_base * od::kInfoPerMat;
+    v.pa = WsArr{reinterpret_cast<float*>(ws + b.off_pa), b.st_p};
+    v.ra = WsArr{reinterpret_cast<float*>(ws + b.off_ra), b.st_r};
+    v.part = WsArr{reinterpret_cast<float*>(ws + b.off_part), b.st_part};
+    v.colsq = WsArr{reinterpret_cast<float*>(ws + b.off_colsq), b.st_colsq};
+    v.ph = HalfArr{reinterpret_cast<uint16_t*>(ws + b.off_ph), b.st_p};
+    v.pht = HalfArr{reinterpret_cast<uint16_t*>(ws + b.off_pht), b.st_p};
+    v.rh = HalfArr{reinterpret_cast<uint16_t*>(ws + b.off_rh), b.st_r};
+    v.qh = HalfArr{reinterpret_cast<uint16_t*>(ws + b.off_qh), b.st_r};
+    v.qht = HalfArr{reinterpret_cast<uint16_t*>(ws + b.off_qht), b.st_r};
+    v.dacc = dacc_all + (size_t)b.slot_base * od::kDaccPerMat;
+    v.dpart = dpart_all + (size_t)b.slot_base * od::kDiagBlocks * 4;
+  };
+
+  // Alg. 1 lines 1-2, first part: P_raw = (M + G) Q and its Gram matrix
+  auto left_head = [&](int bi) -> int {
     const Batch& b = h->batches[bi];
     const ClassDims& d = b.d;
-    MatPtrs ptrs;
-    std::memset(&ptrs, 0, sizeof(ptrs));
-    for (int s = 0; s < d.nb; ++s) {
-      int i = b.members[s];
-      ptrs.X[s] = X[i]; ptrs.G[s] = G[i]; ptrs.M[s] = M[i]; ptrs.Q[s] = Q[i];
-    }
-    float* scal = scal_all + (size_t)b.slot_base * od::kScalPerMat;
-    int* info = info_all + (size_t)b.slot_base * od::kInfoPerMat;
-    WsArr pa{reinterpret_cast<float*>(ws + b.off_pa), b.st_p};
-    WsArr ra{reinterpret_cast<float*>(ws + b.off_ra), b.st_r};
-    WsArr part{reinterpret_cast<float*>(ws + b.off_part), b.st_part};
-    WsArr colsq{reinterpret_cast<float*>(ws + b.off_colsq), b.st_colsq};
-    const bool fast = prec == od::PREC_F16;
-    const HalfArr none{nullptr, 0};
-    HalfArr ph{reinterpret_cast<uint16_t*>(ws + b.off_ph), b.st_p}, pht{reinterpret_cast<uint16_t*>(ws + b.off_pht), b.st_p};
-    HalfArr rh{reinterpret_cast<uint16_t*>(ws + b.off_rh), b.st_r}, qh{reinterpret_cast<uint16_t*>(ws + b.off_qh), b.st_r};
-    HalfArr qht{reinterpret_cast<uint16_t*>(ws + b.off_qht), b.st_r};
-
-    double* dacc = dacc_all + (size_t)b.slot_base * od::kDaccPerMat;
-    double* dpart = dpart_all + (size_t)b.slot_base * od::kDiagBlocks * 4;
-    if (diag) OD_TRY(od::launch_diag_norms(d, ptrs, dpart, st));
-
-    // Alg. 1 lines 1-2: P_raw = (M + G) Q, then P = orth(P_raw)
+    BatchView v;
+    view_of(b, v);
+    if (diag) OD_TRY(od::launch_diag_norms(d, v.ptrs, v.dpart, st));
     OD_PHASE_BEGIN(ORTHDION_PHASE_STATS);
-    if (fast) OD_TRY(od::launch_stats(d, ptrs, scal, info, qht, st));
+    if (fast) OD_TRY(od::launch_stats(d, v.ptrs, v.scal, v.info, v.qht, st));
     OD_PHASE_END(ORTHDION_PHASE_STATS);
     OD_PHASE_KERNEL(ORTHDION_PHASE_PROJ);
-    OD_TRY(od::launch_proj(d, ptrs, prec, scal, part, b.splits_proj, qht, st));
+    OD_TRY(od::launch_proj(d, v.ptrs, prec, v.scal, v.part, b.splits_proj, v.qht, st));
     OD_PHASE_BEGIN(ORTHDION_PHASE_PROJ_REDUCE);
-    OD_TRY(od::launch_reduce(d.nb, part, b.splits_proj, (int64_t)d.m * d.r, pa, st));
+    OD_TRY(od::launch_reduce(d.nb, v.part, b.splits_proj, (int64_t)d.m * d.r, v.pa, st));
     OD_PHASE_END(ORTHDION_PHASE_PROJ_REDUCE);
+    OD_PHASE_BEGIN(ORTHDION_PHASE_GRAM_LEFT);
+    int rc = orth_gram(b, ws, d.m, b.off_pa, b.st_p, b.splits_gram_p, st);
+    if (rc != ORTHDION_OK) return rc;
+    OD_PHASE_END(ORTHDION_PHASE_GRAM_LEFT);
+    return ORTHDION_OK;
+  };
+
+  // rest of line 2 (P = orth(P_raw)), line 3 (R = (M + G)^T P), and the head of line 4
+  auto middle = [&](int bi) -> int {
+    const Batch& b = h->batches[bi];
+    const ClassDims& d = b.d;
+    BatchView v;
+    view_of(b, v);
     OD_PHASE_BEGIN(ORTHDION_PHASE_ORTH_LEFT);
-    int rc = cholqr2(b, ws, d.m, b.off_pa, b.off_pb, b.st_p, b.splits_gram_p, b.off_tp1, b.off_tp2, 0, nullptr,
-                     fast ? ph : none, fast ? pht : none, scal, info, exact, st);
+    int rc = orth_finish(b, ws, d.m, b.off_pa, b.off_pb, b.st_p, b.splits_gram_p, b.off_tp2, 0, nullptr,
+                         fast ? v.ph : none, fast ? v.pht : none, v.scal, v.info, exact, st);
     if (rc != ORTHDION_OK) return rc;
     OD_PHASE_END(ORTHDION_PHASE_ORTH_LEFT);
-    // line 3: R = (M + G)^T P
     OD_PHASE_KERNEL(ORTHDION_PHASE_BACK);
-    OD_TRY(od::launch_back(d, ptrs, prec, scal, pa, part, b.splits_back, pht, st));
+    OD_TRY(od::launch_back(d, v.ptrs, prec, v.scal, v.pa, v.part, b.splits_back, v.pht, st));
     OD_PHASE_BEGIN(ORTHDION_PHASE_BACK_REDUCE);
-    if (fast) OD_TRY(od::launch_reduce_r(d, part, b.splits_back, ra, rh, scal, st));
-    else OD_TRY(od::launch_reduce(d.nb, part, b.splits_back, (int64_t)d.n * d.r, ra, st));
+    if (fast) OD_TRY(od::launch_reduce_r(d, v.part, b.splits_back, v.ra, v.rh, v.scal, st));
+    else OD_TRY(od::launch_reduce(d.nb, v.part, b.splits_back, (int64_t)d.n * d.r, v.ra, st));
     OD_PHASE_END(ORTHDION_PHASE_BACK_REDUCE);
-    if (diag) OD_TRY(od::launch_diag_cols(d.nb, d.n, d.r, ra, part, b.slabs, dacc, st));
-    // line 4: Q = orth(R) or ColNorm(R), written to the callers' Q (Q_prev is no longer needed)
+    if (diag) OD_TRY(od::launch_diag_cols(d.nb, d.n, d.r, v.ra, v.part, b.slabs, v.dacc, st));
+    if (h->cfg.variant == ORTHDION_QR) {
+      OD_PHASE_BEGIN(ORTHDION_PHASE_GRAM_RIGHT);
+      rc = orth_gram(b, ws, d.n, b.off_ra, b.st_r, b.splits_gram_q, st);
+      if (rc != ORTHDION_OK) return rc;
+      OD_PHASE_END(ORTHDION_PHASE_GRAM_RIGHT);
+    }
+    return ORTHDION_OK;
+  };
+
+  // rest of line 4: Q = orth(R) or ColNorm(R), written to the callers' Q (Q_prev is no longer
+  // needed); lines 5-7: parameter update and error feedback in one pass
+  auto tail = [&](int bi) -> int {
+    const Batch& b = h->batches[bi];
+    const ClassDims& d = b.d;
+    BatchView v;
+    view_of(b, v);
     OD_PHASE_BEGIN(ORTHDION_PHASE_ORTH_RIGHT);
     if (h->cfg.variant == ORTHDION_QR) {
-      rc = cholqr2(b, ws, d.n, b.off_ra, b.off_rb, b.st_r, b.splits_gram_q, b.off_tq1, b.off_tq2, 1, &ptrs,
-                   fast ? qh : none, none, scal, info, exact, st);
+      int rc = orth_finish(b, ws, d.n, b.off_ra, b.off_rb, b.st_r, b.splits_gram_q, b.off_tq2, 1, &v.ptrs,
+                           fast ? v.qh : none, none, v.scal, v.info, exact, st);
       if (rc != ORTHDION_OK) return rc;
     } else {
-      OD_TRY(od::launch_colnorm(d.nb, d.n, d.r, ra, ptrs, part, b.slabs, colsq, scal, info, fast ? qh : none, st));
+      OD_TRY(od::launch_colnorm(d.nb, d.n, d.r, v.ra, v.ptrs, v.part, b.slabs, v.colsq, v.scal, v.info,
+                                fast ? v.qh : none, st));
     }
     OD_PHASE_END(ORTHDION_PHASE_ORTH_RIGHT);
     if (diag) {
@@ -357,18 +462,40 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
       WsArr rb{reinterpret_cast<float*>(ws + b.off_rb), b.st_r};
       WsArr gram{reinterpret_cast<float*>(ws + b.off_gram), b.st_rr}, tmp{reinterpret_cast<float*>(ws + b.off_tmp), b.st_rr};
       WsArr tq1{reinterpret_cast<float*>(ws + b.off_tq1), b.st_rr}, tq2{reinterpret_cast<float*>(ws + b.off_tq2), b.st_rr};
-      if (h->cfg.variant == ORTHDION_QR) OD_TRY(od::launch_diag_trace(d.nb, d.r, tq1, tq2, dacc, st));
-      OD_TRY(od::launch_gather_q(d.nb, d.n, d.r, ptrs, rb, st));
-      OD_TRY(od::launch_gram(d.nb, d.n, d.r, rb, part, b.splits_gram_q, 1, st));
-      OD_TRY(od::launch_reduce(d.nb, part, b.splits_gram_q, (int64_t)d.r * d.r, gram, st));
-      OD_TRY(od::launch_power(d.nb, d.r, gram, tmp, 128, dacc, st));
-      OD_TRY(od::launch_diag_final(d.nb, dpart, dacc, h->cfg.variant == ORTHDION_COLNORM ? 1 : 0,
+      if (h->cfg.variant == ORTHDION_QR) OD_TRY(od::launch_diag_trace(d.nb, d.r, tq1, tq2, v.dacc, st));
+      OD_TRY(od::launch_gather_q(d.nb, d.n, d.r, v.ptrs, rb, st));
+      OD_TRY(od::launch_gram(d.nb, d.n, d.r, rb, v.part, b.splits_gram_q, 1, st));
+      OD_TRY(od::launch_reduce(d.nb, v.part, b.splits_gram_q, (int64_t)d.r * d.r, gram, st));
+      OD_TRY(od::launch_power(d.nb, d.r, gram, tmp, 128, v.dacc, st));
+      OD_TRY(od::launch_diag_final(d.nb, v.dpart, v.dacc, h->cfg.variant == ORTHDION_COLNORM ? 1 : 0,
                                    diag_all + (size_t)b.slot_base * od::kDiagPerMat, st));
     }
-    // lines 5-7: parameter update and error feedback in one pass
     OD_PHASE_KERNEL(ORTHDION_PHASE_EFX);
-    if (fast) OD_TRY(od::launch_efx_h(d, ptrs, scal, ph, rh, qh, a_coef, b_coef, h->cfg.lr, st));
-    else OD_TRY(od::launch_efx(d, ptrs, prec, scal, pa, ra, a_coef, b_coef, h->cfg.lr, st));
+    if (fast) OD_TRY(od::launch_efx_h(d, v.ptrs, v.scal, v.ph, v.rh, v.qh, a_coef, b_coef, h->cfg.lr, st));
+    else OD_TRY(od::launch_efx(d, v.ptrs, prec, v.scal, v.pa, v.ra, a_coef, b_coef, h->cfg.lr, st));
+    return ORTHDION_OK;
+  };
+
+  // Rank class by rank class; inside a class the batches run piece by piece, so that each of
+  // the two Cholesky steps is one launch sequence over all matrices of the rank.  Its time is
+  // booked on the first batch of the class.
+  for (const RankClass& c : h->classes) {
+    int rc;
+    const int bi = c.batches[0];
+    for (int b2 : c.batches)
+      if ((rc = left_head(b2)) != ORTHDION_OK) return rc;
+    OD_PHASE_BEGIN(ORTHDION_PHASE_CHOL_LEFT);
+    if ((rc = class_cholinv(c, ws, c.off_tp1, 0, info_all, st)) != ORTHDION_OK) return rc;
+    OD_PHASE_END(ORTHDION_PHASE_CHOL_LEFT);
+    for (int b2 : c.batches)
+      if ((rc = middle(b2)) != ORTHDION_OK) return rc;
+    if (h->cfg.variant == ORTHDION_QR) {
+      OD_PHASE_BEGIN(ORTHDION_PHASE_CHOL_RIGHT);
+      if ((rc = class_cholinv(c, ws, c.off_tq1, 1, info_all, st)) != ORTHDION_OK) return rc;
+      OD_PHASE_END(ORTHDION_PHASE_CHOL_RIGHT);
+    }
+    for (int b2 : c.batches)
+      if ((rc = tail(b2)) != ORTHDION_OK) return rc;
   }
   if (h->prof_on && h->prof_steps < h->prof_max_steps) h->prof_steps++;
   return ORTHDION_OK;
@@ -379,6 +506,7 @@ extern "C" int orthdion_profile_begin(orthdion_handle h, uint32_t phase_mask, in
   if (max_steps < 1 || max_steps > 100000 || h->prof_on) return ORTHDION_E_INVALID_ARG;
   size_t count = (size_t)max_steps * h->batches.size() * ORTHDION_NPHASE * 2;
   h->prof_events.assign(count, nullptr);
+  h->prof_recorded.assign(count / 2, 0);
   for (int s = 0; s < max_steps; ++s)
     for (size_t b = 0; b < h->batches.size(); ++b)
       for (int ph = 0; ph < ORTHDION_NPHASE; ++ph)
@@ -405,6 +533,7 @@ extern "C" int orthdion_profile_end(orthdion_handle h, float* ms_per_phase, int3
       for (int ph = 0; ph < ORTHDION_NPHASE; ++ph) {
         if (!(h->prof_mask & (1u << ph))) continue;
         size_t idx = (((size_t)s * nb + b) * ORTHDION_NPHASE + (size_t)ph) * 2;
+        if (!h->prof_recorded[idx / 2]) continue;      // e.g. the Cholesky of a class: first batch only
         float ms = 0.f;
         if (hipEventSynchronize(h->prof_events[idx + 1]) != hipSuccess ||
             hipEventElapsedTime(&ms, h->prof_events[idx], h->prof_events[idx + 1]) != hipSuccess) {

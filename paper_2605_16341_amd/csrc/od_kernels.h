@@ -76,14 +76,15 @@ hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits,
 hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs, HalfArr hn,
                         HalfArr ht, int exact, hipStream_t st);
 
-// Cholesky factor and its inverse of the SPD r x r matrix sum_s part[s] (ld r): = T^T T,
-// W = T^-1, both upper triangular with zeros below the diagonal.  For r <= 256 one workgroup
-// per matrix does everything; above, `gram` receives the reduced matrix (destroyed) and the
-// factorisation is blocked, `tmp` being r x r scratch.  A non-positive or non-finite pivot
+// Cholesky factor and its inverse of the SPD r x r matrices `gram` (ld r): gram = T^T T,
+// W = T^-1, both upper triangular with zeros below the diagonal.  The matrices need not belong
+// to one shape class: the work depends on r only, so one call serves every matrix of that
+// rank.  For r <= 256 one workgroup per matrix does everything; above, the factorisation is
+// blocked, `gram` is destroyed and `tmp` is r x r scratch.  A non-positive or non-finite pivot
 // writes its 1-based column to info[mat * kInfoPerMat + info_slot] (first failure wins); the
 // factors of such a matrix are unspecified (they may hold NaN).
-hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr part, int splits, WsArr t, WsArr w, WsArr tmp, int* info,
-                          int info_slot, hipStream_t st);
+hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp, int* info, int info_slot,
+                          hipStream_t st);
 
 // First-order second pass: from the Gram partials of a nearly orthonormal matrix writes
 // T2 = I + Phi(E), W2 = I - Phi(E) and max |E| into scal[mat][scal_slot] (must be zeroed);

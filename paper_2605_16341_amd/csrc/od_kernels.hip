@@ -911,16 +911,13 @@ static hipError_t sgemm(int nb, const SgemmArgs& g, bool a_kc, int exact, hipStr
   return a_kc ? sgemm_t<NumBF<2>, KC>(nb, g, st) : sgemm_t<NumBF<2>, KSF>(nb, g, st);
 }
 
-hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr part, int splits, WsArr t, WsArr w, WsArr tmp, int* info,
-                          int info_slot, hipStream_t st) {
+hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp, int* info, int info_slot,
+                          hipStream_t st) {
   hipError_t e = allow_lds(k_chol256, kCholLds);
   if (e != hipSuccess) return e;
   const int nblk = (r + kLeaf - 1) / kLeaf;
   CholArgs ca = {};
   ca.t = t; ca.w = w; ca.r = r; ca.info = info; ca.info_slot = info_slot;
-  // ordered reduction of the split partial sums on many workgroups first: the factorisation
-  // below runs on one workgroup per matrix and should not spend its time summing
-  if ((e = launch_reduce(nb, part, splits, (int64_t)r * r, gram, st)) != hipSuccess) return e;
   ca.src = gram; ca.splits = 1; ca.split_stride = 0;
   if (nblk == 1) {
     ca.blk = 0;
