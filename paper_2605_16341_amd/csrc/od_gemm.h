@@ -190,7 +190,7 @@ OD_DEV void mma_step(const char* ldsA, const char* ldsB, f32x16 (&acc)[T::FM][T:
 // `lds` must hold T::lds_bytes<Num>() bytes.  Ends with all waves past their last LDS read.
 template <class T, class Num, class DirA, class SrcA, class DirB, class SrcB>
 OD_DEV void gemm_mainloop(const SrcA& a, const SrcB& b, int m0, int n0, int kbeg, int kend,
-                          float scaleA, float scaleB, char* lds, f32x16 (&acc)[T::FM][T::FN]) {
+                          float scaleA, float scaleB, char* lds, f32x16 (&acc)[T::FM][T::FN], int rot = 0) {
   typedef typename LoaderFor<DirA, SrcA, T::MT, T::KT, T::PITCH, T::THREADS>::type LA;
   typedef typename LoaderFor<DirB, SrcB, T::NT, T::KT, T::PITCH, T::THREADS>::type LB;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -200,17 +200,23 @@ OD_DEV void gemm_mainloop(const SrcA& a, const SrcB& b, int m0, int n0, int kbeg
   LA la;
   LB lb;
   if (kbeg >= kend) return;
-  la.load(a, m0, kbeg, tid);
-  lb.load(b, n0, kbeg, tid);
+  // The KT-deep steps are taken in rotated order, starting at step `rot` (mod the step
+  // count).  Workgroups that run side by side and would otherwise walk the same k positions
+  // in lockstep get different rotations from their caller (see k_proj).
+  const int nsteps = (kend - kbeg + T::KT - 1) / T::KT;
+  int cur = rot % nsteps;
+  la.load(a, m0, kbeg + cur * T::KT, tid);
+  lb.load(b, n0, kbeg + cur * T::KT, tid);
   la.template store<Num>(lds, T::PLANE_A, scaleA, tid);
   lb.template store<Num>(lds + OFF_B, T::PLANE_B, scaleB, tid);
   __syncthreads();
   int buf = 0;
-  for (int k = kbeg; k < kend; k += T::KT) {
-    const bool more = (k + T::KT) < kend;
+  for (int i = 0; i < nsteps; ++i) {
+    const bool more = (i + 1) < nsteps;
+    cur = (cur + 1 == nsteps) ? 0 : cur + 1;
     if (more) {
-      la.load(a, m0, k + T::KT, tid);
-      lb.load(b, n0, k + T::KT, tid);
+      la.load(a, m0, kbeg + cur * T::KT, tid);
+      lb.load(b, n0, kbeg + cur * T::KT, tid);
     }
     mma_step<T, Num>(lds + buf * BUF, lds + buf * BUF + OFF_B, acc, wm, wn, lane);
     if (more) {

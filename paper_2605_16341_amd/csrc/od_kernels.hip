@@ -145,7 +145,7 @@ OD_DEV float r_scale(const ClassDims& d, const float* scal, int z) {
 }
 
 template <class T, class Num, class GSrc>
-__global__ __launch_bounds__(T::THREADS, 2) void k_proj(ClassDims d, MatPtrs ptrs, const float* scal, WsArr part, int splits, HalfArr qht) {
+__global__ __launch_bounds__(T::THREADS, 2) void k_proj(ClassDims d, MatPtrs ptrs, const float* scal, WsArr part, int splits, HalfArr qht, int rotate) {
   extern __shared__ __align__(16) char lds[];
   const int tiles_n = (d.r + T::NT - 1) / T::NT;
   // the column tiles of one row panel read the same part of B: keep them on one XCD
@@ -163,7 +163,10 @@ __global__ __launch_bounds__(T::THREADS, 2) void k_proj(ClassDims d, MatPtrs ptr
   if constexpr (Num::F16) {
     // Q as pre-scaled fp16, transposed to [r][n] so that k is contiguous
     SrcH16 bh{qht.base + (int64_t)z * qht.stride, d.r, d.n, d.n};
-    gemm_mainloop<T, Num, KC, SrcSum<GSrc>, KC, SrcH16>(a, bh, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc);
+    // Row panels of one matrix read the same columns of B at the same time, and with a row
+    // stride that is a multiple of the memory-channel interleave they all land on the same
+    // channels: start every panel at a different k step then.
+    gemm_mainloop<T, Num, KC, SrcSum<GSrc>, KC, SrcH16>(a, bh, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc, rotate ? tm : 0);
   } else {
     gemm_mainloop<T, Num, KC, SrcSum<GSrc>, KS, SrcF32>(a, b, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc);
   }
@@ -785,7 +788,10 @@ static hipError_t proj_t(const ClassDims& d, const MatPtrs& ptrs, const float* s
   hipError_t e = allow_lds(k_proj<T, Num, GSrc>, lds);
   if (e != hipSuccess) return e;
   dim3 grid(((d.m + T::MT - 1) / T::MT) * ((d.r + T::NT - 1) / T::NT), splits, d.nb);
-  launch_timed(k_proj<T, Num, GSrc>, grid, dim3(T::THREADS), lds, st, d, ptrs, scal, part, splits, qht);
+  // one matrix whose rows are a multiple of 32 KB apart (in M): measured 10-20 % faster with
+  // rotated k order at 8192 columns; with several matrices in flight the order does not matter
+  const int rotate = (d.nb == 1 && (d.ldm * (int64_t)sizeof(float)) % 32768 == 0) ? 1 : 0;
+  launch_timed(k_proj<T, Num, GSrc>, grid, dim3(T::THREADS), lds, st, d, ptrs, scal, part, splits, qht, rotate);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
