@@ -124,7 +124,10 @@ struct NumBF {
 // R rows, C columns and leading dimension ld (elements).  load8(r, c) returns the 8
 // consecutive elements (r, c..c+7), load4(r, c) the 4 elements (r, c..c+3); positions
 // outside the view read as zero.  C is a multiple of 8, so a group of 8 (or 4) aligned
-// columns is either wholly inside or wholly outside.
+// columns is either wholly inside or wholly outside.  load8u / load4u / load1u are the same
+// reads without the bounds check, for tiles known to lie inside the view: a checked load is
+// a branch, and past a branch the compiler waits for every outstanding load, not just the
+// oldest, which defeats a multi-stage prefetch.
 // ---------------------------------------------------------------------------------
 struct SrcF32 {
   static constexpr bool PACKED = false;
@@ -133,8 +136,16 @@ struct SrcF32 {
   const float* p;
   int R, C;
   int64_t ld;
+  OD_DEV int rows() const { return R; }
+  OD_DEV int cols() const { return C; }
   struct Raw8 { f32x4 a, b; };
   typedef f32x4 Raw4;
+  OD_DEV Raw8 load8u(int r, int c) const {
+    const f32x4* q = reinterpret_cast<const f32x4*>(p + (int64_t)r * ld + c);
+    return Raw8{q[0], q[1]};
+  }
+  OD_DEV Raw4 load4u(int r, int c) const { return *reinterpret_cast<const f32x4*>(p + (int64_t)r * ld + c); }
+  OD_DEV float load1u(int r, int c) const { return p[(int64_t)r * ld + c]; }
   OD_DEV Raw8 load8(int r, int c) const {
     Raw8 v;
     if (r < R && c < C) {
@@ -167,8 +178,12 @@ struct SrcBF16 {
   const uint16_t* p;
   int R, C;
   int64_t ld;
+  OD_DEV int rows() const { return R; }
+  OD_DEV int cols() const { return C; }
   typedef u32x4 Raw8;
   typedef u32x2 Raw4;
+  OD_DEV Raw8 load8u(int r, int c) const { return *reinterpret_cast<const u32x4*>(p + (int64_t)r * ld + c); }
+  OD_DEV Raw4 load4u(int r, int c) const { return *reinterpret_cast<const u32x2*>(p + (int64_t)r * ld + c); }
   OD_DEV Raw8 load8(int r, int c) const {
     if (r < R && c < C) return *reinterpret_cast<const u32x4*>(p + (int64_t)r * ld + c);
     return u32x4{0u, 0u, 0u, 0u};
@@ -195,8 +210,12 @@ struct SrcH16 {
   const uint16_t* p;
   int R, C;
   int64_t ld;
+  OD_DEV int rows() const { return R; }
+  OD_DEV int cols() const { return C; }
   typedef u32x4 Raw8;
   typedef u32x2 Raw4;
+  OD_DEV Raw8 load8u(int r, int c) const { return *reinterpret_cast<const u32x4*>(p + (int64_t)r * ld + c); }
+  OD_DEV Raw4 load4u(int r, int c) const { return *reinterpret_cast<const u32x2*>(p + (int64_t)r * ld + c); }
   OD_DEV Raw8 load8(int r, int c) const {
     if (r < R && c < C) return *reinterpret_cast<const u32x4*>(p + (int64_t)r * ld + c);
     return u32x4{0u, 0u, 0u, 0u};
@@ -227,8 +246,12 @@ struct SrcSum {
   static constexpr bool HAS_LOAD1 = false;
   SrcF32 m;
   GSrc g;
+  OD_DEV int rows() const { return m.R; }
+  OD_DEV int cols() const { return m.C; }
   struct Raw8 { SrcF32::Raw8 a; typename GSrc::Raw8 b; };
   struct Raw4 { SrcF32::Raw4 a; typename GSrc::Raw4 b; };
+  OD_DEV Raw8 load8u(int r, int c) const { return Raw8{m.load8u(r, c), g.load8u(r, c)}; }
+  OD_DEV Raw4 load4u(int r, int c) const { return Raw4{m.load4u(r, c), g.load4u(r, c)}; }
   OD_DEV Raw8 load8(int r, int c) const { return Raw8{m.load8(r, c), g.load8(r, c)}; }
   OD_DEV Raw4 load4(int r, int c) const { return Raw4{m.load4(r, c), g.load4(r, c)}; }
   OD_DEV static void unpack8(const Raw8& v, float* x) {

@@ -42,6 +42,17 @@ struct LoadKC {
       if (ITEMS % THREADS == 0 || item < ITEMS) raw[p] = s.load8(row0 + item / KG, k0 + (item % KG) * 8);
     }
   }
+  // the tile rows and every k below kpad lie inside the source
+  OD_DEV static bool interior(const Src& s, int row0, int kpad) { return row0 + ROWS <= s.rows() && kpad <= s.cols(); }
+  // load() for an interior tile: no bounds checks, hence no branches
+  OD_DEV void loadu(const Src& s, int row0, int k0, int tid) {
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      int item = tid + p * THREADS;
+      if (ITEMS % THREADS != 0) item %= ITEMS;         // surplus threads repeat a valid item; store() skips them
+      raw[p] = s.load8u(row0 + item / KG, k0 + (item % KG) * 8);
+    }
+  }
   template <class Num>
   OD_DEV void store(char* lds, int plane, float scale, int tid) const {
 #pragma unroll
@@ -78,6 +89,17 @@ struct LoadKS {
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) raw[p][kk] = s.load4(k0 + kg * 8 + kk, row0 + rq * 4);
       }
+    }
+  }
+  OD_DEV static bool interior(const Src& s, int row0, int kpad) { return kpad <= s.rows() && row0 + ROWS <= s.cols(); }
+  OD_DEV void loadu(const Src& s, int row0, int k0, int tid) {
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      int item = tid + p * THREADS;
+      if (ITEMS % THREADS != 0) item %= ITEMS;
+      int rq = item % RQ, kg = item / RQ;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) raw[p][kk] = s.load4u(k0 + kg * 8 + kk, row0 + rq * 4);
     }
   }
   template <class Num>
@@ -122,6 +144,17 @@ struct LoadKS1 {
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) raw[p][kk] = s.load1(k0 + kg * 8 + kk, row0 + row);
       }
+    }
+  }
+  OD_DEV static bool interior(const Src& s, int row0, int kpad) { return kpad <= s.rows() && row0 + ROWS <= s.cols(); }
+  OD_DEV void loadu(const Src& s, int row0, int k0, int tid) {
+#pragma unroll
+    for (int p = 0; p < PER; ++p) {
+      int item = tid + p * THREADS;
+      if (ITEMS % THREADS != 0) item %= ITEMS;
+      int row = item % ROWS, kg = item / ROWS;
+#pragma unroll
+      for (int kk = 0; kk < 8; ++kk) raw[p][kk] = s.load1u(k0 + kg * 8 + kk, row0 + row);
     }
   }
   template <class Num>
@@ -234,7 +267,7 @@ OD_DEV void gemm_mainloop(const SrcA& a, const SrcB& b, int m0, int n0, int kbeg
 // matrix-core work of step i.
 template <class T, class Num, class DirA, class SrcA, class DirB, class SrcB, int PF>
 OD_DEV void gemm_mainloop_deep(const SrcA& a, const SrcB& b, int m0, int n0, int kbeg, int kend,
-                               float scaleA, float scaleB, char* lds, f32x16 (&acc)[T::FM][T::FN]) {
+                               float scaleA, float scaleB, char* lds, f32x16 (&acc)[T::FM][T::FN], int rot = 0) {
   typedef typename LoaderFor<DirA, SrcA, T::MT, T::KT, T::PITCH, T::THREADS>::type LA;
   typedef typename LoaderFor<DirB, SrcB, T::NT, T::KT, T::PITCH, T::THREADS>::type LB;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -243,13 +276,61 @@ OD_DEV void gemm_mainloop_deep(const SrcA& a, const SrcB& b, int m0, int n0, int
   constexpr int OFF_B = Num::PARTS * T::PLANE_A;
   if (kbeg >= kend) return;
   const int nsteps = (kend - kbeg + T::KT - 1) / T::KT;
+  rot %= nsteps;
+  // step i works on the k range of step (i + rot) mod nsteps (see gemm_mainloop)
+  auto k_of = [&](int i) { const int c = i + rot; return kbeg + (c >= nsteps ? c - nsteps : c) * T::KT; };
   LA la[PF];
   LB lb[PF];
+  if (nsteps >= 2 * PF && LA::interior(a, m0, kbeg + nsteps * T::KT) && LB::interior(b, n0, kbeg + nsteps * T::KT)) {
+    // Both tiles lie inside their sources for every step: loads without bounds checks, and a
+    // main loop of straight-line code, so that the wait before a store to LDS is for the
+    // oldest register stage only (the younger PF - 1 stay in flight across the barrier).
+#pragma unroll
+    for (int p = 0; p < PF; ++p) {
+      la[p].loadu(a, m0, k_of(p), tid);
+      lb[p].loadu(b, n0, k_of(p), tid);
+    }
+    la[0].template store<Num>(lds, T::PLANE_A, scaleA, tid);
+    lb[0].template store<Num>(lds + OFF_B, T::PLANE_B, scaleB, tid);
+    __syncthreads();
+    int i = 0;
+    for (; i + 2 * PF <= nsteps; i += PF) {        // every refill below is a step that exists
+#pragma unroll
+      for (int j = 0; j < PF; ++j) {
+        const int step = i + j, buf = step & 1;    // step lives in register stage j
+        la[j].loadu(a, m0, k_of(step + PF), tid);
+        lb[j].loadu(b, n0, k_of(step + PF), tid);
+        __builtin_amdgcn_sched_barrier(0);         // the loads stay ahead of the matrix-core work
+        mma_step<T, Num>(lds + buf * BUF, lds + buf * BUF + OFF_B, acc, wm, wn, lane);
+        la[(j + 1) % PF].template store<Num>(lds + (buf ^ 1) * BUF, T::PLANE_A, scaleA, tid);
+        lb[(j + 1) % PF].template store<Num>(lds + (buf ^ 1) * BUF + OFF_B, T::PLANE_B, scaleB, tid);
+        __syncthreads();
+      }
+    }
+    // the last PF .. 2 PF - 1 steps: stage t % PF holds step i + t, the tile of step i is in LDS
+#pragma unroll
+    for (int t = 0; t < 2 * PF - 1; ++t) {
+      const int step = i + t, buf = step & 1;
+      if (step < nsteps) {
+        if (step + PF < nsteps) {
+          la[t % PF].loadu(a, m0, k_of(step + PF), tid);
+          lb[t % PF].loadu(b, n0, k_of(step + PF), tid);
+        }
+        mma_step<T, Num>(lds + buf * BUF, lds + buf * BUF + OFF_B, acc, wm, wn, lane);
+        if (step + 1 < nsteps) {
+          la[(t + 1) % PF].template store<Num>(lds + (buf ^ 1) * BUF, T::PLANE_A, scaleA, tid);
+          lb[(t + 1) % PF].template store<Num>(lds + (buf ^ 1) * BUF + OFF_B, T::PLANE_B, scaleB, tid);
+        }
+        __syncthreads();
+      }
+    }
+    return;
+  }
 #pragma unroll
   for (int p = 0; p < PF; ++p) {
     if (p < nsteps) {
-      la[p].load(a, m0, kbeg + p * T::KT, tid);
-      lb[p].load(b, n0, kbeg + p * T::KT, tid);
+      la[p].load(a, m0, k_of(p), tid);
+      lb[p].load(b, n0, k_of(p), tid);
     }
   }
   la[0].template store<Num>(lds, T::PLANE_A, scaleA, tid);
@@ -262,8 +343,8 @@ OD_DEV void gemm_mainloop_deep(const SrcA& a, const SrcB& b, int m0, int n0, int
       if (i < nsteps) {
         const int buf = i & 1;
         if (i + PF < nsteps) {                 // stage j went to LDS one step ago: refill it
-          la[j].load(a, m0, kbeg + (i + PF) * T::KT, tid);
-          lb[j].load(b, n0, kbeg + (i + PF) * T::KT, tid);
+          la[j].load(a, m0, k_of(i + PF), tid);
+          lb[j].load(b, n0, k_of(i + PF), tid);
         }
         mma_step<T, Num>(lds + buf * BUF, lds + buf * BUF + OFF_B, acc, wm, wn, lane);
         if (i + 1 < nsteps) {

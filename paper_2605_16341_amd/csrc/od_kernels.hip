@@ -21,6 +21,7 @@ typedef Tile<128, 256, 32, 2, 2> TileWide;     // r > 128: wave tile 64 x 128
 typedef Tile<128, 128, 32, 2, 2> TileSquare;   // wave tile 64 x 64
 typedef Tile<128, 64, 32, 4, 1> TileNarrow;    // r <= 64: wave tile 32 x 64
 typedef Tile<64, 256, 32, 2, 2> TileFlat;      // projection, r > 128: twice the row panels, half the splits (wave tile 32 x 128)
+typedef Tile<256, 256, 32, 2, 2> TileHuge;    // back-projection, r > 256: wave tile 128 x 128, one workgroup per CU
 typedef Tile<64, 64, 64, 2, 2> TileSmall;      // wave tile 32 x 32: small problems that need many workgroups
 
 constexpr float kUnitScale = 1024.f;           // scale of orthonormal / unit-column factors in fp16
@@ -144,8 +145,14 @@ OD_DEV float r_scale(const ClassDims& d, const float* scal, int z) {
   return ldexpf(b_scale(d, scal, z), -(ilogbf((float)d.m / (float)d.r) / 2));
 }
 
-template <class T, class Num, class GSrc>
-__global__ __launch_bounds__(T::THREADS, 2) void k_proj(ClassDims d, MatPtrs ptrs, const float* scal, WsArr part, int splits, HalfArr qht, int rotate) {
+// Second argument of __launch_bounds__ (waves per SIMD the register allocation must allow;
+// with 4-wave workgroups that is workgroups per CU).  Register stages of a deep prefetch on
+// top of 8 accumulator tiles, or 16 accumulator tiles alone, need more than 256 registers.
+template <class T, int PF>
+constexpr int min_waves_per_simd() { return ((PF > 1 && T::FM * T::FN >= 8) || T::FM * T::FN >= 16) ? 1 : 2; }
+
+template <class T, class Num, class GSrc, int PF>
+__global__ __launch_bounds__(T::THREADS, (min_waves_per_simd<T, PF>())) void k_proj(ClassDims d, MatPtrs ptrs, const float* scal, WsArr part, int splits, HalfArr qht, int rotate) {
   extern __shared__ __align__(16) char lds[];
   const int tiles_n = (d.r + T::NT - 1) / T::NT;
   // the column tiles of one row panel read the same part of B: keep them on one XCD
@@ -166,7 +173,10 @@ __global__ __launch_bounds__(T::THREADS, 2) void k_proj(ClassDims d, MatPtrs ptr
     // Row panels of one matrix read the same columns of B at the same time, and with a row
     // stride that is a multiple of the memory-channel interleave they all land on the same
     // channels: start every panel at a different k step then.
-    gemm_mainloop<T, Num, KC, SrcSum<GSrc>, KC, SrcH16>(a, bh, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc, rotate ? tm : 0);
+    if constexpr (PF > 1)
+      gemm_mainloop_deep<T, Num, KC, SrcSum<GSrc>, KC, SrcH16, PF>(a, bh, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc, rotate ? tm : 0);
+    else
+      gemm_mainloop<T, Num, KC, SrcSum<GSrc>, KC, SrcH16>(a, bh, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc, rotate ? tm : 0);
   } else {
     gemm_mainloop<T, Num, KC, SrcSum<GSrc>, KS, SrcF32>(a, b, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc);
   }
@@ -180,8 +190,8 @@ __global__ __launch_bounds__(T::THREADS, 2) void k_proj(ClassDims d, MatPtrs ptr
 // ------------------------------------------------------------------------------------
 // R = B^T P  (split over m)                                         Alg. 1 line 3
 // ------------------------------------------------------------------------------------
-template <class T, class Num, class GSrc>
-__global__ __launch_bounds__(T::THREADS, 2) void k_back(ClassDims d, MatPtrs ptrs, const float* scal, WsArr p, WsArr part, int splits, HalfArr pht) {
+template <class T, class Num, class GSrc, int PF>
+__global__ __launch_bounds__(T::THREADS, (min_waves_per_simd<T, PF>())) void k_back(ClassDims d, MatPtrs ptrs, const float* scal, WsArr p, WsArr part, int splits, HalfArr pht) {
   extern __shared__ __align__(16) char lds[];
   const int tiles_n = (d.r + T::NT - 1) / T::NT;
   const int tn = blockIdx.x % tiles_n, tm = blockIdx.x / tiles_n;
@@ -196,7 +206,10 @@ __global__ __launch_bounds__(T::THREADS, 2) void k_back(ClassDims d, MatPtrs ptr
   zero_acc<T>(acc);
   if constexpr (Num::F16) {
     SrcH16 bh{pht.base + (int64_t)z * pht.stride, d.r, d.m, d.m};      // P^T as fp16, [r][m]
-    gemm_mainloop<T, Num, KS, SrcSum<GSrc>, KC, SrcH16>(a, bh, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc);
+    if constexpr (PF > 1)
+      gemm_mainloop_deep<T, Num, KS, SrcSum<GSrc>, KC, SrcH16, PF>(a, bh, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc);
+    else
+      gemm_mainloop<T, Num, KS, SrcSum<GSrc>, KC, SrcH16>(a, bh, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc);
   } else {
     gemm_mainloop<T, Num, KS, SrcSum<GSrc>, KS, SrcF32>(a, b, tm * T::MT, tn * T::NT, kbeg, kend, sa, sb, lds, acc);
   }
@@ -782,16 +795,16 @@ hipError_t launch_stats(const ClassDims& d, const MatPtrs& ptrs, float* scal, in
   return hipSuccess;
 }
 
-template <class T, class Num, class GSrc>
+template <class T, class Num, class GSrc, int PF = 1>
 static hipError_t proj_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr part, int splits, HalfArr qht, hipStream_t st) {
   constexpr int lds = T::template lds_bytes<Num>();
-  hipError_t e = allow_lds(k_proj<T, Num, GSrc>, lds);
+  hipError_t e = allow_lds(k_proj<T, Num, GSrc, PF>, lds);
   if (e != hipSuccess) return e;
   dim3 grid(((d.m + T::MT - 1) / T::MT) * ((d.r + T::NT - 1) / T::NT), splits, d.nb);
   // one matrix whose rows are a multiple of 32 KB apart (in M): measured 10-20 % faster with
   // rotated k order at 8192 columns; with several matrices in flight the order does not matter
   const int rotate = (d.nb == 1 && (d.ldm * (int64_t)sizeof(float)) % 32768 == 0) ? 1 : 0;
-  launch_timed(k_proj<T, Num, GSrc>, grid, dim3(T::THREADS), lds, st, d, ptrs, scal, part, splits, qht, rotate);
+  launch_timed(k_proj<T, Num, GSrc, PF>, grid, dim3(T::THREADS), lds, st, d, ptrs, scal, part, splits, qht, rotate);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -805,20 +818,24 @@ static hipError_t proj_g(const ClassDims& d, const MatPtrs& ptrs, Prec prec, con
   if (prec == PREC_BF3) return proj_t<TileSquare, NumBF<3>, GSrc>(d, ptrs, scal, part, splits, qht, st);
   if (d.r <= 64) return proj_t<TileNarrow, NumF16, GSrc>(d, ptrs, scal, part, splits, qht, st);
   if (d.r <= 128) return proj_t<TileSquare, NumF16, GSrc>(d, ptrs, scal, part, splits, qht, st);
-  if (proj_uses_flat_tiles(d.m, d.r, d.nb)) return proj_t<TileFlat, NumF16, GSrc>(d, ptrs, scal, part, splits, qht, st);
+  if (proj_uses_flat_tiles(d.m, d.r, d.nb)) {
+    // long enough K loops per column tile pay for a second register stage
+    if (d.r > 256) return proj_t<TileFlat, NumF16, GSrc, 2>(d, ptrs, scal, part, splits, qht, st);
+    return proj_t<TileFlat, NumF16, GSrc>(d, ptrs, scal, part, splits, qht, st);
+  }
   return proj_t<TileWide, NumF16, GSrc>(d, ptrs, scal, part, splits, qht, st);
 }
 hipError_t launch_proj(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr part, int splits, HalfArr qht, hipStream_t st) {
   return d.g_bf16 ? proj_g<SrcBF16>(d, ptrs, prec, scal, part, splits, qht, st) : proj_g<SrcF32>(d, ptrs, prec, scal, part, splits, qht, st);
 }
 
-template <class T, class Num, class GSrc>
+template <class T, class Num, class GSrc, int PF = 1>
 static hipError_t back_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr p, WsArr part, int splits, HalfArr pht, hipStream_t st) {
   constexpr int lds = T::template lds_bytes<Num>();
-  hipError_t e = allow_lds(k_back<T, Num, GSrc>, lds);
+  hipError_t e = allow_lds(k_back<T, Num, GSrc, PF>, lds);
   if (e != hipSuccess) return e;
   dim3 grid(((d.n + T::MT - 1) / T::MT) * ((d.r + T::NT - 1) / T::NT), splits, d.nb);
-  launch_timed(k_back<T, Num, GSrc>, grid, dim3(T::THREADS), lds, st, d, ptrs, scal, p, part, splits, pht);
+  launch_timed(k_back<T, Num, GSrc, PF>, grid, dim3(T::THREADS), lds, st, d, ptrs, scal, p, part, splits, pht);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -827,6 +844,9 @@ static hipError_t back_g(const ClassDims& d, const MatPtrs& ptrs, Prec prec, con
   if (prec == PREC_BF3) return back_t<TileSquare, NumBF<3>, GSrc>(d, ptrs, scal, p, part, splits, pht, st);
   if (d.r <= 64) return back_t<TileNarrow, NumF16, GSrc>(d, ptrs, scal, p, part, splits, pht, st);
   if (d.r <= 128) return back_t<TileSquare, NumF16, GSrc>(d, ptrs, scal, p, part, splits, pht, st);
+  // several column tiles per row panel: 256 x 256 tiles halve the operand traffic per product
+  // and run one workgroup per CU with two register stages of loads in flight
+  if (d.r > 256) return back_t<TileHuge, NumF16, GSrc, 2>(d, ptrs, scal, p, part, splits, pht, st);
   return back_t<TileWide, NumF16, GSrc>(d, ptrs, scal, p, part, splits, pht, st);
 }
 hipError_t launch_back(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p, WsArr part, int splits, HalfArr pht, hipStream_t st) {
