@@ -281,7 +281,9 @@ OD_DEV void gemm_mainloop_deep(const SrcA& a, const SrcB& b, int m0, int n0, int
   auto k_of = [&](int i) { const int c = i + rot; return kbeg + (c >= nsteps ? c - nsteps : c) * T::KT; };
   LA la[PF];
   LB lb[PF];
-  if (nsteps >= 2 * PF && LA::interior(a, m0, kbeg + nsteps * T::KT) && LB::interior(b, n0, kbeg + nsteps * T::KT)) {
+  // (small tiles are chosen for short K loops on small grids: they keep the simple loop only)
+  if (T::MT * T::NT >= 128 * 128 && nsteps >= 2 * PF && LA::interior(a, m0, kbeg + nsteps * T::KT) &&
+      LB::interior(b, n0, kbeg + nsteps * T::KT)) {
     // Both tiles lie inside their sources for every step: loads without bounds checks, and a
     // main loop of straight-line code, so that the wait before a store to LDS is for the
     // oldest register stage only (the younger PF - 1 stay in flight across the barrier).

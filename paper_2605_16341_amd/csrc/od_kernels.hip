@@ -262,9 +262,14 @@ __global__ __launch_bounds__(256) void k_reduce_r(ClassDims d, WsArr part, int s
 // ------------------------------------------------------------------------------------
 template <class T, class Num>
 __global__ __launch_bounds__(T::THREADS) void k_gram(int rows, int r, WsArr a, WsArr part, int splits) {
+  static_assert(T::MT == T::NT, "the tile grid of a symmetric result must be symmetric");
   extern __shared__ __align__(16) char lds[];
   const int tiles = (r + T::NT - 1) / T::NT;
-  const int tn = blockIdx.x % tiles, tm = blockIdx.x / tiles;
+  // The result is symmetric: only the tiles (tm, tn) with tm <= tn are computed, row by row
+  // of the tile grid, and an off-diagonal tile is stored a second time, transposed.
+  int tm = 0, tn = blockIdx.x;
+  while (tn >= tiles - tm) { tn -= tiles - tm; ++tm; }
+  tn += tm;
   const int split = blockIdx.y, z = blockIdx.z;
   SrcF32 s{a.base + (int64_t)z * a.stride, rows, r, r};
   int kend;
@@ -276,6 +281,26 @@ __global__ __launch_bounds__(T::THREADS) void k_gram(int rows, int r, WsArr a, W
   for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
     if (row < r && col < r) out[(int64_t)row * r + col] = v;
   });
+  if (tm != tn) {
+    // lane (c, h) holds rows 8q + 4h .. 8q + 4h + 3 of column c: four consecutive entries of
+    // row c of the transposed tile (r is a multiple of 8, so they are inside or outside together)
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / T::WN, wn = wave % T::WN;
+#pragma unroll
+    for (int fm = 0; fm < T::FM; ++fm)
+#pragma unroll
+      for (int fn = 0; fn < T::FN; ++fn) {
+        const int col = tn * T::NT + wn * T::WTN + fn * 32 + (lane & 31);
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+          const int row0 = tm * T::MT + wm * T::WTM + fm * 32 + 8 * q + 4 * (lane >> 5);
+          if (col < r && row0 < r) {
+            const f32x4 v4 = {acc[fm][fn][4 * q], acc[fm][fn][4 * q + 1], acc[fm][fn][4 * q + 2], acc[fm][fn][4 * q + 3]};
+            *reinterpret_cast<f32x4*>(out + (int64_t)col * r + row0) = v4;
+          }
+        }
+      }
+  }
 }
 
 // ------------------------------------------------------------------------------------
@@ -878,7 +903,7 @@ static hipError_t gram_tt(int nb, int rows, int r, WsArr a, WsArr part, int spli
   hipError_t e = allow_lds(k_gram<T, Num>, lds);
   if (e != hipSuccess) return e;
   int tiles = (r + T::NT - 1) / T::NT;
-  hipLaunchKernelGGL((k_gram<T, Num>), dim3(tiles * tiles, splits, nb), dim3(T::THREADS), lds, st, rows, r, a, part, splits);
+  hipLaunchKernelGGL((k_gram<T, Num>), dim3(tiles * (tiles + 1) / 2, splits, nb), dim3(T::THREADS), lds, st, rows, r, a, part, splits);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }

@@ -50,15 +50,18 @@ def _sampled_check(w, index, variant, sample=48, seed=0):
     eye = torch.eye(r, device=dev, dtype=torch.float64)
     B = m0.double() + g1.double()
 
-    # --- properties
-    assert float((P.T @ P - eye).abs().max()) < 2e-5
+    # --- properties.  The last product of the orthogonalisation runs on two-part bf16 operands
+    # (2^-17 relative rounding each), so entries of P^T P - I are a few 2^-16; the bound is for
+    # the largest of up to r^2 = 4M of them.
+    ORTH_TOL = 4e-5
+    assert float((P.T @ P - eye).abs().max()) < ORTH_TOL
     t_p = f["T_P2"].double() @ f["T_P1"].double()
     assert bool((torch.diagonal(t_p) > 0).all())
     assert float(torch.tril(t_p, -1).abs().max()) <= 1e-6 * float(t_p.abs().max())
     praw = B @ q0.double()
     assert float(torch.linalg.norm(P @ t_p - praw) / torch.linalg.norm(praw)) < 2e-2
     if variant == "qr":
-        assert float((Qn.T @ Qn - eye).abs().max()) < 2e-5
+        assert float((Qn.T @ Qn - eye).abs().max()) < ORTH_TOL
         t_q = f["T_Q2"].double() @ f["T_Q1"].double()
         assert bool((torch.diagonal(t_q) > 0).all())
         assert float(torch.linalg.norm(Qn @ t_q - R) / torch.linalg.norm(R)) < 1e-4
