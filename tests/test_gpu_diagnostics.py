@@ -10,7 +10,7 @@ storage with fp16 operands (R carries a relative error of about 2^-11 per entry 
 import numpy as np
 import pytest
 
-from gpu_harness import GpuRun, oracle_for, to_device, to_host
+from gpu_harness import GpuRun, compare_step, oracle_for, to_device, to_host
 from oracle.orthdion_oracle import (OrthDionOracle, bf16_bits_to_f64, diagnostics, rank_policy,
                                     resize_right_factor)
 from paper_2605_16341_amd import binding, synth
@@ -36,12 +36,11 @@ def check_diag(got: dict, want: dict, x_dtype: str, ctx):
 
 
 def run_case(shapes, r, x_dtype, variant, steps, seed, ef="dion", mu=0.95, momentum_std=1e-3):
-    w = synth.Workload("diag", tuple(shapes), r=r, x_dtype=x_dtype, mu=mu, lr=0.01, steps=steps,
-                       momentum_std=momentum_std)
     nmat = len(shapes)
+    ranks = [r] * nmat if isinstance(r, int) else list(r)
     streams = [synth.power_law_stream(m, n, seed + 10 * i, out_dtype=x_dtype, orthonormal=True)
                for i, (m, n) in enumerate(shapes)]
-    states = [synth.initial_state(m, n, r, seed + 10 * i, x_dtype, momentum_std) for i, (m, n) in enumerate(shapes)]
+    states = [synth.initial_state(m, n, ranks[i], seed + 10 * i, x_dtype, momentum_std) for i, (m, n) in enumerate(shapes)]
     gpu = GpuRun(shapes, r, x_dtype, states, variant=variant, ef=ef, mu=mu, lr=0.01)
     gpu.opt.set_diagnostics(True)
     orc = OrthDionOracle(mu=mu, lr=0.01, variant=variant, ef=ef, x_bf16=(x_dtype == "bf16"))
@@ -55,8 +54,13 @@ def run_case(shapes, r, x_dtype, variant, steps, seed, ef="dion", mu=0.95, momen
             x, mom, q = cur[i]
             o = orc.step(x, grads[i], mom, q)
             want = diagnostics(o, mom, grads[i])
-            check_diag(got[i], want, x_dtype, (shapes[i], r, variant, "step", t))
+            check_diag(got[i], want, x_dtype, (shapes[i], ranks[i], variant, "step", t))
             cur[i] = (o["X_bits"] if x_dtype == "bf16" else o["X"], o["M"], o["Q"])
+            if t == steps - 1:
+                # the state itself, so that a result routed to the wrong matrix cannot hide
+                res = compare_step(gpu.fetch(i), o, x, 0.01)
+                for key in ("M", "Q", "P", "R"):
+                    assert res[key] <= (1e-4 if x_dtype == "f32" else 2e-2), (shapes[i], ranks[i], key, res[key])
 
 
 @pytest.mark.parametrize("variant", ["qr", "colnorm"])
@@ -69,6 +73,17 @@ def test_diagnostics_small(variant, x_dtype):
 def test_diagnostics_two_classes_interleaved(variant):
     # the table must come back in the caller's matrix order, not in shape-class order
     run_case([(128, 96), (64, 256), (128, 96)], 16, "f32", variant, steps=2, seed=710)
+
+
+@pytest.mark.parametrize("variant", ["qr", "colnorm"])
+@pytest.mark.parametrize("x_dtype", ["f32", "bf16"])
+def test_matrices_of_different_rank_in_one_handle(variant, x_dtype):
+    """Ranks per matrix ("sort-and-pack" of the adaptive-rank path): the Cholesky step runs per
+    rank over several shape classes, and here the two rank-32 classes are separated by a rank-16
+    one, so results and diagnostics must find their way back to the caller's matrix order."""
+    shapes = [(256, 192), (192, 256), (128, 160), (256, 192), (192, 256), (320, 288)]
+    ranks = [32, 16, 32, 32, 16, 264]
+    run_case(shapes, ranks, x_dtype, variant, steps=2, seed=770)
 
 
 @pytest.mark.parametrize("variant", ["qr", "colnorm"])
