@@ -254,11 +254,15 @@ OD_DEV int diag_tile_factor(f32x16& d_io, f32x16& zt_out, int lane) {
     const float t23 = (d23 - t02 * t03 - t12 * t13) * i22;
     const float p3 = d33 - t03 * t03 - t13 * t13 - t23 * t23;
     const float i33 = __builtin_amdgcn_rsqf(p3);
-    if (bad == 0) {
-      if (!(p0 > 0.f) || p0 > 3.0e38f) bad = 4 * g + 1;
-      else if (!(p1 > 0.f) || p1 > 3.0e38f) bad = 4 * g + 2;
-      else if (!(p2 > 0.f) || p2 > 3.0e38f) bad = 4 * g + 3;
-      else if (!(p3 > 0.f) || p3 > 3.0e38f) bad = 4 * g + 4;
+    // one test per group on the critical path (a NaN or an infinite pivot makes the sum fail
+    // the upper bound; fminf alone would skip a NaN); which of the four it was is worked out
+    // only when the test fails
+    const float pmin = fminf(fminf(p0, p1), fminf(p2, p3)), psum = (p0 + p1) + (p2 + p3);
+    if (bad == 0 && !(pmin > 0.f && psum < 3.0e38f)) {
+      if (!(p0 > 0.f) || !(p0 < 3.0e38f)) bad = 4 * g + 1;
+      else if (!(p1 > 0.f) || !(p1 < 3.0e38f)) bad = 4 * g + 2;
+      else if (!(p2 > 0.f) || !(p2 < 3.0e38f)) bad = 4 * g + 3;
+      else bad = 4 * g + 4;
     }
     // inverse of the 4 x 4 upper factor
     const float w01 = -(t01 * i11) * i00, w12 = -(t12 * i22) * i11, w23 = -(t23 * i33) * i22;
