@@ -54,8 +54,9 @@ constexpr int kPTile = 3 * kPPlane;    // bytes per pre-split tile
 // LDS: Wt[2] fp32 (W_JJ^T of even / odd steps) | panel[8] pre-split T(J, K)^T | vpanel[8] pre-split V(J, I)
 constexpr int kCholOffPanel = 2 * kCTileF * 4;
 constexpr int kCholOffVPanel = kCholOffPanel + kCNT * kPTile;
-constexpr int kCholOffSync = kCholOffVPanel + kCNT * kPTile;   // published[8] | next_ready[8] (ints)
-constexpr int kCholLds = kCholOffSync + 2 * kCNT * 4;
+constexpr int kCholOffSync = kCholOffVPanel + kCNT * kPTile;   // published[8] | s_ready[8] (ints)
+constexpr int kCholOffStash = kCholOffSync + 2 * kCNT * 4;      // two fp32 tile images: S(J, J+1) for the diagonal wave
+constexpr int kCholLds = kCholOffStash + 2 * 4096;
 constexpr int kCholSpinLimit = 1 << 22;  // bound of every wait below (never reached: the producers do not wait)
 
 #ifdef OD_CHOL_TIMING
@@ -311,7 +312,8 @@ __global__ __launch_bounds__(kCholThreads) void k_chol256(CholArgs a) {
   char* vpanel = lds_raw + kCholOffVPanel;                               // V(J, I) pre-split, one tile per I; before
                                                                          // step I-1 ends: the waiting tile (I, I)
   int* published = reinterpret_cast<int*>(lds_raw + kCholOffSync);       // tiles of step J published so far
-  int* next_ready = published + kCNT;                                    // tile (J+1, J+1) ready for its factorisation
+  int* s_ready = published + kCNT;                                       // S(J, J+1) has its last update and is in the stash
+  char* stash = lds_raw + kCholOffStash;                                 // buffer J & 1
 
   const int z = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -458,11 +460,13 @@ __global__ __launch_bounds__(kCholThreads) void k_chol256(CholArgs a) {
 #pragma unroll
       for (int v = 0; v < 16; ++v) tile[v] = 0.f;       // from now on the sum S'(K, J)
       // the waiting diagonal tile (K, K) -= T(J, K)^T T(J, K), operands read back from the panel
-      char* dk = vpanel + K * kPTile;
-      f32x16 dt = load_dtile(dk, lane);
-      lds_product(dt, panel + K * kPTile, panel + K * kPTile, true);
-      store_dtile(dk, dt, lane);
-      if (K == J + 1) lds_signal_add(next_ready + J, lane);
+      // (tile (J+1, J+1) gets this update from the diagonal wave itself, which is about to factor it)
+      if (K != J + 1) {
+        char* dk = vpanel + K * kPTile;
+        f32x16 dt = load_dtile(dk, lane);
+        lds_product(dt, panel + K * kPTile, panel + K * kPTile, true);
+        store_dtile(dk, dt, lane);
+      }
       lds_signal_add(published + J, lane);
     } else {
       store_presplit(vpanel + I * kPTile, res, lane);
@@ -484,16 +488,45 @@ __global__ __launch_bounds__(kCholThreads) void k_chol256(CholArgs a) {
     // the diagonal tiles: (0, 0) is factored at once, the others wait in LDS for their updates
     for (int I = 1; I < nt; ++I) store_dtile(vpanel + I * kPTile, load_tile(I, I), lane);
     do_diag(0, load_tile(0, 0));
+  } else {
+    // tile (0, 1) as loaded is what the diagonal wave needs first
+#pragma unroll
+    for (int s = 0; s < kCSlots; ++s) {
+      const int I = (int)(ownI >> (4 * s)) & 15, K = (int)(ownK >> (4 * s)) & 15;
+      if (I == 0 && K == 1 && K < nt) store_dtile(stash, acc[s], lane);     // made visible by the barrier below
+    }
   }
   lds_barrier();
   for (int J = 0; J < nt; ++J) {
     OD_TICK(4 + 4 * J);
     if (diag_wave) {
-      // ---- as soon as tile (J+1, J+1) has its last update, factor it
+      // ---- the serial chain stays in this wave: T(J, J+1) = W_JJ^T S(J, J+1) from the stash,
+      // tile (J+1, J+1) -= T^T T (both fp32 products with the accumulator as k-side operand,
+      // see panel_tile), then its factorisation.  The workers form T(J, J+1) again for the panel.
       if (J + 1 < nt) {
-        lds_wait_ge(next_ready + J, 1);
+        if (J > 0) lds_wait_ge(s_ready + J, 1);
         OD_TICK(5 + 4 * J);
-        do_diag(J + 1, load_dtile(vpanel + (J + 1) * kPTile, lane));
+        const f32x16 sj = load_dtile(stash + (J & 1) * 4096, lane);
+        f32x16 dn = load_dtile(vpanel + (J + 1) * kPTile, lane);
+        const float* wt = Wt + (J & 1) * kCTileF;
+        f32x4 mrow[4];
+#pragma unroll
+        for (int q = 0; q < 4; ++q) mrow[q] = *reinterpret_cast<const f32x4*>(wt + col * kCPitch + 8 * q + 4 * half);
+        f32x16 t1, t2;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { t1[v] = 0.f; t2[v] = 0.f; }
+#pragma unroll
+        for (int q = 0; q < 4; q += 2)
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            t1 = mfma_f32_k2(mrow[q][e], sj[4 * q + e], t1);
+            t2 = mfma_f32_k2(mrow[q + 1][e], sj[4 * q + 4 + e], t2);
+          }
+#pragma unroll
+        for (int v = 0; v < 16; ++v) t1[v] += t2[v];
+#pragma unroll
+        for (int v = 0; v < 16; ++v) dn = mfma_f32_k2(-t1[v], t1[v], dn);
+        do_diag(J + 1, dn);
       }
       OD_TICK(6 + 4 * J);
     } else {
@@ -524,6 +557,11 @@ __global__ __launch_bounds__(kCholThreads) void k_chol256(CholArgs a) {
         if (K > J && K < nt) {
           if (I > J) lds_product(acc[s], panel + I * kPTile, panel + K * kPTile, true);
           else lds_product(acc[s], panel + K * kPTile, vpanel + I * kPTile, false);
+          // S(J+1, J+2) is final now: hand it to the diagonal wave
+          if (I == J + 1 && K == J + 2) {
+            store_dtile(stash + ((J + 1) & 1) * 4096, acc[s], lane);
+            lds_signal_add(s_ready + J + 1, lane);
+          }
         }
       }
     }
