@@ -27,9 +27,9 @@ MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense fp16 / bf16 matrix cores, publishe
 # copy kernel of known size); see profiles/.  Keyed by (workload, phase); bytes per launch.
 MEASURED_TRAFFIC = {
     # profiles/orthdion_step_C2_hbm_counters.txt: 2.000 * FETCH_SIZE + 1.000 * WRITE_SIZE, bytes
-    ("C2", "efx"): 272488789,
-    ("C2", "back"): 186528993,
-    ("C2", "proj"): 155091914,
+    ("C2", "efx"): 272360352,
+    ("C2", "back"): 186303728,
+    ("C2", "proj"): 155488096,
 }
 
 
