@@ -43,7 +43,7 @@ from typing import Dict, Optional, Tuple
 import numpy as np
 
 __all__ = ["thin_qr_positive", "col_norm", "ef_coefficients", "OrthDionOracle",
-           "bf16_bits_to_f64", "f64_to_bf16_bits", "rel_fro", "effective_rank", "diagnostics", "rank_policy",
+           "bf16_bits_to_f64", "f64_to_bf16_bits", "rel_fro", "effective_rank", "diagnostics", "gradient_persistence", "rank_policy",
            "resize_right_factor"]
 
 
@@ -254,6 +254,20 @@ def diagnostics(step_out: Dict[str, np.ndarray], m_prev, g) -> Dict[str, float]:
         "nu": float(np.linalg.norm(q, 2)),
         "erank": effective_rank(r),
     }
+
+
+def gradient_persistence(p_t, g_t, p_prev, g_prev) -> float:
+    """phi_t = cos of the angle between the out-of-subspace parts of two consecutive gradients,
+    (I - P_t P_t^T) G_t and (I - P_{t-1} P_{t-1}^T) G_{t-1}, as matrices under the Frobenius
+    inner product (Sec. 6.3, App. J key quantities).  Its sign names the error-feedback regime:
+    coherent (> 0), stochastic (about 0), anti-correlated (< 0)."""
+    def outside(p, g):
+        g = bf16_bits_to_f64(g) if np.asarray(g).dtype == np.uint16 else np.asarray(g, dtype=np.float64)
+        p = np.asarray(p, dtype=np.float64)
+        return g - p @ (p.T @ g)
+    a, b = outside(p_t, g_t), outside(p_prev, g_prev)
+    na, nb = float(np.linalg.norm(a)), float(np.linalg.norm(b))
+    return float(np.sum(a * b)) / (na * nb) if na > 0 and nb > 0 else 0.0
 
 
 def rank_policy(e_t: float, r_t: int, ema_prev: float, r_min: int, r_max: int, alpha: float,

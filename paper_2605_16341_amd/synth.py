@@ -84,10 +84,22 @@ class GradientStream:
     signal: np.ndarray          # m x n, float64 or float32
     noise_std: float
     out_dtype: str              # "f32" or "bf16"
+    persistence: float = 0.0    # lag-1 correlation of the noise terms, in [-0.5, 0.5]
+
+    def _draw(self, step: int) -> np.ndarray:
+        rng = rng_for(self.seed + 1 + int(step))
+        return rng.standard_normal((self.m, self.n), dtype=np.float32)
 
     def gradient_f32(self, step: int) -> np.ndarray:
-        rng = rng_for(self.seed + 1 + int(step))
-        noise = rng.standard_normal((self.m, self.n), dtype=np.float32)
+        noise = self._draw(step)
+        if self.persistence != 0.0:
+            # moving average of two independent draws: unit variance, lag-1 correlation
+            # phi * sqrt(1 - phi^2) = persistence, zero correlation beyond lag 1
+            rho = float(self.persistence)
+            if abs(rho) > 0.5:
+                raise ValueError("persistence must lie in [-0.5, 0.5]")
+            phi = np.sign(rho) * np.sqrt((1.0 - np.sqrt(1.0 - 4.0 * rho * rho)) / 2.0)
+            noise = (np.float32(phi) * self._draw(step - 1) + np.float32(np.sqrt(1.0 - phi * phi)) * noise)
         g = (self.signal + np.float32(self.noise_std) * noise).astype(np.float32)
         return g
 
@@ -115,7 +127,7 @@ def inverse_index_stream(m: int, n: int, seed: int, noise_std: float = 0.01,
 def power_law_stream(m: int, n: int, seed: int, exponent: float = 0.5,
                      noise_energy: float = 0.05, rms: float = 1e-2,
                      out_dtype: str = "bf16", orthonormal: bool = True,
-                     components: Optional[int] = None) -> GradientStream:
+                     components: Optional[int] = None, persistence: float = 0.0) -> GradientStream:
     """Gradients whose signal has singular values ``i^-exponent`` and whose isotropic
     Gaussian noise carries ``noise_energy`` of the squared Frobenius norm.
 
@@ -123,7 +135,9 @@ def power_law_stream(m: int, n: int, seed: int, exponent: float = 0.5,
     ``orthonormal=False`` the singular-vector factors are Gaussian/sqrt(dim)
     stand-ins (used for the largest shapes, where an exact orthonormal factor
     would cost more than the test itself).  ``components`` limits the number of
-    spectral terms (default ``min(m, n)``).
+    spectral terms (default ``min(m, n)``).  ``persistence`` correlates the noise of
+    consecutive steps (the coherent / stochastic / anti-correlated regimes of the
+    error-feedback analysis, Sec. 6.3 of the paper).
     """
     rng = rng_for(seed)
     k = min(m, n) if components is None else int(components)
@@ -139,7 +153,7 @@ def power_law_stream(m: int, n: int, seed: int, exponent: float = 0.5,
         a = gaussian_factor(m, k, rng)
         c = gaussian_factor(n, k, rng)
         signal = (a * (c_s * s).astype(np.float32)[None, :]) @ c.T
-    return GradientStream(m, n, seed, signal, float(c_n), out_dtype)
+    return GradientStream(m, n, seed, signal, float(c_n), out_dtype, float(persistence))
 
 
 # --------------------------------------------------------------------------

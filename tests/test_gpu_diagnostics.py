@@ -35,10 +35,10 @@ def check_diag(got: dict, want: dict, x_dtype: str, ctx):
     assert got["nu"] <= want["nu"] * (1 + 1e-5) or x_dtype == "bf16"
 
 
-def run_case(shapes, r, x_dtype, variant, steps, seed, ef="dion", mu=0.95, momentum_std=1e-3):
+def run_case(shapes, r, x_dtype, variant, steps, seed, ef="dion", mu=0.95, momentum_std=1e-3, persistence=0.0):
     nmat = len(shapes)
     ranks = [r] * nmat if isinstance(r, int) else list(r)
-    streams = [synth.power_law_stream(m, n, seed + 10 * i, out_dtype=x_dtype, orthonormal=True)
+    streams = [synth.power_law_stream(m, n, seed + 10 * i, out_dtype=x_dtype, orthonormal=True, persistence=persistence)
                for i, (m, n) in enumerate(shapes)]
     states = [synth.initial_state(m, n, ranks[i], seed + 10 * i, x_dtype, momentum_std) for i, (m, n) in enumerate(shapes)]
     gpu = GpuRun(shapes, r, x_dtype, states, variant=variant, ef=ef, mu=mu, lr=0.01)
@@ -203,6 +203,14 @@ def test_beta_sweep_paper_form(beta):
     """Error-feedback coefficient sweep of Sec. 6.3 (paper-form EF, beta passed as mu) on a
     synthetic stream with fresh noise every step: diagnostics follow the oracle at every beta."""
     run_case([(256, 192)], 32, "f32", "qr", steps=4, seed=780, ef="paper", mu=beta, momentum_std=0.0)
+
+
+@pytest.mark.parametrize("rho", [-0.4, 0.4])
+@pytest.mark.parametrize("beta", [1.0, 0.1])
+def test_beta_regimes_with_correlated_noise(beta, rho):
+    """The coherent and anti-correlated regimes of Sec. 6.3: noise of consecutive steps
+    correlated with the given sign (the uncorrelated regime is the sweep above)."""
+    run_case([(256, 192)], 32, "bf16", "qr", steps=4, seed=785, ef="paper", mu=beta, momentum_std=0.0, persistence=rho)
 
 
 def test_polyak_form():

@@ -6,6 +6,7 @@ import numpy as np
 import pytest
 
 from oracle.orthdion_oracle import OrthDionOracle, diagnostics, effective_rank, rank_policy
+from paper_2605_16341_amd import synth
 from test_oracle_pins import jacobi_svd, rand_problem
 
 
@@ -222,3 +223,61 @@ def test_beta_sweep_residual_is_beta_times_the_lost_part():
             d = diagnostics(o, mom, g)
             assert abs(np.linalg.norm(o["M"]) - beta * d["tracking_error"] * d["b_norm"]) < 1e-10 * d["b_norm"]
             x, mom, q = o["X"], o["M"], o["Q"]
+
+
+def test_gradient_persistence_pins():
+    """phi_t against its definition's special cases: a repeated gradient gives 1, a negated
+    one -1, gradients inside the tracked subspace contribute nothing, orthogonal residuals 0;
+    and a hand-computed 3 x 2 case."""
+    from oracle.orthdion_oracle import gradient_persistence
+    rng = synth.rng_for(4242)
+    m, n, r = 12, 9, 3
+    p = synth.random_orthonormal(m, r, rng)
+    g = rng.standard_normal((m, n))
+    assert abs(gradient_persistence(p, g, p, g) - 1.0) < 1e-12
+    assert abs(gradient_persistence(p, g, p, -g) + 1.0) < 1e-12
+    inside = p @ rng.standard_normal((r, n))                  # lies in span(P): no residual of its own
+    # adding an in-subspace part changes nothing
+    assert abs(gradient_persistence(p, g + inside, p, g) - 1.0) < 1e-9
+    # hand case: P = e1 (3 x 1); residuals are rows 2..3 of the gradients
+    p1 = np.array([[1.0], [0.0], [0.0]])
+    ga = np.array([[5.0, 5.0], [1.0, 0.0], [0.0, 1.0]])
+    gb = np.array([[-7.0, 2.0], [1.0, 1.0], [0.0, 0.0]])
+    # <(1,0,0,1),(1,1,0,0)> / (sqrt2 sqrt2) = 1/2
+    assert abs(gradient_persistence(p1, ga, p1, gb) - 0.5) < 1e-12
+    # different subspaces on the two sides
+    p2 = np.array([[0.0], [1.0], [0.0]])
+    # residual of gb outside e2: rows 1 and 3: (-7, 2, 0, 0); residual of ga outside e1: (1,0,0,1) in rows 2,3
+    # as 3 x 2 matrices: A = [[0,0],[1,0],[0,1]], B = [[-7,2],[0,0],[0,0]] -> inner 0
+    assert abs(gradient_persistence(p1, ga, p2, gb)) < 1e-12
+
+
+@pytest.mark.parametrize("rho", [-0.4, 0.0, 0.4])
+def test_synthetic_streams_have_the_persistence_they_claim(rho):
+    """The noise of consecutive synthetic gradients is correlated as requested, and the oracle's
+    phi_t of an Orth-Dion run on that stream takes the sign of the regime."""
+    from oracle.orthdion_oracle import OrthDionOracle, gradient_persistence
+    m, n, r = 96, 80, 8
+    # the signal has exactly r components, so that what lies outside the tracked subspace is noise
+    stream = synth.power_law_stream(m, n, 5150, noise_energy=0.5, out_dtype="f32", persistence=rho, components=r)
+    noise = [stream.gradient_f32(t).astype(np.float64) - stream.signal for t in range(6)]
+    corr = [float(np.sum(noise[t] * noise[t + 1]) / (np.linalg.norm(noise[t]) * np.linalg.norm(noise[t + 1]))) for t in range(5)]
+    assert abs(np.mean(corr) - rho) < 0.03, corr
+    lag2 = float(np.sum(noise[0] * noise[2]) / (np.linalg.norm(noise[0]) * np.linalg.norm(noise[2])))
+    assert abs(lag2) < 0.05
+    st = synth.initial_state(m, n, r, 5150, "f32", 0.0)
+    orc = OrthDionOracle(mu=0.3, lr=0.01, variant="qr", ef="paper", x_bf16=False)
+    x, mom, q = st.X.astype(np.float64), st.M.astype(np.float64), st.Q.astype(np.float64)
+    phis, prev = [], None
+    for t in range(6):
+        g = stream.gradient(t)
+        o = orc.step(x, g, mom, q)
+        if prev is not None:
+            phis.append(gradient_persistence(o["P"], g, prev[0], prev[1]))
+        prev = (o["P"], g)
+        x, mom, q = o["X"], o["M"], o["Q"]
+    mean_phi = float(np.mean(phis))
+    if rho == 0.0:
+        assert abs(mean_phi) < 0.1, phis
+    else:
+        assert np.sign(mean_phi) == np.sign(rho) and abs(mean_phi) > 0.1, phis
