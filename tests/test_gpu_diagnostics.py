@@ -198,6 +198,75 @@ def test_adaptive_rank_loop_follows_the_oracle():
     assert ranks[-1] < r0, ranks          # the rule did shrink the rank on this spectrum
 
 
+def test_adaptive_rank_loop_over_a_matrix_set():
+    """Ada-Orth-Dion over three matrices with their own ranks: every step the rank rule runs per
+    matrix on the device's effective-rank estimate; when any rank changes, the warm-start
+    factors are resized and the handle is rebuilt with the new rank list (matrices of equal
+    shape and rank share a batch, the Cholesky steps run per rank).  Ranks and states must
+    follow an oracle loop that is driven by its own estimates."""
+    import torch
+    shapes = [(192, 160), (160, 224), (192, 160)]
+    exps = [1.5, 0.4, 1.0]                        # fast, slow and medium spectral decay
+    alpha, gamma, r_min, r_max = 0.6, 1.1, 8, 48
+    nmat = len(shapes)
+    streams = [synth.power_law_stream(m, n, 860 + 7 * i, exponent=exps[i], noise_energy=0.01, out_dtype="f32",
+                                      orthonormal=True) for i, (m, n) in enumerate(shapes)]
+    ranks = [48, 48, 48]
+    states = [synth.initial_state(m, n, ranks[i], 860 + 7 * i, "f32", 0.0) for i, (m, n) in enumerate(shapes)]
+    pads = synth.rng_for(861)
+    orc = OrthDionOracle(mu=0.95, lr=0.01, variant="qr", x_bf16=False)
+    host = [(s.X.astype(np.float64), s.M.astype(np.float64), s.Q.astype(np.float64)) for s in states]
+    X = [to_device(s.X, torch) for s in states]
+    M = [to_device(s.M, torch) for s in states]
+    Q = [to_device(s.Q, torch) for s in states]
+    ema = [float(r) for r in ranks]
+    opt = binding.OrthDion(shapes, list(ranks), x_dtype="f32", variant="qr")
+    opt.set_diagnostics(True)
+    history = []
+    for t in range(6):
+        grads = [st.gradient(t) for st in streams]
+        opt.step(X, [to_device(g, torch) for g in grads], M, Q)
+        torch.cuda.synchronize()
+        assert opt.info() == [0] * nmat
+        dev = opt.diagnostics()
+        new_ranks = list(ranks)
+        for i in range(nmat):
+            xo, mo, qo = host[i]
+            o = orc.step(xo, grads[i], mo, qo)
+            want = diagnostics(o, mo, grads[i])
+            assert abs(dev[i]["erank"] - want["erank"]) <= 1e-3 * want["erank"], (t, i)
+            ema_dev, nxt_dev = binding.orthdion_rank_policy(dev[i]["erank"], ema[i], r_min, r_max, alpha, gamma)
+            ema_orc, nxt_orc = rank_policy(want["erank"], ranks[i], ema[i], r_min, r_max, alpha, gamma)
+            if abs(gamma * ema_orc - round(gamma * ema_orc)) >= 2e-2:      # away from a rounding edge
+                assert nxt_dev == nxt_orc, (t, i, nxt_dev, nxt_orc)
+            ema[i] = ema_orc
+            new_ranks[i] = nxt_orc
+            qn = o["Q"]
+            if nxt_orc != ranks[i]:
+                grow = max(nxt_orc - ranks[i], 0)
+                pad = pads.standard_normal((shapes[i][1], grow)).astype(np.float32) / np.sqrt(shapes[i][1]) if grow else None
+                qn = resize_right_factor(qn, nxt_orc, pad.astype(np.float64) if pad is not None else None)
+                q_new = torch.empty((shapes[i][1], nxt_orc), dtype=torch.float32, device="cuda:0")
+                dpad = to_device(pad, torch) if pad is not None else None
+                binding.orthdion_resize_q(Q[i].data_ptr(), shapes[i][1], ranks[i], q_new.data_ptr(), nxt_orc,
+                                          dpad.data_ptr() if dpad is not None else 0,
+                                          torch.cuda.current_stream().cuda_stream)
+                torch.cuda.synchronize()
+                Q[i] = q_new
+            host[i] = (o["X"], o["M"], qn)
+            assert np.linalg.norm(to_host(M[i], torch).astype(np.float64) - o["M"]) <= 1e-4 * np.linalg.norm(o["M"]), (t, i)
+            assert np.linalg.norm(to_host(Q[i], torch).astype(np.float64) - qn) <= 1e-4 * np.linalg.norm(qn), (t, i)
+        if new_ranks != ranks:
+            opt.close()
+            opt = binding.OrthDion(shapes, list(new_ranks), x_dtype="f32", variant="qr")
+            opt.set_diagnostics(True)
+            ranks = new_ranks
+        history.append(tuple(ranks))
+    # the three spectra end at different ranks, and the fast-decaying one shrank
+    assert len(set(history[-1])) >= 2, history
+    assert history[-1][0] < 48, history
+
+
 @pytest.mark.parametrize("beta", [1.0, 0.5, 0.1, 0.05])
 def test_beta_sweep_paper_form(beta):
     """Error-feedback coefficient sweep of Sec. 6.3 (paper-form EF, beta passed as mu) on a
