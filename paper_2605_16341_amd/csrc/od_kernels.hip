@@ -652,8 +652,10 @@ __global__ __launch_bounds__(T::THREADS) void k_efx(ClassDims d, MatPtrs ptrs, c
 //     issued before the K loop would not overlap it: the loop's waits for its own operand
 //     loads complete in issue order, behind the older requests.)
 // ------------------------------------------------------------------------------------
+// (second bound: four waves per SIMD, i.e. at most 128 registers, so that two of these 8-wave
+// workgroups share a CU as the last point above needs)
 template <bool XBF, bool GBF>
-__global__ __launch_bounds__(512, 2) void k_efx_h(ClassDims d, MatPtrs ptrs, const float* scal, HalfArr ph, HalfArr rh,
+__global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, const float* scal, HalfArr ph, HalfArr rh,
                                                HalfArr qh, float a_coef, float b_coef, float lr) {
   constexpr int TJ = 128, TI = 128, KT = 32, PITCH = KT * 2 + 16, PLANE = 128 * PITCH, BUF = 3 * PLANE;
   extern __shared__ __align__(16) char lds[];
