@@ -124,3 +124,15 @@ def test_workspace_grows_with_the_set():
     assert b.orthdion_workspace_bytes(two) > 30 * b.orthdion_workspace_bytes(one) // 2
     b.orthdion_destroy(one)
     b.orthdion_destroy(two)
+
+
+def test_binding_phase_and_diagnostic_names_follow_the_header():
+    """The binding's name lists are in the header's enum order and of its length."""
+    import re
+    from paper_2605_16341_amd import binding
+    text = open(os.path.join(os.path.dirname(__file__), "..", "include", "orthdion.h")).read()
+    phases = re.findall(r"ORTHDION_PHASE_([A-Z_]+)\s*=\s*(\d+)", text)
+    assert [name.lower() for name, _ in phases] == binding.PHASES
+    assert [int(v) for _, v in phases] == list(range(len(phases)))
+    assert int(re.search(r"ORTHDION_NPHASE\s*=\s*(\d+)", text).group(1)) == len(binding.PHASES)
+    assert int(re.search(r"ORTHDION_NDIAG\s*=\s*(\d+)", text).group(1)) == len(binding.DIAG)

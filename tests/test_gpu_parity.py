@@ -260,3 +260,36 @@ def test_step_replayed_from_a_hip_graph_matches_eager_bit_for_bit():
             a, b = eager.fetch(i, with_factors=False), twin.fetch(i, with_factors=False)
             for key in ("X", "M", "Q"):
                 assert a[key].tobytes() == b[key].tobytes(), (t, i, key)
+
+
+def test_phase_profile_counts_and_leaves_results_alone():
+    """orthdion_profile_begin / _end: every phase is reported once per step and batch, the two
+    Cholesky phases once per step and rank (they run for all shape classes of a rank at
+    once); a profiled run gives bit-identical results; begin twice or end without begin fail."""
+    import torch
+    shapes = ((256, 128), (128, 512), (256, 128), (96, 96))     # three shape classes, one rank
+    w = synth.Workload("prof", shapes, r=32, x_dtype="bf16", steps=3)
+    nmat = len(shapes)
+    states = [synth.make_state(w, i) for i in range(nmat)]
+    grads = [[synth.make_stream(w, i).gradient(t) for i in range(nmat)] for t in range(3)]
+    runs = []
+    for profiled in (False, True):
+        gpu = GpuRun(w.shapes, w.r, w.x_dtype, states, mu=w.mu, lr=w.lr)
+        if profiled:
+            binding.orthdion_profile_begin(gpu.opt.handle, (1 << binding.ORTHDION_NPHASE) - 1, 2)
+            with pytest.raises(binding.OrthDionError):
+                binding.orthdion_profile_begin(gpu.opt.handle, 1, 1)
+        for t in range(3):                                       # one step more than the profile holds
+            assert gpu.step(grads[t]) == [0] * nmat
+        if profiled:
+            prof = binding.orthdion_profile_end(gpu.opt.handle)
+            assert set(prof) == set(binding.PHASES)
+            for name, (ms, count) in prof.items():
+                assert ms > 0.0, name
+                assert count == (2 if name.startswith("chol_") else 2 * 3), (name, count)
+            with pytest.raises(binding.OrthDionError):
+                binding.orthdion_profile_end(gpu.opt.handle)
+        runs.append([gpu.fetch(i, with_factors=False) for i in range(nmat)])
+    for a, b in zip(*runs):
+        for key in ("X", "M", "Q"):
+            assert a[key].tobytes() == b[key].tobytes(), key
