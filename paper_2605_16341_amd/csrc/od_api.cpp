@@ -291,8 +291,11 @@ static int orth_finish(const Batch& b, char* ws, int rows, size_t off_a0, size_t
   const HalfArr none{nullptr, 0};
   OD_TRY(od::launch_apply(nb, rows, r, a0, w, a1, nullptr, none, none, exact, st));
   OD_TRY(od::launch_gram(nb, rows, r, a1, part, splits, exact, st));
-  OD_TRY(od::launch_corr(nb, r, part, splits, t2, w, scal, 2 + info_slot, info, info_slot, st));
-  OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, hn, ht, exact, st));
+  // fast precision: the second pass as a correction a1 - a1 Phi(E) (one fp16 product; a1 itself
+  // stays in fp32); exact precision: the product a1 (I - Phi(E)) on six-product operands
+  OD_TRY(od::launch_corr(nb, r, part, splits, t2, w, exact ? 0 : 1, scal, 2 + info_slot, info, info_slot, st));
+  if (exact) OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, hn, ht, exact, st));
+  else OD_TRY(od::launch_apply_correction(nb, rows, r, a1, w, a0, q_out, hn, ht, st));
   return ORTHDION_OK;
 }
 

@@ -194,7 +194,9 @@ template <class T, class Num, class GSrc, int PF>
 __global__ __launch_bounds__(T::THREADS, (min_waves_per_simd<T, PF>())) void k_back(ClassDims d, MatPtrs ptrs, const float* scal, WsArr p, WsArr part, int splits, HalfArr pht) {
   extern __shared__ __align__(16) char lds[];
   const int tiles_n = (d.r + T::NT - 1) / T::NT;
-  const int tn = blockIdx.x % tiles_n, tm = blockIdx.x / tiles_n;
+  // as in the projection: the column tiles of one panel of B share an XCD's L2
+  const int bid = tiles_n > 1 ? xcd_contiguous(blockIdx.x, gridDim.x) : blockIdx.x;
+  const int tn = bid % tiles_n, tm = bid / tiles_n;
   const int split = blockIdx.y, z = blockIdx.z;
   SrcSum<GSrc> a = make_b_source<GSrc>(d, ptrs, z);      // read as [k = row i][operand row = column j]
   SrcF32 b{p.base + (int64_t)z * p.stride, d.m, d.r, d.r};
@@ -267,10 +269,12 @@ __global__ __launch_bounds__(T::THREADS) void k_gram(int rows, int r, WsArr a, W
   const int tiles = (r + T::NT - 1) / T::NT;
   // The result is symmetric: only the tiles (tm, tn) with tm <= tn are computed, row by row
   // of the tile grid, and an off-diagonal tile is stored a second time, transposed.
-  int tm = 0, tn = blockIdx.x;
+  // All tiles of one row split read the same rows of A: they get consecutive places on one XCD.
+  const int logical = xcd_contiguous(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
+  int tm = 0, tn = logical % (int)gridDim.x;
   while (tn >= tiles - tm) { tn -= tiles - tm; ++tm; }
   tn += tm;
-  const int split = blockIdx.y, z = blockIdx.z;
+  const int split = logical / (int)gridDim.x, z = blockIdx.z;
   SrcF32 s{a.base + (int64_t)z * a.stride, rows, r, r};
   int kend;
   const int kbeg = split_begin(rows, splits, T::KT, split, &kend);
@@ -306,13 +310,21 @@ __global__ __launch_bounds__(T::THREADS) void k_gram(int rows, int r, WsArr a, W
 // ------------------------------------------------------------------------------------
 // out = A W with W upper triangular (the triangular solve of CholeskyQR as a product
 // with the explicit inverse factor)
+//
+// CORR: the second pass of CholeskyQR2 in correction form.  `w` holds Phi(E) (entries far
+// below one) and the result is A - A Phi: the product is a small correction of A, so one fp16
+// product (A scaled by 2^10, Phi by 2^13: relative error 2^-11 of a term of size |E|) is
+// enough, and A itself enters in full fp32 precision.
 // ------------------------------------------------------------------------------------
-template <class T, class Num, bool DEEP>
+constexpr float kPhiScale = 8192.f;
+template <class T, class Num, bool DEEP, bool CORR>
 __global__ __launch_bounds__(T::THREADS) void k_apply(int rows, int r, WsArr a, WsArr w, WsArr out, MatPtrs ptrs, int to_q,
                                                       HalfArr hn, HalfArr ht) {
   extern __shared__ __align__(16) char lds[];
   const int tiles_n = (r + T::NT - 1) / T::NT;
-  const int tn = blockIdx.x % tiles_n, tm = blockIdx.x / tiles_n;
+  // the column tiles of one row panel of A share an XCD's L2
+  const int bid = tiles_n > 1 ? xcd_contiguous(blockIdx.x, gridDim.x) : blockIdx.x;
+  const int tn = bid % tiles_n, tm = bid / tiles_n;
   const int z = blockIdx.z;
   SrcF32 sa{a.base + (int64_t)z * a.stride, rows, r, r};
   SrcF32 sw{w.base + (int64_t)z * w.stride, r, r, r};
@@ -320,8 +332,25 @@ __global__ __launch_bounds__(T::THREADS) void k_apply(int rows, int r, WsArr a, 
   if (kend > r) kend = r;
   f32x16 acc[T::FM][T::FN];
   zero_acc<T>(acc);
-  if constexpr (DEEP) gemm_mainloop_deep<T, Num, KC, SrcF32, KS, SrcF32, 3>(sa, sw, tm * T::MT, tn * T::NT, 0, kend, 1.f, 1.f, lds, acc);
-  else gemm_mainloop<T, Num, KC, SrcF32, KS, SrcF32>(sa, sw, tm * T::MT, tn * T::NT, 0, kend, 1.f, 1.f, lds, acc);
+  const float s_a = CORR ? kUnitScale : 1.f, s_w = CORR ? kPhiScale : 1.f;
+  if constexpr (DEEP) gemm_mainloop_deep<T, Num, KC, SrcF32, KS, SrcF32, 3>(sa, sw, tm * T::MT, tn * T::NT, 0, kend, s_a, s_w, lds, acc);
+  else gemm_mainloop<T, Num, KC, SrcF32, KS, SrcF32>(sa, sw, tm * T::MT, tn * T::NT, 0, kend, s_a, s_w, lds, acc);
+  if constexpr (CORR) {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int wm = wave / T::WN, wn = wave % T::WN;
+    constexpr float inv = 1.f / (kUnitScale * kPhiScale);
+#pragma unroll
+    for (int fm = 0; fm < T::FM; ++fm)
+#pragma unroll
+      for (int fn = 0; fn < T::FN; ++fn)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = tm * T::MT + wm * T::WTM + fm * 32 + acc_row(v, lane);
+          const int col = tn * T::NT + wn * T::WTN + fn * 32 + acc_col(lane);
+          const float a1 = (row < rows && col < r) ? sa.p[(int64_t)row * r + col] : 0.f;
+          acc[fm][fn][v] = a1 - inv * acc[fm][fn][v];
+        }
+  }
   float* dst = to_q ? ptrs.Q[z] : out.base + (int64_t)z * out.stride;
   for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
     if (row < rows && col < r) dst[(int64_t)row * r + col] = v;
@@ -421,8 +450,8 @@ constexpr float kMaxGramDeviation = 0.1f;   // largest |E| entry the first-order
 // triangle + half the diagonal, and the inverse factor I - Phi(E) + O(E^2).  Writes
 // T2 = I + Phi(E), W2 = I - Phi(E) and the largest |E| entry (scal[mat][scal_slot]).
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_corr(int r, WsArr part, int splits, WsArr t2, WsArr w2, float* scal, int scal_slot,
-                                              int* info, int info_slot) {
+__global__ __launch_bounds__(256) void k_corr(int r, WsArr part, int splits, WsArr t2, WsArr w2, int phi_only, float* scal,
+                                              int scal_slot, int* info, int info_slot) {
   const int z = blockIdx.y;
   const float* src = part.base + (int64_t)z * part.stride;
   float* tp = t2.base + (int64_t)z * t2.stride;
@@ -447,7 +476,7 @@ __global__ __launch_bounds__(256) void k_corr(int r, WsArr part, int splits, WsA
       else if (j == i) phi = 0.5f * e;
       const float id = (i == j) ? 1.f : 0.f;
       to[c] = id + phi;
-      wo[c] = id - phi;
+      wo[c] = phi_only ? phi : id - phi;
     }
     reinterpret_cast<f32x4*>(tp)[i4] = to;
     reinterpret_cast<f32x4*>(wp)[i4] = wo;
@@ -920,27 +949,30 @@ hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits,
   return exact ? gram_t<NumBF<3>>(nb, rows, r, a, part, splits, st) : gram_t<NumBF<2>>(nb, rows, r, a, part, splits, st);
 }
 
-template <class T, class Num, bool DEEP>
+template <class T, class Num, bool DEEP, bool CORR>
 static hipError_t apply_tt(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
   constexpr int lds = T::template lds_bytes<Num>();
-  hipError_t e = allow_lds(k_apply<T, Num, DEEP>, lds);
+  hipError_t e = allow_lds(k_apply<T, Num, DEEP, CORR>, lds);
   if (e != hipSuccess) return e;
   MatPtrs none = {};
   dim3 grid(((rows + T::MT - 1) / T::MT) * ((r + T::NT - 1) / T::NT), 1, nb);
-  hipLaunchKernelGGL((k_apply<T, Num, DEEP>), grid, dim3(T::THREADS), lds, st, rows, r, a, w, out, ptrs ? *ptrs : none, ptrs ? 1 : 0, hn, ht);
+  hipLaunchKernelGGL((k_apply<T, Num, DEEP, CORR>), grid, dim3(T::THREADS), lds, st, rows, r, a, w, out, ptrs ? *ptrs : none, ptrs ? 1 : 0, hn, ht);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
-template <class Num>
+template <class Num, bool CORR>
 static hipError_t apply_t(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
   const int big = ((rows + 127) / 128) * ((r + 127) / 128) * nb;
-  if (big < 512) return apply_tt<TileSmall, Num, true>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
+  if (big < 512) return apply_tt<TileSmall, Num, true, CORR>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
   // 128 columns per tile: the loop of a column tile ends at its last row of W (upper triangular),
   // so narrower tiles skip more of the zero half than 256-column ones would (measured -10 %)
-  return apply_tt<TileSquare, Num, false>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
+  return apply_tt<TileSquare, Num, false, CORR>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
 }
 hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs, HalfArr hn, HalfArr ht, int exact, hipStream_t st) {
-  return exact ? apply_t<NumBF<3>>(nb, rows, r, a, w, out, q_ptrs, hn, ht, st) : apply_t<NumBF<2>>(nb, rows, r, a, w, out, q_ptrs, hn, ht, st);
+  return exact ? apply_t<NumBF<3>, false>(nb, rows, r, a, w, out, q_ptrs, hn, ht, st) : apply_t<NumBF<2>, false>(nb, rows, r, a, w, out, q_ptrs, hn, ht, st);
+}
+hipError_t launch_apply_correction(int nb, int rows, int r, WsArr a, WsArr phi, WsArr out, const MatPtrs* q_ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
+  return apply_t<NumF16, true>(nb, rows, r, a, phi, out, q_ptrs, hn, ht, st);
 }
 
 template <class T, class Num, class DirA>
@@ -1023,12 +1055,12 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp
   return hipSuccess;
 }
 
-hipError_t launch_corr(int nb, int r, WsArr part, int splits, WsArr t2, WsArr w2, float* scal, int scal_slot, int* info,
-                       int info_slot, hipStream_t st) {
+hipError_t launch_corr(int nb, int r, WsArr part, int splits, WsArr t2, WsArr w2, int phi_only, float* scal, int scal_slot,
+                       int* info, int info_slot, hipStream_t st) {
   int64_t count = (int64_t)r * r;
   int blocks = (int)((count / 4 + 255) / 256);
   if (blocks > 1024) blocks = 1024;
-  hipLaunchKernelGGL(k_corr, dim3(blocks, nb), dim3(256), 0, st, r, part, splits, t2, w2, scal, scal_slot, info, info_slot);
+  hipLaunchKernelGGL(k_corr, dim3(blocks, nb), dim3(256), 0, st, r, part, splits, t2, w2, phi_only, scal, scal_slot, info, info_slot);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
