@@ -50,10 +50,14 @@ def _sampled_check(w, index, variant, sample=48, seed=0):
     eye = torch.eye(r, device=dev, dtype=torch.float64)
     B = m0.double() + g1.double()
 
-    # --- properties.  The last product of the orthogonalisation runs on two-part bf16 operands
-    # (2^-17 relative rounding each), so entries of P^T P - I are a few 2^-16; the bound is for
-    # the largest of up to r^2 = 4M of them.
-    ORTH_TOL = 4e-5
+    # --- properties.  The second CholeskyQR pass corrects the deviation E it measures with a
+    # Gram matrix of two-part bf16 operands (2^-17 relative rounding each): what it cannot see
+    # is that measurement's own rounding, a few 2^-18 per entry; the bound is for the largest of
+    # up to r^2 = 4M entries (observed: 3.2e-6 to 4.4e-6 at every benchmark shape).  With
+    # ColNorm the warm-start factor has unit but not orthogonal columns, B Q is worse conditioned,
+    # the deviation after the first pass is larger and its second-order remainder shows (1.6e-5
+    # at r = 1024).
+    ORTH_TOL = 1e-5 if variant == "qr" else 4e-5
     assert float((P.T @ P - eye).abs().max()) < ORTH_TOL
     t_p = f["T_P2"].double() @ f["T_P1"].double()
     assert bool((torch.diagonal(t_p) > 0).all())
