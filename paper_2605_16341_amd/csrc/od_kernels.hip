@@ -22,6 +22,7 @@ typedef Tile<128, 128, 32, 2, 2> TileSquare;   // wave tile 64 x 64
 typedef Tile<128, 64, 32, 4, 1> TileNarrow;    // r <= 64: wave tile 32 x 64
 typedef Tile<64, 256, 32, 2, 2> TileFlat;      // projection, r > 128: twice the row panels, half the splits (wave tile 32 x 128)
 typedef Tile<256, 256, 32, 2, 2> TileHuge;    // back-projection, r > 256: wave tile 128 x 128, one workgroup per CU
+typedef Tile<128, 128, 64, 2, 2> TileSquareDeepK;   // single-part operands: half the k steps at the same LDS footprint
 typedef Tile<64, 64, 64, 2, 2> TileSmall;      // wave tile 32 x 32: small problems that need many workgroups
 
 constexpr float kUnitScale = 1024.f;           // scale of orthonormal / unit-column factors in fp16
@@ -966,7 +967,10 @@ static hipError_t apply_t(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, 
   if (big < 512) return apply_tt<TileSmall, Num, true, CORR>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
   // 128 columns per tile: the loop of a column tile ends at its last row of W (upper triangular),
   // so narrower tiles skip more of the zero half than 256-column ones would (measured -10 %)
-  return apply_tt<TileSquare, Num, false, CORR>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
+  // one operand part leaves LDS room for 64-deep steps at two workgroups per CU (measured -13 to
+  // -23 %); with two parts the deeper tile halves the occupancy and loses
+  if constexpr (Num::PARTS == 1) return apply_tt<TileSquareDeepK, Num, false, CORR>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
+  else return apply_tt<TileSquare, Num, false, CORR>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
 }
 hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs, HalfArr hn, HalfArr ht, int exact, hipStream_t st) {
   return exact ? apply_t<NumBF<3>, false>(nb, rows, r, a, w, out, q_ptrs, hn, ht, st) : apply_t<NumBF<2>, false>(nb, rows, r, a, w, out, q_ptrs, hn, ht, st);
