@@ -690,7 +690,21 @@ __global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, con
   constexpr int TJ = 128, TI = 128, KT = 32, PITCH = KT * 2 + 16, PLANE = 128 * PITCH, BUF = 3 * PLANE;
   extern __shared__ __align__(16) char lds[];
   const int tiles_i = (d.m + TI - 1) / TI;
-  const int ti = blockIdx.x % tiles_i, tj = blockIdx.x / tiles_i;
+  int ti = blockIdx.x % tiles_i, tj = blockIdx.x / tiles_i;
+  if (d.r > 256) {
+    // Long K loops re-read the panels of P, R and Q often enough to matter: bands of eight tile
+    // columns, row-major inside a band, one contiguous range of that order per XCD, so that the
+    // 64 workgroups an XCD holds at a time form an 8 x 8 block of tiles and every panel fetched
+    // into its L2 serves eight of them (measured -4 to -5 %; at r = 256 the plain order is 2 us
+    // faster).
+    const int tiles_j = (d.n + TJ - 1) / TJ;
+    const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int band = logical / (tiles_i * 8);
+    const int in_band = logical - band * tiles_i * 8;
+    const int bw = min(8, tiles_j - band * 8);
+    ti = in_band / bw;
+    tj = band * 8 + in_band % bw;
+  }
   const int z = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wi = wave & 3, wj = wave >> 2, c = lane & 31;
