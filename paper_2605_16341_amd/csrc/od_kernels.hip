@@ -416,11 +416,10 @@ OD_DEV SrcF32 sub_view(const float* base, int r, int row0, int col0, int rows, i
 }
 
 template <class T, class Num, class DirA>
-__global__ __launch_bounds__(T::THREADS) void k_sgemm(SgemmArgs g) {
-  extern __shared__ __align__(16) char lds[];
+OD_DEV void sgemm_tile(const SgemmArgs& g, int bx, int bz, char* lds) {
   const int tiles_n = (g.Nc + T::NT - 1) / T::NT;
-  const int tn = blockIdx.x % tiles_n, tm = blockIdx.x / tiles_n;
-  const int q = blockIdx.z % g.nq, z = blockIdx.z / g.nq;
+  const int tn = bx % tiles_n, tm = bx / tiles_n;
+  const int q = bz % g.nq, z = bz / g.nq;
   const int o = q * g.q_step;
   const float* ap = g.a.base + (int64_t)z * g.a.stride;
   const float* bp = g.b.base + (int64_t)z * g.b.stride;
@@ -439,6 +438,22 @@ __global__ __launch_bounds__(T::THREADS) void k_sgemm(SgemmArgs g) {
       *dst = g.alpha * v + g.beta * old;
     }
   });
+}
+
+template <class T, class Num, class DirA>
+__global__ __launch_bounds__(T::THREADS) void k_sgemm(SgemmArgs g) {
+  extern __shared__ __align__(16) char lds[];
+  sgemm_tile<T, Num, DirA>(g, blockIdx.x, blockIdx.z, lds);
+}
+
+// Two independent products in one launch (the first `tiles1` workgroups of a matrix work on
+// g1, the rest on g2): the blocked factorisation is a chain of short launches, and pairing
+// the products that do not depend on each other shortens it.
+template <class T, class Num, class DirA1, class DirA2>
+__global__ __launch_bounds__(T::THREADS) void k_sgemm_pair(SgemmArgs g1, SgemmArgs g2, int tiles1) {
+  extern __shared__ __align__(16) char lds[];
+  if ((int)blockIdx.x < tiles1) sgemm_tile<T, Num, DirA1>(g1, blockIdx.x, blockIdx.z, lds);
+  else sgemm_tile<T, Num, DirA2>(g2, blockIdx.x - tiles1, blockIdx.z, lds);
 }
 
 
@@ -1015,6 +1030,30 @@ static hipError_t sgemm(int nb, const SgemmArgs& g, bool a_kc, int exact, hipStr
   return a_kc ? sgemm_t<NumBF<2>, KC>(nb, g, st) : sgemm_t<NumBF<2>, KSF>(nb, g, st);
 }
 
+// g1 with A read as [k][row] (KSF) and g2 with A read as [row][k] (KC), six-product operands,
+// in one launch; either may be empty.  Both have nq = 1.
+template <class T>
+static hipError_t sgemm_pair_tt(int nb, const SgemmArgs& g1, const SgemmArgs& g2, hipStream_t st) {
+  typedef NumBF<3> Num;
+  constexpr int lds = T::template lds_bytes<Num>();
+  hipError_t e = allow_lds(k_sgemm_pair<T, Num, KSF, KC>, lds);
+  if (e != hipSuccess) return e;
+  const int tiles1 = ((g1.Mc + T::MT - 1) / T::MT) * ((g1.Nc + T::NT - 1) / T::NT);
+  const int tiles2 = ((g2.Mc + T::MT - 1) / T::MT) * ((g2.Nc + T::NT - 1) / T::NT);
+  hipLaunchKernelGGL((k_sgemm_pair<T, Num, KSF, KC>), dim3(tiles1 + tiles2, 1, nb), dim3(T::THREADS), lds, st, g1, g2, tiles1);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+static hipError_t sgemm_pair(int nb, const SgemmArgs& g1, const SgemmArgs& g2, hipStream_t st) {
+  const bool has1 = g1.Mc > 0 && g1.Nc > 0 && g1.Kc > 0, has2 = g2.Mc > 0 && g2.Nc > 0 && g2.Kc > 0;
+  if (!has1 && !has2) return hipSuccess;
+  if (!has2) return sgemm(nb, g1, false, 1, st);
+  if (!has1) return sgemm(nb, g2, true, 1, st);
+  const int big = (((g1.Mc + 127) / 128) * ((g1.Nc + 127) / 128) + ((g2.Mc + 127) / 128) * ((g2.Nc + 127) / 128)) * nb;
+  if (big < 512) return sgemm_pair_tt<TileSmall>(nb, g1, g2, st);
+  return sgemm_pair_tt<TileSquare>(nb, g1, g2, st);
+}
+
 hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp, int* info, int info_slot,
                           hipStream_t st) {
   hipError_t e = allow_lds(k_chol256, kCholLds);
@@ -1037,38 +1076,40 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp
     hipLaunchKernelGGL(k_zero_pair, dim3(blocks, nb), dim3(256), 0, st, t, w, count);
     OD_CHECK_LAUNCH();
   }
-  const int exact = 1;
+  // Step p: factor the diagonal block (T_pp, W_pp), then two launches of two independent
+  // products each:
+  //   (1) the panel of the factor      T(p, rest) = W_pp^T G(p, rest)
+  //       and, for the inverse,        tmp(0:p, p) = T(0:p, p) W_pp
+  //   (2) the trailing update          G(rest, rest) -= T(p, rest)^T T(p, rest)
+  //       and block column p of W      W(0:p, p) = -W(0:p, 0:p) tmp(0:p, p)
+  // (the inverse of [[A, b], [0, c]] is [[A^-1, -A^-1 b c^-1], [0, c^-1]]).
   for (int p = 0; p < nblk; ++p) {
     ca.blk = p;
     hipLaunchKernelGGL(k_chol256, dim3(nb), dim3(kCholThreads), kCholLds, st, ca);
     OD_CHECK_LAUNCH();
-    if (p + 1 == nblk) break;
-    const int o = p * kLeaf, o1 = (p + 1) * kLeaf, rest = r - o1;
-    SgemmArgs g = {};
-    g.r = r; g.nq = 1; g.q_step = 0;
-    // T(p, rest) = W_pp^T G(p, rest)
-    g.a = w; g.b = gram; g.c = t;
-    g.a_r0 = o; g.a_k0 = o; g.b_k0 = o; g.b_c0 = o1; g.c_r0 = o; g.c_c0 = o1;
-    g.Mc = kLeaf; g.Nc = rest; g.Kc = kLeaf; g.alpha = 1.f; g.beta = 0.f;
-    if ((e = sgemm(nb, g, false, exact, st)) != hipSuccess) return e;
-    // G(rest, rest) -= T(p, rest)^T T(p, rest)
-    g.a = t; g.b = t; g.c = gram;
-    g.a_r0 = o1; g.a_k0 = o; g.b_k0 = o; g.b_c0 = o1; g.c_r0 = o1; g.c_c0 = o1;
-    g.Mc = rest; g.Nc = rest; g.Kc = kLeaf; g.alpha = -1.f; g.beta = 1.f;
-    if ((e = sgemm(nb, g, false, exact, st)) != hipSuccess) return e;
-  }
-  // W(I, I+d) = -W_II * sum_{K=I+1..I+d} T(I, K) W(K, I+d), block diagonal by block diagonal
-  for (int d = 1; d < nblk; ++d) {
-    SgemmArgs g = {};
-    g.r = r; g.nq = nblk - d; g.q_step = kLeaf;
-    g.a = t; g.b = w; g.c = tmp;
-    g.a_r0 = 0; g.a_k0 = kLeaf; g.b_k0 = kLeaf; g.b_c0 = d * kLeaf; g.c_r0 = 0; g.c_c0 = d * kLeaf;
-    g.Mc = kLeaf; g.Nc = kLeaf; g.Kc = d * kLeaf; g.alpha = 1.f; g.beta = 0.f;
-    if ((e = sgemm(nb, g, true, exact, st)) != hipSuccess) return e;
-    g.a = w; g.b = tmp; g.c = w;
-    g.a_r0 = 0; g.a_k0 = 0; g.b_k0 = 0; g.b_c0 = d * kLeaf; g.c_r0 = 0; g.c_c0 = d * kLeaf;
-    g.Mc = kLeaf; g.Nc = kLeaf; g.Kc = kLeaf; g.alpha = -1.f; g.beta = 0.f;
-    if ((e = sgemm(nb, g, true, exact, st)) != hipSuccess) return e;
+    const int o = p * kLeaf, o1 = (p + 1) * kLeaf, rest = r > o1 ? r - o1 : 0;
+    const int bw = r - o < kLeaf ? r - o : kLeaf;       // width of block column p
+    SgemmArgs panel = {}, prod = {}, trail = {}, wcol = {};
+    panel.r = prod.r = trail.r = wcol.r = r;
+    panel.nq = prod.nq = trail.nq = wcol.nq = 1;
+    if (rest > 0) {
+      panel.a = w; panel.b = gram; panel.c = t;
+      panel.a_r0 = o; panel.a_k0 = o; panel.b_k0 = o; panel.b_c0 = o1; panel.c_r0 = o; panel.c_c0 = o1;
+      panel.Mc = kLeaf; panel.Nc = rest; panel.Kc = kLeaf; panel.alpha = 1.f; panel.beta = 0.f;
+      trail.a = t; trail.b = t; trail.c = gram;
+      trail.a_r0 = o1; trail.a_k0 = o; trail.b_k0 = o; trail.b_c0 = o1; trail.c_r0 = o1; trail.c_c0 = o1;
+      trail.Mc = rest; trail.Nc = rest; trail.Kc = kLeaf; trail.alpha = -1.f; trail.beta = 1.f;
+    }
+    if (p > 0) {
+      prod.a = t; prod.b = w; prod.c = tmp;
+      prod.a_r0 = 0; prod.a_k0 = o; prod.b_k0 = o; prod.b_c0 = o; prod.c_r0 = 0; prod.c_c0 = o;
+      prod.Mc = o; prod.Nc = bw; prod.Kc = bw; prod.alpha = 1.f; prod.beta = 0.f;
+      wcol.a = w; wcol.b = tmp; wcol.c = w;
+      wcol.a_r0 = 0; wcol.a_k0 = 0; wcol.b_k0 = 0; wcol.b_c0 = o; wcol.c_r0 = 0; wcol.c_c0 = o;
+      wcol.Mc = o; wcol.Nc = bw; wcol.Kc = o; wcol.alpha = -1.f; wcol.beta = 0.f;
+    }
+    if ((e = sgemm_pair(nb, panel, prod, st)) != hipSuccess) return e;
+    if ((e = sgemm_pair(nb, trail, wcol, st)) != hipSuccess) return e;
   }
   return hipSuccess;
 }
