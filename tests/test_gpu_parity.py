@@ -64,7 +64,7 @@ def test_config1_fp32_256_rank16_five_steps():
 
 
 @pytest.mark.parametrize("m,n,r", [(512, 384, 64), (200, 328, 24), (384, 640, 136), (1024, 768, 256),
-                                   (64, 32, 32), (40, 1032, 8), (776, 264, 264)])
+                                   (64, 32, 32), (40, 1032, 8), (776, 264, 264), (800, 784, 776)])
 @pytest.mark.parametrize("variant", ["qr", "colnorm"])
 def test_bf16_small_shapes_both_variants(m, n, r, variant):
     w = synth.Workload(f"t{m}x{n}r{r}", ((m, n),), r=r, x_dtype="bf16", steps=3)
