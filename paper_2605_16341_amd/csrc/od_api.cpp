@@ -405,9 +405,11 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     if (fast) OD_TRY(od::launch_stats(d, v.ptrs, v.scal, v.info, v.qht, st));
     OD_PHASE_END(ORTHDION_PHASE_STATS);
     OD_PHASE_KERNEL(ORTHDION_PHASE_PROJ);
-    OD_TRY(od::launch_proj(d, v.ptrs, prec, v.scal, v.part, b.splits_proj, v.qht, st));
+    // a single split is the result itself: written straight to its place, nothing to add up
+    const bool proj_direct = b.splits_proj == 1;
+    OD_TRY(od::launch_proj(d, v.ptrs, prec, v.scal, proj_direct ? v.pa : v.part, b.splits_proj, v.qht, st));
     OD_PHASE_BEGIN(ORTHDION_PHASE_PROJ_REDUCE);
-    OD_TRY(od::launch_reduce(d.nb, v.part, b.splits_proj, (int64_t)d.m * d.r, v.pa, st));
+    if (!proj_direct) OD_TRY(od::launch_reduce(d.nb, v.part, b.splits_proj, (int64_t)d.m * d.r, v.pa, st));
     OD_PHASE_END(ORTHDION_PHASE_PROJ_REDUCE);
     OD_PHASE_BEGIN(ORTHDION_PHASE_GRAM_LEFT);
     int rc = orth_gram(b, ws, d.m, b.off_pa, b.st_p, b.splits_gram_p, st);
