@@ -64,7 +64,8 @@ hipError_t launch_back(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const
                        WsArr p, WsArr part, int splits, HalfArr pht, hipStream_t st);
 // out[i] = sum_s part[s * count + i], i < count, per matrix
 hipError_t launch_reduce(int nb, WsArr part, int splits, int64_t count, WsArr out, hipStream_t st);
-// the same for R (n x r), also written as pre-scaled fp16 [n][r]
+// the same for R (n x r), also written as pre-scaled fp16 [n][r]; with one split `part` may be
+// `out` itself (the back-projection wrote R in place): then only the fp16 copy is written
 hipError_t launch_reduce_r(const ClassDims& d, WsArr part, int splits, WsArr out, HalfArr rh, const float* scal, hipStream_t st);
 
 // Gram partials: part[split][r][r] = A[k-range, :]^T A[k-range, :], A is rows x r (ld r)

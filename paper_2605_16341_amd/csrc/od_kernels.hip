@@ -254,7 +254,7 @@ __global__ __launch_bounds__(256) void k_reduce_r(ClassDims d, WsArr part, int s
     f32x4 s = reinterpret_cast<const f32x4*>(src)[i];
 #pragma unroll 8
     for (int k = 1; k < splits; ++k) s += reinterpret_cast<const f32x4*>(src + (int64_t)k * count)[i];
-    reinterpret_cast<f32x4*>(dst)[i] = s;
+    if (dst != src) reinterpret_cast<f32x4*>(dst)[i] = s;     // in place (one split): only the fp16 copy is new
     u32x2 h = {pack_f16_sat(s[0] * sr, s[1] * sr), pack_f16_sat(s[2] * sr, s[3] * sr)};
     reinterpret_cast<u32x2*>(dh)[i] = h;
   }
