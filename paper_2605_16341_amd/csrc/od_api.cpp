@@ -293,9 +293,11 @@ static int orth_finish(const Batch& b, char* ws, int rows, size_t off_a0, size_t
   OD_TRY(od::launch_gram(nb, rows, r, a1, part, splits, exact, st));
   // fast precision: the second pass as a correction a1 - a1 Phi(E) (one fp16 product; a1 itself
   // stays in fp32); exact precision: the product a1 (I - Phi(E)) on six-product operands
-  OD_TRY(od::launch_corr(nb, r, part, splits, t2, w, exact ? 0 : 1, scal, 2 + info_slot, info, info_slot, st));
+  // (Phi^T as fp16 operand words lives in the r x r scratch the factorisation no longer needs)
+  const HalfArr phit{exact ? nullptr : reinterpret_cast<uint16_t*>(ws + b.off_tmp), 2 * b.st_rr};
+  OD_TRY(od::launch_corr(nb, r, part, splits, t2, w, phit, scal, 2 + info_slot, info, info_slot, st));
   if (exact) OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, hn, ht, exact, st));
-  else OD_TRY(od::launch_apply_correction(nb, rows, r, a1, w, a0, q_out, hn, ht, st));
+  else OD_TRY(od::launch_apply_correction(nb, rows, r, a1, phit, a0, q_out, hn, ht, st));
   return ORTHDION_OK;
 }
 

@@ -77,8 +77,9 @@ hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits,
 hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs, HalfArr hn,
                         HalfArr ht, int exact, hipStream_t st);
 // out = A - A * Phi with Phi upper triangular and small (the first-order second pass of
-// CholeskyQR2): A enters in fp32, the correction is a single fp16 product.  Outputs as above.
-hipError_t launch_apply_correction(int nb, int rows, int r, WsArr a, WsArr phi, WsArr out, const MatPtrs* q_ptrs,
+// CholeskyQR2): A enters in fp32, the correction is a single fp16 product.  `phit` is Phi^T as
+// fp16 scaled by 2^13, [r][r] per matrix (written by launch_corr).  Outputs as above.
+hipError_t launch_apply_correction(int nb, int rows, int r, WsArr a, HalfArr phit, WsArr out, const MatPtrs* q_ptrs,
                                    HalfArr hn, HalfArr ht, hipStream_t st);
 
 // Cholesky factor and its inverse of the SPD r x r matrices `gram` (ld r): gram = T^T T,
@@ -92,10 +93,11 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp
                           hipStream_t st);
 
 // First-order second pass: from the Gram partials of a nearly orthonormal matrix writes
-// T2 = I + Phi(E), W2 = I - Phi(E) (or Phi(E) itself with phi_only) and max |E| into
-// scal[mat][scal_slot] (must be zeroed); a deviation above 0.1 (or NaN) is a breakdown:
-// info[mat][info_slot] = r unless already set.
-hipError_t launch_corr(int nb, int r, WsArr part, int splits, WsArr t2, WsArr w2, int phi_only, float* scal,
+// T2 = I + Phi(E), and either W2 = I - Phi(E) (fp32) or, with phit.base non-null, Phi(E)^T as
+// fp16 scaled by 2^13 ([r][r], stride phit.stride) instead; max |E| into scal[mat][scal_slot]
+// (must be zeroed); a deviation above 0.1 (or NaN) is a breakdown: info[mat][info_slot] = r
+// unless already set.
+hipError_t launch_corr(int nb, int r, WsArr part, int splits, WsArr t2, WsArr w2, HalfArr phit, float* scal,
                        int scal_slot, int* info, int info_slot, hipStream_t st);
 
 // scal[mat][1] = power-of-two scale for R from trace(gram) = ||R||_F^2 (rows n, cols r)

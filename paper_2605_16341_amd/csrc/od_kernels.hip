@@ -319,8 +319,8 @@ __global__ __launch_bounds__(T::THREADS) void k_gram(int rows, int r, WsArr a, W
 // ------------------------------------------------------------------------------------
 constexpr float kPhiScale = 8192.f;
 template <class T, class Num, bool DEEP, bool CORR>
-__global__ __launch_bounds__(T::THREADS) void k_apply(int rows, int r, WsArr a, WsArr w, WsArr out, MatPtrs ptrs, int to_q,
-                                                      HalfArr hn, HalfArr ht) {
+__global__ __launch_bounds__(T::THREADS) void k_apply(int rows, int r, WsArr a, WsArr w, HalfArr wh, WsArr out, MatPtrs ptrs,
+                                                      int to_q, HalfArr hn, HalfArr ht) {
   extern __shared__ __align__(16) char lds[];
   const int tiles_n = (r + T::NT - 1) / T::NT;
   // the column tiles of one row panel of A share an XCD's L2
@@ -333,9 +333,16 @@ __global__ __launch_bounds__(T::THREADS) void k_apply(int rows, int r, WsArr a, 
   if (kend > r) kend = r;
   f32x16 acc[T::FM][T::FN];
   zero_acc<T>(acc);
-  const float s_a = CORR ? kUnitScale : 1.f, s_w = CORR ? kPhiScale : 1.f;
-  if constexpr (DEEP) gemm_mainloop_deep<T, Num, KC, SrcF32, KS, SrcF32, 3>(sa, sw, tm * T::MT, tn * T::NT, 0, kend, s_a, s_w, lds, acc);
-  else gemm_mainloop<T, Num, KC, SrcF32, KS, SrcF32>(sa, sw, tm * T::MT, tn * T::NT, 0, kend, s_a, s_w, lds, acc);
+  if constexpr (CORR) {
+    // Phi arrives as ready operand words (fp16, scaled, transposed to [column][k]): its tiles go
+    // to LDS as they are, without the transposition and conversion a fp32 source needs
+    SrcH16 swh{wh.base + (int64_t)z * wh.stride, r, r, r};
+    if constexpr (DEEP) gemm_mainloop_deep<T, Num, KC, SrcF32, KC, SrcH16, 3>(sa, swh, tm * T::MT, tn * T::NT, 0, kend, kUnitScale, 1.f, lds, acc);
+    else gemm_mainloop<T, Num, KC, SrcF32, KC, SrcH16>(sa, swh, tm * T::MT, tn * T::NT, 0, kend, kUnitScale, 1.f, lds, acc);
+  } else {
+    if constexpr (DEEP) gemm_mainloop_deep<T, Num, KC, SrcF32, KS, SrcF32, 3>(sa, sw, tm * T::MT, tn * T::NT, 0, kend, 1.f, 1.f, lds, acc);
+    else gemm_mainloop<T, Num, KC, SrcF32, KS, SrcF32>(sa, sw, tm * T::MT, tn * T::NT, 0, kend, 1.f, 1.f, lds, acc);
+  }
   if constexpr (CORR) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int wm = wave / T::WN, wn = wave % T::WN;
@@ -466,7 +473,7 @@ constexpr float kMaxGramDeviation = 0.1f;   // largest |E| entry the first-order
 // triangle + half the diagonal, and the inverse factor I - Phi(E) + O(E^2).  Writes
 // T2 = I + Phi(E), W2 = I - Phi(E) and the largest |E| entry (scal[mat][scal_slot]).
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_corr(int r, WsArr part, int splits, WsArr t2, WsArr w2, int phi_only, float* scal,
+__global__ __launch_bounds__(256) void k_corr(int r, WsArr part, int splits, WsArr t2, WsArr w2, HalfArr phit, float* scal,
                                               int scal_slot, int* info, int info_slot) {
   const int z = blockIdx.y;
   const float* src = part.base + (int64_t)z * part.stride;
@@ -481,7 +488,7 @@ __global__ __launch_bounds__(256) void k_corr(int r, WsArr part, int splits, WsA
     f32x4 g = reinterpret_cast<const f32x4*>(src)[i4];
 #pragma unroll 8
     for (int sp = 1; sp < splits; ++sp) g += reinterpret_cast<const f32x4*>(src + (int64_t)sp * count)[i4];
-    f32x4 to, wo;
+    f32x4 to, wo, pt;
 #pragma unroll
     for (int c = 0; c < 4; ++c) {
       const int j = j0 + c;
@@ -492,10 +499,21 @@ __global__ __launch_bounds__(256) void k_corr(int r, WsArr part, int splits, WsA
       else if (j == i) phi = 0.5f * e;
       const float id = (i == j) ? 1.f : 0.f;
       to[c] = id + phi;
-      wo[c] = phi_only ? phi : id - phi;
+      wo[c] = id - phi;
+      // E is symmetric, so row i of Phi^T (the operand layout [column][k]) is made of the same
+      // entries of row i of E, taken below the diagonal instead of above
+      float lower = 0.f;
+      if (j < i) lower = e;
+      else if (j == i) lower = 0.5f * e;
+      pt[c] = lower * kPhiScale;
     }
     reinterpret_cast<f32x4*>(tp)[i4] = to;
-    reinterpret_cast<f32x4*>(wp)[i4] = wo;
+    if (phit.base == nullptr) {
+      reinterpret_cast<f32x4*>(wp)[i4] = wo;
+    } else {
+      const u32x2 h = {pack_f16_sat(pt[0], pt[1]), pack_f16_sat(pt[2], pt[3])};
+      reinterpret_cast<u32x2*>(phit.base + (int64_t)z * phit.stride)[i4] = h;
+    }
   }
   __shared__ float red[256];
   red[threadIdx.x] = emax;
@@ -980,32 +998,34 @@ hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits,
 }
 
 template <class T, class Num, bool DEEP, bool CORR>
-static hipError_t apply_tt(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
+static hipError_t apply_tt(int nb, int rows, int r, WsArr a, WsArr w, HalfArr wh, WsArr out, const MatPtrs* ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
   constexpr int lds = T::template lds_bytes<Num>();
   hipError_t e = allow_lds(k_apply<T, Num, DEEP, CORR>, lds);
   if (e != hipSuccess) return e;
   MatPtrs none = {};
   dim3 grid(((rows + T::MT - 1) / T::MT) * ((r + T::NT - 1) / T::NT), 1, nb);
-  hipLaunchKernelGGL((k_apply<T, Num, DEEP, CORR>), grid, dim3(T::THREADS), lds, st, rows, r, a, w, out, ptrs ? *ptrs : none, ptrs ? 1 : 0, hn, ht);
+  hipLaunchKernelGGL((k_apply<T, Num, DEEP, CORR>), grid, dim3(T::THREADS), lds, st, rows, r, a, w, wh, out, ptrs ? *ptrs : none, ptrs ? 1 : 0, hn, ht);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
 template <class Num, bool CORR>
-static hipError_t apply_t(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
+static hipError_t apply_t(int nb, int rows, int r, WsArr a, WsArr w, HalfArr wh, WsArr out, const MatPtrs* ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
   const int big = ((rows + 127) / 128) * ((r + 127) / 128) * nb;
-  if (big < 512) return apply_tt<TileSmall, Num, true, CORR>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
+  if (big < 512) return apply_tt<TileSmall, Num, true, CORR>(nb, rows, r, a, w, wh, out, ptrs, hn, ht, st);
   // 128 columns per tile: the loop of a column tile ends at its last row of W (upper triangular),
   // so narrower tiles skip more of the zero half than 256-column ones would (measured -10 %)
   // one operand part leaves LDS room for 64-deep steps at two workgroups per CU (measured -13 to
   // -23 %); with two parts the deeper tile halves the occupancy and loses
-  if constexpr (Num::PARTS == 1) return apply_tt<TileSquareDeepK, Num, false, CORR>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
-  else return apply_tt<TileSquare, Num, false, CORR>(nb, rows, r, a, w, out, ptrs, hn, ht, st);
+  if constexpr (Num::PARTS == 1) return apply_tt<TileSquareDeepK, Num, false, CORR>(nb, rows, r, a, w, wh, out, ptrs, hn, ht, st);
+  else return apply_tt<TileSquare, Num, false, CORR>(nb, rows, r, a, w, wh, out, ptrs, hn, ht, st);
 }
 hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs, HalfArr hn, HalfArr ht, int exact, hipStream_t st) {
-  return exact ? apply_t<NumBF<3>, false>(nb, rows, r, a, w, out, q_ptrs, hn, ht, st) : apply_t<NumBF<2>, false>(nb, rows, r, a, w, out, q_ptrs, hn, ht, st);
+  const HalfArr none{nullptr, 0};
+  return exact ? apply_t<NumBF<3>, false>(nb, rows, r, a, w, none, out, q_ptrs, hn, ht, st) : apply_t<NumBF<2>, false>(nb, rows, r, a, w, none, out, q_ptrs, hn, ht, st);
 }
-hipError_t launch_apply_correction(int nb, int rows, int r, WsArr a, WsArr phi, WsArr out, const MatPtrs* q_ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
-  return apply_t<NumF16, true>(nb, rows, r, a, phi, out, q_ptrs, hn, ht, st);
+hipError_t launch_apply_correction(int nb, int rows, int r, WsArr a, HalfArr phit, WsArr out, const MatPtrs* q_ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
+  const WsArr unused{nullptr, 0};
+  return apply_t<NumF16, true>(nb, rows, r, a, unused, phit, out, q_ptrs, hn, ht, st);
 }
 
 template <class T, class Num, class DirA>
@@ -1114,12 +1134,12 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp
   return hipSuccess;
 }
 
-hipError_t launch_corr(int nb, int r, WsArr part, int splits, WsArr t2, WsArr w2, int phi_only, float* scal, int scal_slot,
+hipError_t launch_corr(int nb, int r, WsArr part, int splits, WsArr t2, WsArr w2, HalfArr phit, float* scal, int scal_slot,
                        int* info, int info_slot, hipStream_t st) {
   int64_t count = (int64_t)r * r;
   int blocks = (int)((count / 4 + 255) / 256);
   if (blocks > 1024) blocks = 1024;
-  hipLaunchKernelGGL(k_corr, dim3(blocks, nb), dim3(256), 0, st, r, part, splits, t2, w2, phi_only, scal, scal_slot, info, info_slot);
+  hipLaunchKernelGGL(k_corr, dim3(blocks, nb), dim3(256), 0, st, r, part, splits, t2, w2, phit, scal, scal_slot, info, info_slot);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
