@@ -717,7 +717,20 @@ __global__ __launch_bounds__(T::THREADS) void k_efx(ClassDims d, MatPtrs ptrs, c
 // ------------------------------------------------------------------------------------
 // (second bound: four waves per SIMD, i.e. at most 128 registers, so that two of these 8-wave
 // workgroups share a CU as the last point above needs)
-template <bool XBF, bool GBF>
+// streamed once and not needed again before they are evicted anyway: keep them from pushing the
+// factor panels out of L2 (used for long K loops, where the panels are re-read by many tiles)
+template <bool STREAM, class V>
+OD_DEV V ld_stream(const V* p) {
+  if constexpr (STREAM) return __builtin_nontemporal_load(p);
+  else return *p;
+}
+template <bool STREAM, class V>
+OD_DEV void st_stream(V* p, V v) {
+  if constexpr (STREAM) __builtin_nontemporal_store(v, p);
+  else *p = v;
+}
+
+template <bool XBF, bool GBF, bool STREAM>
 __global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, const float* scal, HalfArr ph, HalfArr rh,
                                                HalfArr qh, float a_coef, float b_coef, float lr) {
   constexpr int TJ = 128, TI = 128, KT = 32, PITCH = KT * 2 + 16, PLANE = 128 * PITCH, BUF = 3 * PLANE;
@@ -812,11 +825,11 @@ __global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, con
       mv[u] = f32x2{0.f, 0.f};
       gp[u] = 0u; xp[u] = 0u; gv[u] = f32x2{0.f, 0.f}; xv[u] = f32x2{0.f, 0.f};
       if (i < d.m && j0 < d.n) {
-        mv[u] = *reinterpret_cast<const f32x2*>(Mz + (int64_t)i * d.ldm + j0);
-        if constexpr (GBF) gp[u] = *reinterpret_cast<const uint32_t*>(Gz + ((int64_t)i * d.ldg + j0) * GE);
-        else gv[u] = *reinterpret_cast<const f32x2*>(Gz + ((int64_t)i * d.ldg + j0) * GE);
-        if constexpr (XBF) xp[u] = *reinterpret_cast<const uint32_t*>(Xz + ((int64_t)i * d.ldx + j0) * XE);
-        else xv[u] = *reinterpret_cast<const f32x2*>(Xz + ((int64_t)i * d.ldx + j0) * XE);
+        mv[u] = ld_stream<STREAM>(reinterpret_cast<const f32x2*>(Mz + (int64_t)i * d.ldm + j0));
+        if constexpr (GBF) gp[u] = ld_stream<STREAM>(reinterpret_cast<const uint32_t*>(Gz + ((int64_t)i * d.ldg + j0) * GE));
+        else gv[u] = ld_stream<STREAM>(reinterpret_cast<const f32x2*>(Gz + ((int64_t)i * d.ldg + j0) * GE));
+        if constexpr (XBF) xp[u] = ld_stream<STREAM>(reinterpret_cast<const uint32_t*>(Xz + ((int64_t)i * d.ldx + j0) * XE));
+        else xv[u] = ld_stream<STREAM>(reinterpret_cast<const f32x2*>(Xz + ((int64_t)i * d.ldx + j0) * XE));
       }
     }
 #pragma unroll
@@ -833,9 +846,9 @@ __global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, con
           mo[e] = a_coef * (mv[u][e] + g[e]) - cr * acc_r[e][v];
           xo[e] = x[e] - cq * acc_q[e][v];
         }
-        *reinterpret_cast<f32x2*>(Mz + (int64_t)i * d.ldm + j0) = mo;
-        if constexpr (XBF) *reinterpret_cast<uint32_t*>(Xz + ((int64_t)i * d.ldx + j0) * XE) = pack_bf16_rne(xo[0], xo[1]);
-        else *reinterpret_cast<f32x2*>(Xz + ((int64_t)i * d.ldx + j0) * XE) = xo;
+        st_stream<STREAM>(reinterpret_cast<f32x2*>(Mz + (int64_t)i * d.ldm + j0), mo);
+        if constexpr (XBF) st_stream<STREAM>(reinterpret_cast<uint32_t*>(Xz + ((int64_t)i * d.ldx + j0) * XE), pack_bf16_rne(xo[0], xo[1]));
+        else st_stream<STREAM>(reinterpret_cast<f32x2*>(Xz + ((int64_t)i * d.ldx + j0) * XE), xo);
       }
     }
   }
@@ -1189,7 +1202,8 @@ static hipError_t efx_h_t(const ClassDims& d, const MatPtrs& ptrs, const float* 
                           float a_coef, float b_coef, float lr, hipStream_t st) {
   constexpr int lds = 2 * 3 * 128 * 80;
   dim3 grid(((d.m + 127) / 128) * ((d.n + 127) / 128), 1, d.nb);
-  launch_timed(k_efx_h<XBF, GBF>, grid, dim3(512), lds, st, d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr);
+  if (d.r > 256) launch_timed(k_efx_h<XBF, GBF, true>, grid, dim3(512), lds, st, d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr);
+  else launch_timed(k_efx_h<XBF, GBF, false>, grid, dim3(512), lds, st, d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
