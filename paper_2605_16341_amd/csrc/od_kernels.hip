@@ -1202,7 +1202,9 @@ static hipError_t efx_h_t(const ClassDims& d, const MatPtrs& ptrs, const float* 
                           float a_coef, float b_coef, float lr, hipStream_t st) {
   constexpr int lds = 2 * 3 * 128 * 80;
   dim3 grid(((d.m + 127) / 128) * ((d.n + 127) / 128), 1, d.nb);
-  if (d.r > 256) launch_timed(k_efx_h<XBF, GBF, true>, grid, dim3(512), lds, st, d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr);
+  // also for sets far beyond the Infinity Cache at any rank: nontemporal stores leave no dirty
+  // lines behind for the next kernel to wait on (measured on 8192 x 8192: the step is 2-7 % faster)
+  if (d.r > 256 || (int64_t)d.m * d.n * d.nb >= ((int64_t)48 << 20)) launch_timed(k_efx_h<XBF, GBF, true>, grid, dim3(512), lds, st, d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr);
   else launch_timed(k_efx_h<XBF, GBF, false>, grid, dim3(512), lds, st, d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr);
   OD_CHECK_LAUNCH();
   return hipSuccess;
