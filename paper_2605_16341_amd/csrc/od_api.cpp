@@ -273,6 +273,11 @@ static int orth_gram(const Batch& b, char* ws, int rows, size_t off_a0, int64_t 
   WsArr a0{reinterpret_cast<float*>(ws + off_a0), st_a};
   WsArr part{reinterpret_cast<float*>(ws + b.off_part), b.st_part};
   WsArr gram{reinterpret_cast<float*>(ws + b.off_gram), b.st_rr};
+  // a single split is the Gram matrix itself: written straight into the class array
+  if (splits == 1) {
+    OD_TRY(od::launch_gram(b.d.nb, rows, b.d.r, a0, gram, 1, 1, st));
+    return ORTHDION_OK;
+  }
   OD_TRY(od::launch_gram(b.d.nb, rows, b.d.r, a0, part, splits, 1, st));
   // ordered reduction of the split partial sums on many workgroups: the factorisation runs on
   // one workgroup per matrix and should not spend its time summing
