@@ -27,9 +27,13 @@ MFMA_PEAK_TFLOPS = 2500.0      # MI355X dense fp16 / bf16 matrix cores, publishe
 # copy kernel of known size); see profiles/.  Keyed by (workload, phase); bytes per launch.
 MEASURED_TRAFFIC = {
     # profiles/orthdion_step_C2_hbm_counters.txt: 2.000 * FETCH_SIZE + 1.000 * WRITE_SIZE, bytes
-    ("C2", "efx"): 272360352,
-    ("C2", "back"): 186303728,
-    ("C2", "proj"): 155488096,
+    ("C2", "efx"): 272795008,
+    ("C2", "back"): 186232466,
+    ("C2", "proj"): 155187017,
+    # profiles/orthdion_step_C5-r16_hbm_counters.txt
+    ("C5-r16", "efx"): 944195895,
+    ("C5-r16", "back"): 409127991,
+    ("C5-r16", "proj"): 419819959,
 }
 
 
