@@ -285,17 +285,26 @@ static int orth_gram(const Batch& b, char* ws, int rows, size_t off_a0, int64_t 
   return ORTHDION_OK;
 }
 
+// Ranks of one 32 x 32 tile take the first pass in a single launch (factorisation included), so
+// the class-wide Cholesky step is skipped for them.
+static bool first_pass_in_one_launch(int r) { return r <= 32; }
+
 static int orth_finish(const Batch& b, char* ws, int rows, size_t off_a0, size_t off_a1, int64_t st_a, int splits,
-                       size_t off_t2, int info_slot, const MatPtrs* q_out, HalfArr hn, HalfArr ht, float* scal,
-                       int* info, int exact, hipStream_t st) {
+                       size_t off_t1, size_t off_t2, int info_slot, const MatPtrs* q_out, HalfArr hn, HalfArr ht,
+                       float* scal, int* info, int exact, hipStream_t st) {
   const int nb = b.d.nb, r = b.d.r;
   WsArr a0{reinterpret_cast<float*>(ws + off_a0), st_a}, a1{reinterpret_cast<float*>(ws + off_a1), st_a};
   WsArr part{reinterpret_cast<float*>(ws + b.off_part), b.st_part};
   WsArr w{reinterpret_cast<float*>(ws + b.off_w), b.st_rr};
   WsArr t2{reinterpret_cast<float*>(ws + off_t2), b.st_rr};
   const HalfArr none{nullptr, 0};
-  OD_TRY(od::launch_apply(nb, rows, r, a0, w, a1, nullptr, none, none, exact, st));
-  OD_TRY(od::launch_gram(nb, rows, r, a1, part, splits, exact, st));
+  if (first_pass_in_one_launch(r)) {
+    WsArr gram{reinterpret_cast<float*>(ws + b.off_gram), b.st_rr}, t1{reinterpret_cast<float*>(ws + off_t1), b.st_rr};
+    OD_TRY(od::launch_small_first_pass(nb, rows, r, a0, gram, t1, w, a1, part, splits, info, info_slot, st));
+  } else {
+    OD_TRY(od::launch_apply(nb, rows, r, a0, w, a1, nullptr, none, none, exact, st));
+    OD_TRY(od::launch_gram(nb, rows, r, a1, part, splits, exact, st));
+  }
   // fast precision: the second pass as a correction a1 - a1 Phi(E) (one fp16 product; a1 itself
   // stays in fp32); exact precision: the product a1 (I - Phi(E)) on six-product operands
   // (Phi^T as fp16 operand words lives in the r x r scratch the factorisation no longer needs)
@@ -309,6 +318,7 @@ static int orth_finish(const Batch& b, char* ws, int rows, size_t off_a0, size_t
 // Cholesky factor and inverse for every matrix of a rank class; `off_t1` names the class array
 // that receives the factors (left or right side).
 static int class_cholinv(const RankClass& c, char* ws, size_t off_t1, int info_slot, int* info_all, hipStream_t st) {
+  if (first_pass_in_one_launch(c.r)) return ORTHDION_OK;
   WsArr gram{reinterpret_cast<float*>(ws + c.off_gram), c.st_rr};
   WsArr w{reinterpret_cast<float*>(ws + c.off_w), c.st_rr}, tmp{reinterpret_cast<float*>(ws + c.off_tmp), c.st_rr};
   WsArr t1{reinterpret_cast<float*>(ws + off_t1), c.st_rr};
@@ -432,7 +442,7 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     BatchView v;
     view_of(b, v);
     OD_PHASE_BEGIN(ORTHDION_PHASE_ORTH_LEFT);
-    int rc = orth_finish(b, ws, d.m, b.off_pa, b.off_pb, b.st_p, b.splits_gram_p, b.off_tp2, 0, nullptr,
+    int rc = orth_finish(b, ws, d.m, b.off_pa, b.off_pb, b.st_p, b.splits_gram_p, b.off_tp1, b.off_tp2, 0, nullptr,
                          fast ? v.ph : none, fast ? v.pht : none, v.scal, v.info, exact, st);
     if (rc != ORTHDION_OK) return rc;
     OD_PHASE_END(ORTHDION_PHASE_ORTH_LEFT);
@@ -464,7 +474,7 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     view_of(b, v);
     OD_PHASE_BEGIN(ORTHDION_PHASE_ORTH_RIGHT);
     if (h->cfg.variant == ORTHDION_QR) {
-      int rc = orth_finish(b, ws, d.n, b.off_ra, b.off_rb, b.st_r, b.splits_gram_q, b.off_tq2, 1, &v.ptrs,
+      int rc = orth_finish(b, ws, d.n, b.off_ra, b.off_rb, b.st_r, b.splits_gram_q, b.off_tq1, b.off_tq2, 1, &v.ptrs,
                            fast ? v.qh : none, none, v.scal, v.info, exact, st);
       if (rc != ORTHDION_OK) return rc;
     } else {

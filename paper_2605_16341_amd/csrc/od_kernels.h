@@ -92,6 +92,12 @@ hipError_t launch_apply_correction(int nb, int rows, int r, WsArr a, HalfArr phi
 hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp, int* info, int info_slot,
                           hipStream_t st);
 
+// r <= 32: Cholesky factor and inverse of `gram`, A1 = A0 W1 and the Gram partials of A1
+// (`splits` of them, r x r each, in `part`) in one launch; T1 and W1 are written as by
+// launch_cholinv, a bad pivot is reported the same way.
+hipError_t launch_small_first_pass(int nb, int rows, int r, WsArr a0, WsArr gram, WsArr t1, WsArr w1, WsArr a1, WsArr part,
+                                   int splits, int* info, int info_slot, hipStream_t st);
+
 // First-order second pass: from the Gram partials of a nearly orthonormal matrix writes
 // T2 = I + Phi(E), and either W2 = I - Phi(E) (fp32) or, with phit.base non-null, Phi(E)^T as
 // fp16 scaled by 2^13 ([r][r], stride phit.stride) instead; max |E| into scal[mat][scal_slot]

@@ -396,6 +396,117 @@ __global__ __launch_bounds__(T::THREADS) void k_apply(int rows, int r, WsArr a, 
 }
 
 // ------------------------------------------------------------------------------------
+// r <= 32: the first CholeskyQR pass in one launch.  At this size every kernel of the pass is
+// a few microseconds of latency, so three of them become one: every workgroup factors the
+// (reduced) Gram matrix for itself in its first wave (one 32 x 32 tile, padded with the
+// identity), applies W = T^-1 to its share of the rows in plain fp32 and leaves the Gram
+// partial of the rows it has just produced for the second pass.  Workgroup 0 of a matrix also
+// writes T1 and W1.  One thread per row; `part` receives `splits` partial sums of r x r.
+// ------------------------------------------------------------------------------------
+constexpr int kSmallRows = 256, kSmallPitch = 36;
+__global__ __launch_bounds__(kSmallRows) void k_small_first_pass(int rows, int r, WsArr a0, WsArr gram, WsArr t1, WsArr w1,
+                                                                WsArr a1, WsArr part, int splits, int* info, int info_slot) {
+  __shared__ __align__(16) float Wl[32 * kSmallPitch];           // W[k][j]
+  __shared__ __align__(16) float S[kSmallRows * kSmallPitch];    // the rows of a1 of one pass
+  const int z = blockIdx.y, split = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  if (wave == 0) {
+    const float* G = gram.base + (int64_t)z * gram.stride;
+    const int c = lane & 31, h = lane >> 5;
+    // accumulator layout (lane = column c, registers = rows) read through the mirrored element
+    // of the symmetric matrix: four consecutive entries of row c
+    f32x16 d, zt;
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
+      const int gi = 8 * q + 4 * h;
+      f32x4 v4 = {0.f, 0.f, 0.f, 0.f};
+      if (c < r && gi < r) v4 = *reinterpret_cast<const f32x4*>(G + (int64_t)c * r + gi);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) d[4 * q + e] = (c < r && gi < r) ? v4[e] : ((gi + e == c) ? 1.f : 0.f);
+    }
+    const int bad = diag_tile_factor(d, zt, lane);
+    if (bad != 0 && lane == 0) atomicCAS(&info[z * kInfoPerMat + info_slot], 0, bad);
+    // zt = M with W = M^T: lane c holds row c of W
+#pragma unroll
+    for (int v = 0; v < 16; ++v) Wl[c * kSmallPitch + acc_row(v, lane)] = zt[v];
+    if (split == 0 && c < r) {
+      float* tp = t1.base + (int64_t)z * t1.stride;
+      float* wp = w1.base + (int64_t)z * w1.stride;
+#pragma unroll
+      for (int q = 0; q < 4; ++q) {
+        const int gi = 8 * q + 4 * h;
+        if (gi < r) {
+#pragma unroll
+          for (int e = 0; e < 4; ++e) tp[(int64_t)(gi + e) * r + c] = d[4 * q + e];
+          const f32x4 v4 = {zt[4 * q], zt[4 * q + 1], zt[4 * q + 2], zt[4 * q + 3]};
+          *reinterpret_cast<f32x4*>(wp + (int64_t)c * r + gi) = v4;
+        }
+      }
+    }
+  }
+  int kend;
+  const int kbeg = split_begin(rows, splits, 8, split, &kend);
+  const float* A = a0.base + (int64_t)z * a0.stride;
+  float* O = a1.base + (int64_t)z * a1.stride;
+  // Gram of the produced rows: every wave adds up its 64 rows of a pass on the matrix cores
+  // (fp32 32x32x2 products, both operands the same register: lane (c, h) feeds row 2i + h,
+  // column c); the four partial tiles are summed through LDS at the end.
+  f32x16 gacc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) gacc[v] = 0.f;
+  bool first = true;
+  for (int base = kbeg; base < kend; base += kSmallRows) {
+    const int row = base + tid;
+    const bool valid = row < kend;
+    float x[32];
+#pragma unroll
+    for (int j4 = 0; j4 < 8; ++j4) {
+      f32x4 v4 = {0.f, 0.f, 0.f, 0.f};
+      if (valid && 4 * j4 < r) v4 = *reinterpret_cast<const f32x4*>(A + (int64_t)row * r + 4 * j4);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) x[4 * j4 + e] = v4[e];
+    }
+    // the first rows are requested before the wait for the factorisation
+    if (first) { __syncthreads(); first = false; }
+    // o = x W, W upper triangular: column block jb takes k <= 4 jb + 3
+    f32x4 o[8];
+#pragma unroll
+    for (int jb = 0; jb < 8; ++jb) o[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int k = 0; k < 32; ++k)
+#pragma unroll
+      for (int jb = k / 4; jb < 8; ++jb) {
+        const f32x4 w4 = *reinterpret_cast<const f32x4*>(Wl + k * kSmallPitch + 4 * jb);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) o[jb][e] = fmaf(x[k], w4[e], o[jb][e]);
+      }
+#pragma unroll
+    for (int jb = 0; jb < 8; ++jb) {
+      if (valid && 4 * jb < r) *reinterpret_cast<f32x4*>(O + (int64_t)row * r + 4 * jb) = o[jb];
+      *reinterpret_cast<f32x4*>(S + tid * kSmallPitch + 4 * jb) = valid ? o[jb] : f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    __syncthreads();
+    const float* sw = S + (wave * 64 + (lane >> 5)) * kSmallPitch + (lane & 31);
+#pragma unroll 8
+    for (int i = 0; i < 32; ++i) {
+      const float a = sw[2 * i * kSmallPitch];
+      gacc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, a, gacc, 0, 0, 0);
+    }
+    __syncthreads();
+  }
+  if (first) __syncthreads();          // a workgroup without rows still meets the others' barrier count
+  // sum of the four waves' tiles: S doubles as [wave][32][pitch]
+#pragma unroll
+  for (int v = 0; v < 16; ++v) S[(wave * 32 + acc_row(v, lane)) * kSmallPitch + (lane & 31)] = gacc[v];
+  __syncthreads();
+  const int gi_ = tid >> 3, gj_ = 4 * (tid & 7);
+  f32x4 g2 = *reinterpret_cast<const f32x4*>(S + gi_ * kSmallPitch + gj_);
+#pragma unroll
+  for (int w = 1; w < 4; ++w) g2 += *reinterpret_cast<const f32x4*>(S + (w * 32 + gi_) * kSmallPitch + gj_);
+  if (gi_ < r && gj_ < r)
+    *reinterpret_cast<f32x4*>(part.base + (int64_t)z * part.stride + (int64_t)split * r * r + (int64_t)gi_ * r + gj_) = g2;
+}
+
+// ------------------------------------------------------------------------------------
 // small general product on r x r workspace matrices, used by the blocked Cholesky and
 // triangular inverse:  C[cr.., cc..] = alpha * A * B + beta * C over Mc x Nc x Kc with
 // block origins that advance affinely with the inner batch index q.
@@ -1144,6 +1255,15 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp
     if ((e = sgemm_pair(nb, panel, prod, st)) != hipSuccess) return e;
     if ((e = sgemm_pair(nb, trail, wcol, st)) != hipSuccess) return e;
   }
+  return hipSuccess;
+}
+
+hipError_t launch_small_first_pass(int nb, int rows, int r, WsArr a0, WsArr gram, WsArr t1, WsArr w1, WsArr a1, WsArr part,
+                                   int splits, int* info, int info_slot, hipStream_t st) {
+  if (r > 32) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_small_first_pass, dim3(splits, nb), dim3(kSmallRows), 0, st, rows, r, a0, gram, t1, w1, a1, part, splits,
+                     info, info_slot);
+  OD_CHECK_LAUNCH();
   return hipSuccess;
 }
 
