@@ -144,7 +144,9 @@ int orthdion_workspace_layout(orthdion_handle h, int32_t index, size_t* off_p, s
  *                           elapsed milliseconds and the number of intervals summed (steps x
  *                           shape-class batches) into two arrays of ORTHDION_NPHASE entries.
  * The two CHOL phases do not depend on m and n and run once for all matrices of one rank r,
- * whatever their shape class: they contribute one interval per step and distinct rank. */
+ * whatever their shape class: they contribute one interval per step and distinct rank.  For
+ * r <= 32 the factorisation is part of the first kernel of the ORTH phase that follows (one
+ * launch does it together with the triangular product), and the CHOL interval is empty. */
 typedef enum {
   ORTHDION_PHASE_STATS = 0,        /* sampled scale of B for the fp16 operand format      */
   ORTHDION_PHASE_PROJ = 1,         /* kernel: P_raw partials = (M + G) Q      (line 2)    */
