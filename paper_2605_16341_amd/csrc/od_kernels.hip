@@ -1043,7 +1043,12 @@ bool proj_uses_flat_tiles(int m, int r, int nb) {
 }
 template <class GSrc>
 static hipError_t proj_g(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr part, int splits, HalfArr qht, hipStream_t st) {
-  if (prec == PREC_BF3) return proj_t<TileSquare, NumBF<3>, GSrc>(d, ptrs, scal, part, splits, qht, st);
+  if (prec == PREC_BF3) {
+    // small problems: 64-deep steps halve the number of round trips of a loop that is all latency
+    if ((int64_t)((d.m + 127) / 128) * ((d.r + 127) / 128) * splits * d.nb < 256)
+      return proj_t<TileSmall, NumBF<3>, GSrc>(d, ptrs, scal, part, splits, qht, st);
+    return proj_t<TileSquare, NumBF<3>, GSrc>(d, ptrs, scal, part, splits, qht, st);
+  }
   if (d.r <= 64) return proj_t<TileNarrow, NumF16, GSrc>(d, ptrs, scal, part, splits, qht, st);
   if (d.r <= 128) return proj_t<TileSquare, NumF16, GSrc>(d, ptrs, scal, part, splits, qht, st);
   if (proj_uses_flat_tiles(d.m, d.r, d.nb)) {
@@ -1069,7 +1074,11 @@ static hipError_t back_t(const ClassDims& d, const MatPtrs& ptrs, const float* s
 }
 template <class GSrc>
 static hipError_t back_g(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p, WsArr part, int splits, HalfArr pht, hipStream_t st) {
-  if (prec == PREC_BF3) return back_t<TileSquare, NumBF<3>, GSrc>(d, ptrs, scal, p, part, splits, pht, st);
+  if (prec == PREC_BF3) {
+    if ((int64_t)((d.n + 127) / 128) * ((d.r + 127) / 128) * splits * d.nb < 256)
+      return back_t<TileSmall, NumBF<3>, GSrc>(d, ptrs, scal, p, part, splits, pht, st);
+    return back_t<TileSquare, NumBF<3>, GSrc>(d, ptrs, scal, p, part, splits, pht, st);
+  }
   if (d.r <= 64) return back_t<TileNarrow, NumF16, GSrc>(d, ptrs, scal, p, part, splits, pht, st);
   if (d.r <= 128) return back_t<TileSquare, NumF16, GSrc>(d, ptrs, scal, p, part, splits, pht, st);
   // several column tiles per row panel: 256 x 256 tiles halve the operand traffic per product
@@ -1297,10 +1306,9 @@ hipError_t launch_colnorm(int nb, int n, int r, WsArr rr, const MatPtrs& ptrs, W
   return hipSuccess;
 }
 
-template <class Num, bool XBF, bool GBF>
-static hipError_t efx_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr p, WsArr rr, float a_coef,
-                        float b_coef, float lr, hipStream_t st) {
-  typedef TileSquare T;
+template <class T, class Num, bool XBF, bool GBF>
+static hipError_t efx_tt(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr p, WsArr rr, float a_coef,
+                         float b_coef, float lr, hipStream_t st) {
   constexpr int lds = T::template lds_bytes<Num>();
   hipError_t e = allow_lds(k_efx<T, Num, XBF, GBF>, lds);
   if (e != hipSuccess) return e;
@@ -1308,6 +1316,14 @@ static hipError_t efx_t(const ClassDims& d, const MatPtrs& ptrs, const float* sc
   launch_timed(k_efx<T, Num, XBF, GBF>, grid, dim3(T::THREADS), lds, st, d, ptrs, scal, p, rr, a_coef, b_coef, lr);
   OD_CHECK_LAUNCH();
   return hipSuccess;
+}
+template <class Num, bool XBF, bool GBF>
+static hipError_t efx_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr p, WsArr rr, float a_coef,
+                        float b_coef, float lr, hipStream_t st) {
+  // small problems: more, smaller tiles (the kernel is a few microseconds of latency per tile)
+  if ((int64_t)((d.m + 127) / 128) * ((d.n + 127) / 128) * d.nb < 256)
+    return efx_tt<TileSmall, Num, XBF, GBF>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st);
+  return efx_tt<TileSquare, Num, XBF, GBF>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st);
 }
 template <class Num>
 static hipError_t efx_n(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr p, WsArr rr, float a_coef,
