@@ -211,6 +211,11 @@ extern "C" int orthdion_create(orthdion_handle* out, const orthdion_matdesc* mat
     if ((int64_t)b.splits_back * n * r > part) part = (int64_t)b.splits_back * n * r;
     if ((int64_t)b.splits_gram_p * r * r > part) part = (int64_t)b.splits_gram_p * r * r;
     if ((int64_t)b.splits_gram_q * r * r > part) part = (int64_t)b.splits_gram_q * r * r;
+    // r <= 32: the Gram partials of both CholeskyQR passes live side by side
+    if (r <= 32) {
+      const int64_t sg = b.splits_gram_p > b.splits_gram_q ? b.splits_gram_p : b.splits_gram_q;
+      if (2 * sg * r * r > part) part = 2 * sg * r * r;
+    }
     if ((int64_t)b.slabs * r > part) part = (int64_t)b.slabs * r;
     // strides rounded so that every matrix slice stays 256-byte aligned
     auto rnd = [](int64_t e) { return (e + 63) / 64 * 64; };
@@ -273,6 +278,12 @@ static int orth_gram(const Batch& b, char* ws, int rows, size_t off_a0, int64_t 
   WsArr a0{reinterpret_cast<float*>(ws + off_a0), st_a};
   WsArr part{reinterpret_cast<float*>(ws + b.off_part), b.st_part};
   WsArr gram{reinterpret_cast<float*>(ws + b.off_gram), b.st_rr};
+  // one 32 x 32 tile: partial sums in plain fp32, left in the first half of `part` for the
+  // kernel that factors them (its own partials go to the second half)
+  if (b.d.r <= 32) {
+    OD_TRY(od::launch_small_gram(b.d.nb, rows, b.d.r, a0, part, splits, st));
+    return ORTHDION_OK;
+  }
   // a single split is the Gram matrix itself: written straight into the class array
   if (splits == 1) {
     OD_TRY(od::launch_gram(b.d.nb, rows, b.d.r, a0, gram, 1, 1, st));
@@ -299,8 +310,10 @@ static int orth_finish(const Batch& b, char* ws, int rows, size_t off_a0, size_t
   WsArr t2{reinterpret_cast<float*>(ws + off_t2), b.st_rr};
   const HalfArr none{nullptr, 0};
   if (first_pass_in_one_launch(r)) {
-    WsArr gram{reinterpret_cast<float*>(ws + b.off_gram), b.st_rr}, t1{reinterpret_cast<float*>(ws + off_t1), b.st_rr};
-    OD_TRY(od::launch_small_first_pass(nb, rows, r, a0, gram, t1, w, a1, part, splits, info, info_slot, st));
+    WsArr t1{reinterpret_cast<float*>(ws + off_t1), b.st_rr};
+    const WsArr part1 = part;                                   // Gram partials of a0 (orth_gram)
+    part.base += (int64_t)splits * r * r;                       // Gram partials of a1, read by the second pass
+    OD_TRY(od::launch_small_first_pass(nb, rows, r, a0, part1, splits, t1, w, a1, part, splits, info, info_slot, st));
   } else {
     OD_TRY(od::launch_apply(nb, rows, r, a0, w, a1, nullptr, none, none, exact, st));
     OD_TRY(od::launch_gram(nb, rows, r, a1, part, splits, exact, st));

@@ -95,8 +95,11 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp
 // r <= 32: Cholesky factor and inverse of `gram`, A1 = A0 W1 and the Gram partials of A1
 // (`splits` of them, r x r each, in `part`) in one launch; T1 and W1 are written as by
 // launch_cholinv, a bad pivot is reported the same way.
-hipError_t launch_small_first_pass(int nb, int rows, int r, WsArr a0, WsArr gram, WsArr t1, WsArr w1, WsArr a1, WsArr part,
-                                   int splits, int* info, int info_slot, hipStream_t st);
+// `gram` holds `gram_splits` partial sums per matrix, r * r elements apart (launch_small_gram).
+hipError_t launch_small_first_pass(int nb, int rows, int r, WsArr a0, WsArr gram, int gram_splits, WsArr t1, WsArr w1, WsArr a1,
+                                   WsArr part, int splits, int* info, int info_slot, hipStream_t st);
+// r <= 32: Gram partials of A0 in plain fp32, part[split][r][r]
+hipError_t launch_small_gram(int nb, int rows, int r, WsArr a0, WsArr part, int splits, hipStream_t st);
 
 // First-order second pass: from the Gram partials of a nearly orthonormal matrix writes
 // T2 = I + Phi(E), and either W2 = I - Phi(E) (fp32) or, with phit.base non-null, Phi(E)^T as

@@ -404,8 +404,60 @@ __global__ __launch_bounds__(T::THREADS) void k_apply(int rows, int r, WsArr a, 
 // writes T1 and W1.  One thread per row; `part` receives `splits` partial sums of r x r.
 // ------------------------------------------------------------------------------------
 constexpr int kSmallRows = 256, kSmallPitch = 36;
-__global__ __launch_bounds__(kSmallRows) void k_small_first_pass(int rows, int r, WsArr a0, WsArr gram, WsArr t1, WsArr w1,
-                                                                WsArr a1, WsArr part, int splits, int* info, int info_slot) {
+
+// Sum of a^T a over the 64 rows a wave owns of the tile S ([rows][kSmallPitch], 32 columns) on
+// the matrix cores: fp32 32x32x2 products with both operands the same register (lane (c, h)
+// feeds row 2i + h, column c).
+OD_DEV f32x16 small_gram_rows(const float* S, int wave, int lane, f32x16 acc) {
+  const float* sw = S + (wave * 64 + (lane >> 5)) * kSmallPitch + (lane & 31);
+#pragma unroll 8
+  for (int i = 0; i < 32; ++i) {
+    const float a = sw[2 * i * kSmallPitch];
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, a, acc, 0, 0, 0);
+  }
+  return acc;
+}
+// The four waves' tiles summed through S (then [wave][32][kSmallPitch]) and stored as r x r.
+OD_DEV void small_gram_store(float* S, const f32x16& acc, int r, float* out, int tid) {
+  const int lane = tid & 63, wave = tid >> 6;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) S[(wave * 32 + acc_row(v, lane)) * kSmallPitch + (lane & 31)] = acc[v];
+  __syncthreads();
+  const int gi = tid >> 3, gj = 4 * (tid & 7);
+  f32x4 g = *reinterpret_cast<const f32x4*>(S + gi * kSmallPitch + gj);
+#pragma unroll
+  for (int w = 1; w < 4; ++w) g += *reinterpret_cast<const f32x4*>(S + (w * 32 + gi) * kSmallPitch + gj);
+  if (gi < r && gj < r) *reinterpret_cast<f32x4*>(out + (int64_t)gi * r + gj) = g;
+}
+
+// r <= 32: Gram partials A^T A of `splits` row ranges, one thread per row, in plain fp32.
+__global__ __launch_bounds__(kSmallRows) void k_small_gram(int rows, int r, WsArr a0, WsArr part, int splits) {
+  __shared__ __align__(16) float S[kSmallRows * kSmallPitch];
+  const int z = blockIdx.y, split = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  int kend;
+  const int kbeg = split_begin(rows, splits, 8, split, &kend);
+  const float* A = a0.base + (int64_t)z * a0.stride;
+  f32x16 acc;
+#pragma unroll
+  for (int v = 0; v < 16; ++v) acc[v] = 0.f;
+  for (int base = kbeg; base < kend; base += kSmallRows) {
+    const int row = base + tid;
+#pragma unroll
+    for (int j4 = 0; j4 < 8; ++j4) {
+      f32x4 v4 = {0.f, 0.f, 0.f, 0.f};
+      if (row < kend && 4 * j4 < r) v4 = *reinterpret_cast<const f32x4*>(A + (int64_t)row * r + 4 * j4);
+      *reinterpret_cast<f32x4*>(S + tid * kSmallPitch + 4 * j4) = v4;
+    }
+    __syncthreads();
+    acc = small_gram_rows(S, wave, lane, acc);
+    __syncthreads();
+  }
+  small_gram_store(S, acc, r, part.base + (int64_t)z * part.stride + (int64_t)split * r * r, tid);
+}
+
+__global__ __launch_bounds__(kSmallRows) void k_small_first_pass(int rows, int r, WsArr a0, WsArr gram, int gram_splits, WsArr t1,
+                                                                WsArr w1, WsArr a1, WsArr part, int splits, int* info,
+                                                                int info_slot) {
   __shared__ __align__(16) float Wl[32 * kSmallPitch];           // W[k][j]
   __shared__ __align__(16) float S[kSmallRows * kSmallPitch];    // the rows of a1 of one pass
   const int z = blockIdx.y, split = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -419,7 +471,11 @@ __global__ __launch_bounds__(kSmallRows) void k_small_first_pass(int rows, int r
     for (int q = 0; q < 4; ++q) {
       const int gi = 8 * q + 4 * h;
       f32x4 v4 = {0.f, 0.f, 0.f, 0.f};
-      if (c < r && gi < r) v4 = *reinterpret_cast<const f32x4*>(G + (int64_t)c * r + gi);
+      if (c < r && gi < r) {
+        // `gram_splits` partial sums, r * r apart, added in order
+#pragma unroll 8
+        for (int sp = 0; sp < gram_splits; ++sp) v4 += *reinterpret_cast<const f32x4*>(G + (int64_t)sp * r * r + (int64_t)c * r + gi);
+      }
 #pragma unroll
       for (int e = 0; e < 4; ++e) d[4 * q + e] = (c < r && gi < r) ? v4[e] : ((gi + e == c) ? 1.f : 0.f);
     }
@@ -447,9 +503,7 @@ __global__ __launch_bounds__(kSmallRows) void k_small_first_pass(int rows, int r
   const int kbeg = split_begin(rows, splits, 8, split, &kend);
   const float* A = a0.base + (int64_t)z * a0.stride;
   float* O = a1.base + (int64_t)z * a1.stride;
-  // Gram of the produced rows: every wave adds up its 64 rows of a pass on the matrix cores
-  // (fp32 32x32x2 products, both operands the same register: lane (c, h) feeds row 2i + h,
-  // column c); the four partial tiles are summed through LDS at the end.
+  // Gram of the produced rows, 64 per wave and pass; the four tiles are summed at the end
   f32x16 gacc;
 #pragma unroll
   for (int v = 0; v < 16; ++v) gacc[v] = 0.f;
@@ -485,25 +539,11 @@ __global__ __launch_bounds__(kSmallRows) void k_small_first_pass(int rows, int r
       *reinterpret_cast<f32x4*>(S + tid * kSmallPitch + 4 * jb) = valid ? o[jb] : f32x4{0.f, 0.f, 0.f, 0.f};
     }
     __syncthreads();
-    const float* sw = S + (wave * 64 + (lane >> 5)) * kSmallPitch + (lane & 31);
-#pragma unroll 8
-    for (int i = 0; i < 32; ++i) {
-      const float a = sw[2 * i * kSmallPitch];
-      gacc = __builtin_amdgcn_mfma_f32_32x32x2f32(a, a, gacc, 0, 0, 0);
-    }
+    gacc = small_gram_rows(S, wave, lane, gacc);
     __syncthreads();
   }
   if (first) __syncthreads();          // a workgroup without rows still meets the others' barrier count
-  // sum of the four waves' tiles: S doubles as [wave][32][pitch]
-#pragma unroll
-  for (int v = 0; v < 16; ++v) S[(wave * 32 + acc_row(v, lane)) * kSmallPitch + (lane & 31)] = gacc[v];
-  __syncthreads();
-  const int gi_ = tid >> 3, gj_ = 4 * (tid & 7);
-  f32x4 g2 = *reinterpret_cast<const f32x4*>(S + gi_ * kSmallPitch + gj_);
-#pragma unroll
-  for (int w = 1; w < 4; ++w) g2 += *reinterpret_cast<const f32x4*>(S + (w * 32 + gi_) * kSmallPitch + gj_);
-  if (gi_ < r && gj_ < r)
-    *reinterpret_cast<f32x4*>(part.base + (int64_t)z * part.stride + (int64_t)split * r * r + (int64_t)gi_ * r + gj_) = g2;
+  small_gram_store(S, gacc, r, part.base + (int64_t)z * part.stride + (int64_t)split * r * r, tid);
 }
 
 // ------------------------------------------------------------------------------------
@@ -1267,11 +1307,18 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp
   return hipSuccess;
 }
 
-hipError_t launch_small_first_pass(int nb, int rows, int r, WsArr a0, WsArr gram, WsArr t1, WsArr w1, WsArr a1, WsArr part,
-                                   int splits, int* info, int info_slot, hipStream_t st) {
+hipError_t launch_small_gram(int nb, int rows, int r, WsArr a0, WsArr part, int splits, hipStream_t st) {
   if (r > 32) return hipErrorInvalidValue;
-  hipLaunchKernelGGL(k_small_first_pass, dim3(splits, nb), dim3(kSmallRows), 0, st, rows, r, a0, gram, t1, w1, a1, part, splits,
-                     info, info_slot);
+  hipLaunchKernelGGL(k_small_gram, dim3(splits, nb), dim3(kSmallRows), 0, st, rows, r, a0, part, splits);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+
+hipError_t launch_small_first_pass(int nb, int rows, int r, WsArr a0, WsArr gram, int gram_splits, WsArr t1, WsArr w1, WsArr a1,
+                                   WsArr part, int splits, int* info, int info_slot, hipStream_t st) {
+  if (r > 32) return hipErrorInvalidValue;
+  hipLaunchKernelGGL(k_small_first_pass, dim3(splits, nb), dim3(kSmallRows), 0, st, rows, r, a0, gram, gram_splits, t1, w1, a1,
+                     part, splits, info, info_slot);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
