@@ -269,6 +269,10 @@ def main():
     step_bytes = sum(algorithmic_work(w, p)[0] for p in ("proj", "back", "efx"))
     step_flops = sum(algorithmic_work(w, p)[1] for p in ("proj", "back", "efx"))
 
+    # counter-measured traffic of the three streaming kernels over the whole step, where profiled
+    meas = [MEASURED_TRAFFIC.get((w.name, p)) for p in ("proj", "back", "efx")]
+    step_measured = sum(meas) if all(meas) and args.variant == "qr" else None
+
     out = {
         "metric": "Orth-Dion optimizer steps/sec over model matrix set; achieved HBM GB/s vs peak",
         "value": steps_per_s, "unit": "steps/s", "n_gpus": 1, "steps": K, "warmup": args.warmup,
@@ -292,7 +296,9 @@ def main():
                        "algorithmic_TFLOPs": step_flops / (ms_per_step * 1e-3) / 1e12,
                        "hbm_frac": step_bytes / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS,
                        "mfma_frac": step_flops / (ms_per_step * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
-                       "hbm_frac_of_copy": step_bytes / (ms_per_step * 1e-3) / 1e9 / copy_gbps},
+                       "hbm_frac_of_copy": step_bytes / (ms_per_step * 1e-3) / 1e9 / copy_gbps,
+                       "measured_GBps": (step_measured / (ms_per_step * 1e-3) / 1e9) if step_measured else None,
+                       "measured_hbm_frac": (step_measured / (ms_per_step * 1e-3) / 1e9 / HBM_PEAK_GBS) if step_measured else None},
         "phase_ms_per_step_warmup": {k: round(v, 5) for k, v in phase_ms.items()},
         "batches": batches,
     }
