@@ -366,8 +366,11 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
   int* info_all = reinterpret_cast<int*>(ws + h->off_info);
   float* scal_all = reinterpret_cast<float*>(ws + h->off_scal);
   if (prec != od::PREC_F16) {     // in fast precision the first kernel of every batch clears its own words
-    OD_TRY(od::launch_fill_int(info_all, (int64_t)nmat * od::kInfoPerMat, 0, st));
-    OD_TRY(od::launch_fill_f32(scal_all, (int64_t)nmat * od::kScalPerMat, 0.f, st));
+    // the scale words and, right behind them in the workspace, the info words: one fill (0.f and
+    // 0 are the same bits)
+    static_assert(sizeof(float) == sizeof(int), "one fill clears both tables");
+    const int64_t words = (int64_t)((h->off_info - h->off_scal) / sizeof(int)) + (int64_t)nmat * od::kInfoPerMat;
+    OD_TRY(od::launch_fill_int(reinterpret_cast<int*>(scal_all), words, 0, st));
   }
   h->last_ws = workspace;
   const bool diag = h->diag_on;
