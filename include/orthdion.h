@@ -49,7 +49,8 @@ typedef enum {
   ORTHDION_E_WORKSPACE_TOO_SMALL = -4,
   ORTHDION_E_MISALIGNED = -5,         /* a device pointer is not 16-byte aligned                */
   ORTHDION_E_HIP = -6,                /* a HIP call failed; hipGetLastError has the cause       */
-  ORTHDION_E_NO_STEP = -7             /* orthdion_get_info before any orthdion_step             */
+  ORTHDION_E_NO_STEP = -7,            /* orthdion_get_info before any orthdion_step             */
+  ORTHDION_E_NO_MEMORY = -8           /* a host allocation failed                               */
 } orthdion_status;
 
 typedef enum { ORTHDION_F32 = 0, ORTHDION_BF16 = 1 } orthdion_dtype;

@@ -35,6 +35,13 @@ Readings of points the paper leaves open:
 
 Every product is a plain numpy matmul in float64; the QR is Householder
 reflections written out below.  Nothing is blocked, fused or reordered.
+
+``OrthDionOracle(qr="library")`` takes the same thin QR factor (Alg. 1 lines 2 and 4; the
+positive-diagonal factor is unique for full column rank) from numpy's QR routine with the
+signs fixed afterwards, instead of the reflections written out here.  It exists for the
+parity tests at the largest benchmark shapes (rank >= 1024), where the written-out
+reflections take minutes per matrix; the two routes are pinned against each other and
+against the same closed forms in the CPU tests.  The default stays the written-out one.
 """
 from __future__ import annotations
 
@@ -42,7 +49,7 @@ from typing import Dict, Optional, Tuple
 
 import numpy as np
 
-__all__ = ["thin_qr_positive", "col_norm", "ef_coefficients", "OrthDionOracle",
+__all__ = ["thin_qr_positive", "thin_qr_library", "col_norm", "ef_coefficients", "OrthDionOracle",
            "bf16_bits_to_f64", "f64_to_bf16_bits", "rel_fro", "effective_rank", "diagnostics", "gradient_persistence", "rank_policy",
            "resize_right_factor"]
 
@@ -113,6 +120,18 @@ def thin_qr_positive(a: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
     return q * sign[None, :], t * sign[:, None]
 
 
+def thin_qr_library(a: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
+    """The same factorisation as ``thin_qr_positive`` (``a = q @ t``, orthonormal ``q``, upper
+    triangular ``t`` with ``diag(t) > 0``; Alg. 1 lines 2 and 4) with numpy's thin QR as the
+    library step: column j of ``q`` and row j of ``t`` change sign wherever ``t[j, j] < 0``."""
+    a = np.asarray(a, dtype=np.float64)
+    if a.shape[0] < a.shape[1]:
+        raise ValueError("thin QR needs rows >= cols")
+    q, t = np.linalg.qr(a, mode="reduced")
+    sign = np.where(np.diag(t) < 0.0, -1.0, 1.0)
+    return q * sign[None, :], np.triu(t) * sign[:, None]
+
+
 def col_norm(r: np.ndarray) -> np.ndarray:
     """ColNorm of the Dion variant: every column rescaled to unit Euclidean length.
     A zero column is left as zeros."""
@@ -143,10 +162,13 @@ class OrthDionOracle:
     test can plant a mistake in exactly one of them and check that the pins notice."""
 
     def __init__(self, mu: float = 0.95, lr: float = 0.01, variant: str = "qr",
-                 ef: str = "dion", x_bf16: bool = False):
+                 ef: str = "dion", x_bf16: bool = False, qr: str = "householder"):
         if variant not in ("qr", "colnorm"):
             raise ValueError("variant must be 'qr' or 'colnorm'")
+        if qr not in ("householder", "library"):
+            raise ValueError("qr must be 'householder' or 'library'")
         self.mu, self.lr, self.variant, self.ef, self.x_bf16 = float(mu), float(lr), variant, ef, bool(x_bf16)
+        self.qr = qr
         ef_coefficients(mu, ef)
 
     # Alg. 1 line 1
@@ -159,7 +181,7 @@ class OrthDionOracle:
 
     # Alg. 1 lines 2 and 4 (orth)
     def orth(self, a: np.ndarray) -> Tuple[np.ndarray, np.ndarray]:
-        return thin_qr_positive(a)
+        return thin_qr_library(a) if self.qr == "library" else thin_qr_positive(a)
 
     # Alg. 1 line 3
     def back_project(self, b: np.ndarray, p: np.ndarray) -> np.ndarray:

@@ -18,6 +18,7 @@ ORTHDION_E_WORKSPACE_TOO_SMALL = -4
 ORTHDION_E_MISALIGNED = -5
 ORTHDION_E_HIP = -6
 ORTHDION_E_NO_STEP = -7
+ORTHDION_E_NO_MEMORY = -8
 
 ORTHDION_F32, ORTHDION_BF16 = 0, 1
 ORTHDION_QR, ORTHDION_COLNORM = 0, 1
@@ -249,6 +250,8 @@ class OrthDion:
         self.shapes = [tuple(s) for s in shapes]
         self.nmat = len(self.shapes)
         self.r = r
+        self._x_dtype = {"f32": torch.float32, "bf16": torch.bfloat16}[x_dtype]
+        self._g_dtype = {"f32": torch.float32, "bf16": torch.bfloat16}[g_dtype]
         self.handle = orthdion_create(self.shapes, r, dt[x_dtype], dt[g_dtype],
                                       {"qr": ORTHDION_QR, "colnorm": ORTHDION_COLNORM}[variant],
                                       {"dion": ORTHDION_EF_DION, "paper": ORTHDION_EF_PAPER, "polyak": ORTHDION_EF_POLYAK}[ef],
@@ -258,8 +261,26 @@ class OrthDion:
         self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=device)
         self._torch = torch
 
+    def _check_buffers(self, X, G, M, Q) -> None:
+        """The library sees raw addresses only: a tensor of the wrong type, shape or layout
+        would be read and written out of bounds, so it is refused here."""
+        torch = self._torch
+        for name, seq in (("X", X), ("G", G), ("M", M), ("Q", Q)):
+            if len(seq) != self.nmat:
+                raise ValueError(f"{name}: expected {self.nmat} tensors, got {len(seq)}")
+        for i, (m, n) in enumerate(self.shapes):
+            r = self.r if isinstance(self.r, int) else self.r[i]
+            want = {"X": ((m, n), self._x_dtype), "G": ((m, n), self._g_dtype), "M": ((m, n), torch.float32),
+                    "Q": ((n, r), torch.float32)}
+            for name, t in (("X", X[i]), ("G", G[i]), ("M", M[i]), ("Q", Q[i])):
+                shape, dtype = want[name]
+                if not t.is_cuda or tuple(t.shape) != shape or t.dtype != dtype or not t.is_contiguous():
+                    raise ValueError(f"{name}[{i}]: need a contiguous {dtype} device tensor of shape {shape}, got "
+                                     f"{t.dtype} {tuple(t.shape)} on {t.device}, contiguous={t.is_contiguous()}")
+
     def step(self, X, G, M, Q, stream=None) -> None:
         torch = self._torch
+        self._check_buffers(X, G, M, Q)
         st = stream if stream is not None else torch.cuda.current_stream().cuda_stream
         orthdion_step(self.handle, [t.data_ptr() for t in X], [t.data_ptr() for t in G],
                       [t.data_ptr() for t in M], [t.data_ptr() for t in Q],

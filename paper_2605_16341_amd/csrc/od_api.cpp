@@ -110,10 +110,36 @@ static int check_shape(const orthdion_matdesc& m) {
   return ORTHDION_OK;
 }
 
+// Nothing may throw across the C boundary: the entry points that allocate host memory run their
+// bodies through this.
+template <class F>
+static int no_throw(F&& body) {
+  try {
+    return body();
+  } catch (const std::bad_alloc&) {
+    return ORTHDION_E_NO_MEMORY;
+  } catch (...) {
+    return ORTHDION_E_INVALID_ARG;
+  }
+}
+
+static int create_impl(orthdion_handle* out, const orthdion_matdesc* mats, int32_t nmat, const orthdion_config* cfg);
+
 extern "C" int orthdion_create(orthdion_handle* out, const orthdion_matdesc* mats, int32_t nmat,
                                const orthdion_config* cfg) {
   if (!out) return ORTHDION_E_NULL_PTR;
   *out = nullptr;
+  orthdion_handle h = nullptr;
+  const int rc = no_throw([&] { return create_impl(&h, mats, nmat, cfg); });
+  if (rc != ORTHDION_OK) {
+    delete h;
+    return rc;
+  }
+  *out = h;
+  return ORTHDION_OK;
+}
+
+static int create_impl(orthdion_handle* out, const orthdion_matdesc* mats, int32_t nmat, const orthdion_config* cfg) {
   if (!mats || !cfg) return ORTHDION_E_NULL_PTR;
   if (nmat < 1 || nmat > (1 << 20)) return ORTHDION_E_INVALID_ARG;
   int rc = check_config(cfg);
@@ -122,7 +148,8 @@ extern "C" int orthdion_create(orthdion_handle* out, const orthdion_matdesc* mat
     if ((rc = check_shape(mats[i])) != ORTHDION_OK) return rc;
 
   orthdion_ctx* h = new (std::nothrow) orthdion_ctx();
-  if (!h) return ORTHDION_E_INVALID_ARG;
+  if (!h) return ORTHDION_E_NO_MEMORY;
+  *out = h;                        // the caller frees it if anything below fails or throws
   h->mats.assign(mats, mats + nmat);
   h->cfg = *cfg;
   h->last_ws = nullptr;
@@ -236,7 +263,6 @@ extern "C" int orthdion_create(orthdion_handle* out, const orthdion_matdesc* mat
     b.off_rh = take_h(b.st_r); b.off_qh = take_h(b.st_r); b.off_qht = take_h(b.st_r);
   }
   h->ws_bytes = off;
-  *out = h;
   return ORTHDION_OK;
 }
 
@@ -307,10 +333,9 @@ static int orth_finish(const Batch& b, char* ws, int rows, size_t off_a0, size_t
   WsArr a0{reinterpret_cast<float*>(ws + off_a0), st_a}, a1{reinterpret_cast<float*>(ws + off_a1), st_a};
   WsArr part{reinterpret_cast<float*>(ws + b.off_part), b.st_part};
   WsArr w{reinterpret_cast<float*>(ws + b.off_w), b.st_rr};
-  WsArr t2{reinterpret_cast<float*>(ws + off_t2), b.st_rr};
+  WsArr t1{reinterpret_cast<float*>(ws + off_t1), b.st_rr}, t2{reinterpret_cast<float*>(ws + off_t2), b.st_rr};
   const HalfArr none{nullptr, 0};
   if (first_pass_in_one_launch(r)) {
-    WsArr t1{reinterpret_cast<float*>(ws + off_t1), b.st_rr};
     const WsArr part1 = part;                                   // Gram partials of a0 (orth_gram)
     part.base += (int64_t)splits * r * r;                       // Gram partials of a1, read by the second pass
     OD_TRY(od::launch_small_first_pass(nb, rows, r, a0, part1, splits, t1, w, a1, part, splits, info, info_slot, st));
@@ -322,9 +347,25 @@ static int orth_finish(const Batch& b, char* ws, int rows, size_t off_a0, size_t
   // stays in fp32); exact precision: the product a1 (I - Phi(E)) on six-product operands
   // (Phi^T as fp16 operand words lives in the r x r scratch the factorisation no longer needs)
   const HalfArr phit{exact ? nullptr : reinterpret_cast<uint16_t*>(ws + b.off_tmp), 2 * b.st_rr};
-  OD_TRY(od::launch_corr(nb, r, part, splits, t2, w, phit, scal, 2 + info_slot, info, info_slot, st));
-  if (exact) OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, hn, ht, exact, st));
-  else OD_TRY(od::launch_apply_correction(nb, rows, r, a1, phit, a0, q_out, hn, ht, st));
+  OD_TRY(od::launch_corr(nb, r, part, splits, t1, t2, w, phit, scal, 2 + info_slot, info, info_slot, st));
+  // A matrix whose first pass left a deviation too large for the first-order form (an
+  // ill-conditioned B Q or R) gets a true second pass instead: Cholesky factor and inverse of
+  // its I + E (T2 and W2 are overwritten), then the full triangular product.  Every launch of
+  // this branch returns at once for the other matrices.
+  const od::Pred big{scal, 2 + info_slot, od::kFirstOrderDeviation, 1}, small{scal, 2 + info_slot, od::kFirstOrderDeviation, 0};
+  WsArr gram{reinterpret_cast<float*>(ws + b.off_gram), b.st_rr}, tmp{reinterpret_cast<float*>(ws + b.off_tmp), b.st_rr};
+  if (r <= 256) {
+    OD_TRY(od::launch_cholinv(nb, r, part, t2, w, tmp, info, info_slot, st, big, splits, (int64_t)r * r));
+  } else {
+    OD_TRY(od::launch_reduce(nb, part, splits, (int64_t)r * r, gram, st, big));
+    OD_TRY(od::launch_cholinv(nb, r, gram, t2, w, tmp, info, info_slot, st, big));
+  }
+  if (exact) {
+    OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, hn, ht, exact, st));
+  } else {
+    OD_TRY(od::launch_apply_correction(nb, rows, r, a1, phit, a0, q_out, hn, ht, st, small));
+    OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, hn, ht, exact, st, big));
+  }
   return ORTHDION_OK;
 }
 
@@ -512,8 +553,8 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
                                    diag_all + (size_t)b.slot_base * od::kDiagPerMat, st));
     }
     OD_PHASE_KERNEL(ORTHDION_PHASE_EFX);
-    if (fast) OD_TRY(od::launch_efx_h(d, v.ptrs, v.scal, v.ph, v.rh, v.qh, a_coef, b_coef, h->cfg.lr, st));
-    else OD_TRY(od::launch_efx(d, v.ptrs, prec, v.scal, v.pa, v.ra, a_coef, b_coef, h->cfg.lr, st));
+    if (fast) OD_TRY(od::launch_efx_h(d, v.ptrs, v.scal, v.info, v.ph, v.rh, v.qh, a_coef, b_coef, h->cfg.lr, st));
+    else OD_TRY(od::launch_efx(d, v.ptrs, prec, v.scal, v.info, v.pa, v.ra, a_coef, b_coef, h->cfg.lr, st));
     return ORTHDION_OK;
   };
 
@@ -546,8 +587,12 @@ extern "C" int orthdion_profile_begin(orthdion_handle h, uint32_t phase_mask, in
   if (!h) return ORTHDION_E_NULL_PTR;
   if (max_steps < 1 || max_steps > 100000 || h->prof_on) return ORTHDION_E_INVALID_ARG;
   size_t count = (size_t)max_steps * h->batches.size() * ORTHDION_NPHASE * 2;
-  h->prof_events.assign(count, nullptr);
-  h->prof_recorded.assign(count / 2, 0);
+  const int rc_alloc = no_throw([&] {
+    h->prof_events.assign(count, nullptr);
+    h->prof_recorded.assign(count / 2, 0);
+    return (int)ORTHDION_OK;
+  });
+  if (rc_alloc != ORTHDION_OK) return rc_alloc;
   for (int s = 0; s < max_steps; ++s)
     for (size_t b = 0; b < h->batches.size(); ++b)
       for (int ph = 0; ph < ORTHDION_NPHASE; ++ph)
@@ -596,7 +641,9 @@ extern "C" int orthdion_get_info(orthdion_handle h, int32_t* info_host, void* st
   if (!h->last_ws) return ORTHDION_E_NO_STEP;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const int nmat = (int)h->mats.size();
-  std::vector<int> raw((size_t)nmat * od::kInfoPerMat);
+  std::vector<int> raw;
+  const int rc_alloc = no_throw([&] { raw.resize((size_t)nmat * od::kInfoPerMat); return (int)ORTHDION_OK; });
+  if (rc_alloc != ORTHDION_OK) return rc_alloc;
   const char* ws = reinterpret_cast<const char*>(h->last_ws);
   OD_TRY(hipMemcpyAsync(raw.data(), ws + h->off_info, raw.size() * sizeof(int), hipMemcpyDeviceToHost, st));
   OD_TRY(hipStreamSynchronize(st));
@@ -625,7 +672,9 @@ extern "C" int orthdion_get_diagnostics(orthdion_handle h, float* out_host, void
   if (!h->last_ws || !h->diag_valid) return ORTHDION_E_NO_STEP;
   hipStream_t st = reinterpret_cast<hipStream_t>(stream);
   const int nmat = (int)h->mats.size();
-  std::vector<float> raw((size_t)nmat * od::kDiagPerMat);
+  std::vector<float> raw;
+  const int rc_alloc = no_throw([&] { raw.resize((size_t)nmat * od::kDiagPerMat); return (int)ORTHDION_OK; });
+  if (rc_alloc != ORTHDION_OK) return rc_alloc;
   const char* ws = reinterpret_cast<const char*>(h->last_ws);
   OD_TRY(hipMemcpyAsync(raw.data(), ws + h->off_diag, raw.size() * sizeof(float), hipMemcpyDeviceToHost, st));
   OD_TRY(hipStreamSynchronize(st));
@@ -695,6 +744,7 @@ extern "C" const char* orthdion_strerror(int status) {
     case ORTHDION_E_MISALIGNED: return "device pointer not sufficiently aligned";
     case ORTHDION_E_HIP: return "HIP call failed";
     case ORTHDION_E_NO_STEP: return "no step has been enqueued on this handle";
+    case ORTHDION_E_NO_MEMORY: return "out of host memory";
     default: return "unknown status";
   }
 }

@@ -59,12 +59,6 @@ constexpr int kCholOffStash = kCholOffSync + 2 * kCNT * 4;      // two fp32 tile
 constexpr int kCholLds = kCholOffStash + 2 * 4096;
 constexpr int kCholSpinLimit = 1 << 22;  // bound of every wait below (never reached: the producers do not wait)
 
-#ifdef OD_CHOL_TIMING
-#define OD_TICK(slot) do { if (lane == 0) a.dbg[(z * 8 + wave) * 64 + (slot)] = wall_clock64(); } while (0)
-#else
-#define OD_TICK(slot) do { } while (0)
-#endif
-
 struct CholArgs {
   WsArr src;           // Gram block source: `splits` partial sums, `split_stride` elements apart
   int splits;
@@ -74,9 +68,7 @@ struct CholArgs {
   int blk;             // which diagonal block of kCholMax
   int* info;
   int info_slot;
-#ifdef OD_CHOL_TIMING
-  long long* dbg;
-#endif
+  Pred pred;           // the matrix is skipped unless its predicate holds
 };
 
 // tile (I, K), I < K, of slot s of worker u, four bits per slot, 15 = no tile (kept in scalar
@@ -316,6 +308,8 @@ __global__ __launch_bounds__(kCholThreads) void k_chol256(CholArgs a) {
   char* stash = lds_raw + kCholOffStash;                                 // buffer J & 1
 
   const int z = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+  // uniform over the workgroup, before any barrier or LDS hand-off
+  if (a.pred.scal != nullptr && (a.pred.scal[z * kScalPerMat + a.pred.slot] > a.pred.thr) != (a.pred.want != 0)) return;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const bool diag_wave = wave == kCholDiagWave;
   const int worker = diag_wave ? 6 : (wave < kCholDiagWave ? wave : wave - 1);
@@ -330,7 +324,6 @@ __global__ __launch_bounds__(kCholThreads) void k_chol256(CholArgs a) {
   float* wg = a.w.base + (int64_t)z * a.w.stride + off;
   const int col = lane & 31, half = lane >> 5;
   if (tid < 2 * kCNT) published[tid] = 0;
-  OD_TICK(0);
 
   // ---- tiles strictly below the diagonal of T and W are zero and written by nobody else:
   // one tile per iteration (256 threads x 16 bytes = one 32 x 32 tile)
@@ -380,7 +373,6 @@ __global__ __launch_bounds__(kCholThreads) void k_chol256(CholArgs a) {
       for (int v = 0; v < 16; ++v) acc[s][v] = 0.f;
     }
   }
-  OD_TICK(1);
 
   // ================================ factorisation ================================
   // (a) tile (J, J): factor, invert, write T_JJ and W_JJ, publish W_JJ^T
@@ -498,14 +490,12 @@ __global__ __launch_bounds__(kCholThreads) void k_chol256(CholArgs a) {
   }
   lds_barrier();
   for (int J = 0; J < nt; ++J) {
-    OD_TICK(4 + 4 * J);
     if (diag_wave) {
       // ---- the serial chain stays in this wave: T(J, J+1) = W_JJ^T S(J, J+1) from the stash,
       // tile (J+1, J+1) -= T^T T (both fp32 products with the accumulator as k-side operand,
       // see panel_tile), then its factorisation.  The workers form T(J, J+1) again for the panel.
       if (J + 1 < nt) {
         if (J > 0) lds_wait_ge(s_ready + J, 1);
-        OD_TICK(5 + 4 * J);
         const f32x16 sj = load_dtile(stash + (J & 1) * 4096, lane);
         f32x16 dn = load_dtile(vpanel + (J + 1) * kPTile, lane);
         const float* wt = Wt + (J & 1) * kCTileF;
@@ -528,7 +518,6 @@ __global__ __launch_bounds__(kCholThreads) void k_chol256(CholArgs a) {
         for (int v = 0; v < 16; ++v) dn = mfma_f32_k2(-t1[v], t1[v], dn);
         do_diag(J + 1, dn);
       }
-      OD_TICK(6 + 4 * J);
     } else {
       // ---- (b) row J of T and row J of V; the tile the diagonal wave waits for goes first
       const float* wt = Wt + (J & 1) * kCTileF;
@@ -546,11 +535,9 @@ __global__ __launch_bounds__(kCholThreads) void k_chol256(CholArgs a) {
         const bool row_tile = I == J && K > J + 1 && K < nt, col_tile = K == J && I < J;
         if (row_tile || col_tile) panel_tile(acc[s], mrow, J, I, K, row_tile);
       }
-      OD_TICK(5 + 4 * J);
       // ---- (c) once all nt - 1 tiles of the step are published:
       // S(I, K) -= T(J, I)^T T(J, K) for J < I < K;  S'(K, I) += T(J, K)^T V(J, I) for I <= J < K
       lds_wait_ge(published + J, nt - 1);
-      OD_TICK(6 + 4 * J);
 #pragma unroll
       for (int s = 0; s < kCSlots; ++s) {
         const int I = (int)(ownI >> (4 * s)) & 15, K = (int)(ownK >> (4 * s)) & 15;
@@ -565,13 +552,9 @@ __global__ __launch_bounds__(kCholThreads) void k_chol256(CholArgs a) {
         }
       }
     }
-    OD_TICK(7 + 4 * J);
     // the next step rewrites the panels and the other Wt buffer
     lds_barrier();
   }
-  OD_TICK(40);
-  OD_TICK(41);
-  OD_TICK(42);
 }
 
 }  // namespace od

@@ -39,6 +39,16 @@ struct HalfArr {
   int64_t stride;      // elements between consecutive matrices
 };
 
+// A launch made conditional, matrix by matrix, on a scale-table word written by an earlier
+// kernel of the same stream: matrix z is processed only if
+// (scal[z * kScalPerMat + slot] > thr) == (want != 0).  scal == nullptr: unconditional.
+struct Pred {
+  const float* scal;
+  int slot;
+  float thr;
+  int want;
+};
+
 // scal layout per matrix (floats): [1] scale of R, [2] / [3] largest deviation of the
 // first-pass Gram matrix of the left / right factor from identity, [8..39] sampled row sums
 // of squares of B
@@ -47,6 +57,15 @@ constexpr int kScalSample = 8;
 // info layout per matrix (ints): [0] left-factor breakdown column, [1] right-factor
 // breakdown column (1-based, 0 = none), [2] zero-column flag of ColNorm, [3] spare
 constexpr int kInfoPerMat = 4;
+// Second CholeskyQR pass: up to kFirstOrderDeviation (largest entry of the first pass's
+// G - I) the pass is the first-order correction I - Phi(E), whose O(E^2) remainder then stays
+// near the rounding of the measurement itself; above it, up to kMaxGramDeviation, a second
+// factorisation of I + E is run for that matrix; beyond that the matrix is flagged.
+constexpr float kFirstOrderDeviation = 1.0e-3f;
+constexpr float kMaxGramDeviation = 0.5f;
+// smallest ratio of diagonal entries of the first pass's triangular factor (about the
+// reciprocal condition number of the factor) that still counts as full rank
+constexpr float kMinPivotRatio = 1.0e-3f;
 
 // first kernel of a step in fast precision: clears the matrices' scale words [0..7] and flag
 // words, samples sums of squares of B (for its fp16 scale) and writes Q as pre-scaled fp16,
@@ -63,7 +82,7 @@ hipError_t launch_proj(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const
 hipError_t launch_back(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal,
                        WsArr p, WsArr part, int splits, HalfArr pht, hipStream_t st);
 // out[i] = sum_s part[s * count + i], i < count, per matrix
-hipError_t launch_reduce(int nb, WsArr part, int splits, int64_t count, WsArr out, hipStream_t st);
+hipError_t launch_reduce(int nb, WsArr part, int splits, int64_t count, WsArr out, hipStream_t st, Pred pred = Pred{nullptr, 0, 0.f, 0});
 // the same for R (n x r), also written as pre-scaled fp16 [n][r]; with one split `part` may be
 // `out` itself (the back-projection wrote R in place): then only the fp16 copy is written
 hipError_t launch_reduce_r(const ClassDims& d, WsArr part, int splits, WsArr out, HalfArr rh, const float* scal, hipStream_t st);
@@ -75,12 +94,12 @@ hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits,
 // With hn.base / ht.base non-null the result is also stored as fp16 scaled by 2^10, in
 // natural [rows][r] and transposed [r][rows] layout.
 hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs, HalfArr hn,
-                        HalfArr ht, int exact, hipStream_t st);
+                        HalfArr ht, int exact, hipStream_t st, Pred pred = Pred{nullptr, 0, 0.f, 0});
 // out = A - A * Phi with Phi upper triangular and small (the first-order second pass of
 // CholeskyQR2): A enters in fp32, the correction is a single fp16 product.  `phit` is Phi^T as
 // fp16 scaled by 2^13, [r][r] per matrix (written by launch_corr).  Outputs as above.
 hipError_t launch_apply_correction(int nb, int rows, int r, WsArr a, HalfArr phit, WsArr out, const MatPtrs* q_ptrs,
-                                   HalfArr hn, HalfArr ht, hipStream_t st);
+                                   HalfArr hn, HalfArr ht, hipStream_t st, Pred pred = Pred{nullptr, 0, 0.f, 0});
 
 // Cholesky factor and its inverse of the SPD r x r matrices `gram` (ld r): gram = T^T T,
 // W = T^-1, both upper triangular with zeros below the diagonal.  The matrices need not belong
@@ -89,8 +108,10 @@ hipError_t launch_apply_correction(int nb, int rows, int r, WsArr a, HalfArr phi
 // blocked, `gram` is destroyed and `tmp` is r x r scratch.  A non-positive or non-finite pivot
 // writes its 1-based column to info[mat * kInfoPerMat + info_slot] (first failure wins); the
 // factors of such a matrix are unspecified (they may hold NaN).
+// With `splits` > 1 (r <= 256 only) `gram` holds that many partial sums per matrix, `split_stride`
+// elements apart, which the factorisation adds up itself.
 hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp, int* info, int info_slot,
-                          hipStream_t st);
+                          hipStream_t st, Pred pred = Pred{nullptr, 0, 0.f, 0}, int splits = 1, int64_t split_stride = 0);
 
 // r <= 32: Cholesky factor and inverse of `gram`, A1 = A0 W1 and the Gram partials of A1
 // (`splits` of them, r x r each, in `part`) in one launch; T1 and W1 are written as by
@@ -104,9 +125,11 @@ hipError_t launch_small_gram(int nb, int rows, int r, WsArr a0, WsArr part, int 
 // First-order second pass: from the Gram partials of a nearly orthonormal matrix writes
 // T2 = I + Phi(E), and either W2 = I - Phi(E) (fp32) or, with phit.base non-null, Phi(E)^T as
 // fp16 scaled by 2^13 ([r][r], stride phit.stride) instead; max |E| into scal[mat][scal_slot]
-// (must be zeroed); a deviation above 0.1 (or NaN) is a breakdown: info[mat][info_slot] = r
-// unless already set.
-hipError_t launch_corr(int nb, int r, WsArr part, int splits, WsArr t2, WsArr w2, HalfArr phit, float* scal,
+// (must be zeroed); a deviation above kMaxGramDeviation (or NaN) is a breakdown:
+// info[mat][info_slot] = r unless already set.
+// Also reads the diagonal of the first pass's factor `t1`: a ratio of its smallest to its
+// largest entry below kMinPivotRatio reports the matrix as numerically rank deficient.
+hipError_t launch_corr(int nb, int r, WsArr part, int splits, WsArr t1, WsArr t2, WsArr w2, HalfArr phit, float* scal,
                        int scal_slot, int* info, int info_slot, hipStream_t st);
 
 // scal[mat][1] = power-of-two scale for R from trace(gram) = ||R||_F^2 (rows n, cols r)
@@ -118,12 +141,14 @@ hipError_t launch_colnorm(int nb, int n, int r, WsArr rr, const MatPtrs& ptrs, W
                           float* scal, int* info, HalfArr qh, hipStream_t st);
 
 // M_new = a (M+G) - b P R^T ;  X_new = X - lr P Q^T   (one pass over M, G, X)
-hipError_t launch_efx(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p,
+// A matrix whose info words report a breakdown keeps its X and gets M_new = a (M + G): its
+// factors are unspecified and must not reach the caller's state.
+hipError_t launch_efx(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, const int* info, WsArr p,
                       WsArr rr, float a_coef, float b_coef, float lr, hipStream_t st);
 
 // the same pass from the pre-scaled fp16 factors (fast precision)
-hipError_t launch_efx_h(const ClassDims& d, const MatPtrs& ptrs, const float* scal, HalfArr ph, HalfArr rh, HalfArr qh,
-                        float a_coef, float b_coef, float lr, hipStream_t st);
+hipError_t launch_efx_h(const ClassDims& d, const MatPtrs& ptrs, const float* scal, const int* info, HalfArr ph, HalfArr rh,
+                        HalfArr qh, float a_coef, float b_coef, float lr, hipStream_t st);
 
 // ---- optional diagnostics (od_diag.hip) ----
 constexpr int kDiagPerMat = 8;     // floats reported per matrix

@@ -27,6 +27,11 @@ typedef Tile<64, 64, 64, 2, 2> TileSmall;      // wave tile 32 x 32: small probl
 
 constexpr float kUnitScale = 1024.f;           // scale of orthonormal / unit-column factors in fp16
 
+OD_DEV bool pred_on(const Pred& p, int z) {
+  if (p.scal == nullptr) return true;
+  return (p.scal[z * kScalPerMat + p.slot] > p.thr) == (p.want != 0);
+}
+
 OD_DEV int split_begin(int K, int splits, int KT, int s, int* kend) {
   int per = ((K + splits - 1) / splits + KT - 1) / KT * KT;
   int kb = s * per;
@@ -226,8 +231,9 @@ __global__ __launch_bounds__(T::THREADS, (min_waves_per_simd<T, PF>())) void k_b
 // ------------------------------------------------------------------------------------
 // deterministic second stage of the split contractions
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_reduce(WsArr part, int splits, int64_t count, WsArr out) {
+__global__ __launch_bounds__(256) void k_reduce(WsArr part, int splits, int64_t count, WsArr out, Pred pred) {
   const int z = blockIdx.y;
+  if (!pred_on(pred, z)) return;
   const float* src = part.base + (int64_t)z * part.stride;
   float* dst = out.base + (int64_t)z * out.stride;
   const int64_t n4 = count / 4;
@@ -320,8 +326,9 @@ __global__ __launch_bounds__(T::THREADS) void k_gram(int rows, int r, WsArr a, W
 constexpr float kPhiScale = 8192.f;
 template <class T, class Num, bool DEEP, bool CORR>
 __global__ __launch_bounds__(T::THREADS) void k_apply(int rows, int r, WsArr a, WsArr w, HalfArr wh, WsArr out, MatPtrs ptrs,
-                                                      int to_q, HalfArr hn, HalfArr ht) {
+                                                      int to_q, HalfArr hn, HalfArr ht, Pred pred) {
   extern __shared__ __align__(16) char lds[];
+  if (!pred_on(pred, blockIdx.z)) return;
   const int tiles_n = (r + T::NT - 1) / T::NT;
   // the column tiles of one row panel of A share an XCD's L2
   const int bid = tiles_n > 1 ? xcd_contiguous(blockIdx.x, gridDim.x) : blockIdx.x;
@@ -559,6 +566,7 @@ struct SgemmArgs {
   int nq;
   int Mc, Nc, Kc;
   float alpha, beta;
+  Pred pred;
 };
 
 template <class D> OD_DEV constexpr bool DirA_is_kc() { return false; }
@@ -578,6 +586,7 @@ OD_DEV void sgemm_tile(const SgemmArgs& g, int bx, int bz, char* lds) {
   const int tiles_n = (g.Nc + T::NT - 1) / T::NT;
   const int tn = bx % tiles_n, tm = bx / tiles_n;
   const int q = bz % g.nq, z = bz / g.nq;
+  if (!pred_on(g.pred, z)) return;      // uniform over the workgroup: nobody reaches a barrier
   const int o = q * g.q_step;
   const float* ap = g.a.base + (int64_t)z * g.a.stride;
   const float* bp = g.b.base + (int64_t)z * g.b.stride;
@@ -616,7 +625,6 @@ __global__ __launch_bounds__(T::THREADS) void k_sgemm_pair(SgemmArgs g1, SgemmAr
 
 
 constexpr int kLeaf = kCholMax;   // diagonal block of the blocked factorisation
-constexpr float kMaxGramDeviation = 0.1f;   // largest |E| entry the first-order second pass accepts
 
 // ------------------------------------------------------------------------------------
 // Second CholeskyQR pass as a first-order correction.  After the first pass the Gram matrix
@@ -624,7 +632,7 @@ constexpr float kMaxGramDeviation = 0.1f;   // largest |E| entry the first-order
 // triangle + half the diagonal, and the inverse factor I - Phi(E) + O(E^2).  Writes
 // T2 = I + Phi(E), W2 = I - Phi(E) and the largest |E| entry (scal[mat][scal_slot]).
 // ------------------------------------------------------------------------------------
-__global__ __launch_bounds__(256) void k_corr(int r, WsArr part, int splits, WsArr t2, WsArr w2, HalfArr phit, float* scal,
+__global__ __launch_bounds__(256) void k_corr(int r, WsArr part, int splits, WsArr t1, WsArr t2, WsArr w2, HalfArr phit, float* scal,
                                               int scal_slot, int* info, int info_slot) {
   const int z = blockIdx.y;
   const float* src = part.base + (int64_t)z * part.stride;
@@ -681,14 +689,40 @@ __global__ __launch_bounds__(256) void k_corr(int r, WsArr part, int splits, WsA
     // than full column rank, which the Cholesky pivots alone do not always show.
     if (v > kMaxGramDeviation) atomicCAS(&info[z * kInfoPerMat + info_slot], 0, r);
   }
+  // Numerical rank: the diagonal of the first pass's triangular factor spans the factor's
+  // condition number from below.  Beyond about 1 / sqrt(rounding of the Gram matrix) the small
+  // pivots are rounding noise - CholeskyQR would return an orthonormal basis of that noise -
+  // so such a matrix is reported as rank deficient whatever deviation the noise happened to leave.
+  if (blockIdx.x == 0) {
+    const float* t = t1.base + (int64_t)z * t1.stride;
+    float lo = 3.0e38f, hi = 0.f;
+    for (int i = threadIdx.x; i < r; i += 256) {
+      const float d = t[(int64_t)i * r + i];
+      lo = fminf(lo, d == d ? d : 0.f);
+      hi = fmaxf(hi, d);
+    }
+    __shared__ float rlo[256], rhi[256];
+    rlo[threadIdx.x] = lo;
+    rhi[threadIdx.x] = hi;
+    __syncthreads();
+    for (int w = 128; w > 0; w >>= 1) {
+      if ((int)threadIdx.x < w) {
+        rlo[threadIdx.x] = fminf(rlo[threadIdx.x], rlo[threadIdx.x + w]);
+        rhi[threadIdx.x] = fmaxf(rhi[threadIdx.x], rhi[threadIdx.x + w]);
+      }
+      __syncthreads();
+    }
+    if (threadIdx.x == 0 && !(rlo[0] > kMinPivotRatio * rhi[0])) atomicCAS(&info[z * kInfoPerMat + info_slot], 0, r);
+  }
 }
 
 // ------------------------------------------------------------------------------------
 // small helpers
 // ------------------------------------------------------------------------------------
 // zero the r x r matrices of two per-matrix workspace arrays, all matrices in one launch
-__global__ __launch_bounds__(256) void k_zero_pair(WsArr a, WsArr b, int64_t count) {
+__global__ __launch_bounds__(256) void k_zero_pair(WsArr a, WsArr b, int64_t count, Pred pred) {
   const int z = blockIdx.y;
+  if (!pred_on(pred, z)) return;
   f32x4* pa = reinterpret_cast<f32x4*>(a.base + (int64_t)z * a.stride);
   f32x4* pb = reinterpret_cast<f32x4*>(b.base + (int64_t)z * b.stride);
   const f32x4 zero = {0.f, 0.f, 0.f, 0.f};
@@ -786,8 +820,13 @@ __global__ __launch_bounds__(256) void k_colnorm_apply(int n, int r, WsArr rr, W
 // The products are computed transposed (tile rows = columns j of the matrix) so that each
 // lane owns 4 consecutive j of one row i and moves M, G, X with vector accesses.
 // ------------------------------------------------------------------------------------
+OD_DEV bool matrix_flagged(const int* info, int z) {
+  const int* w = info + z * kInfoPerMat;
+  return (w[0] | w[1] | w[2]) != 0;
+}
+
 template <class T, class Num, bool XBF, bool GBF>
-__global__ __launch_bounds__(T::THREADS) void k_efx(ClassDims d, MatPtrs ptrs, const float* scal, WsArr p, WsArr rr,
+__global__ __launch_bounds__(T::THREADS) void k_efx(ClassDims d, MatPtrs ptrs, const float* scal, const int* info, WsArr p, WsArr rr,
                                                     float a_coef, float b_coef, float lr) {
   extern __shared__ __align__(16) char lds[];
   const int tiles_i = (d.m + T::NT - 1) / T::NT;
@@ -804,6 +843,10 @@ __global__ __launch_bounds__(T::THREADS) void k_efx(ClassDims d, MatPtrs ptrs, c
   gemm_mainloop<T, Num, KC, SrcF32, KC, SrcF32>(sr, sp, tj * T::MT, ti * T::NT, 0, d.r, s_r, s_u, lds, acc_r);
   gemm_mainloop<T, Num, KC, SrcF32, KC, SrcF32>(sq, sp, tj * T::MT, ti * T::NT, 0, d.r, s_u, s_u, lds, acc_q);
   const float cr = b_coef / (s_r * s_u), cq = lr / (s_u * s_u);
+  if (matrix_flagged(info, z)) {        // unspecified factors (possibly NaN) never reach X and M
+    zero_acc<T>(acc_r);
+    zero_acc<T>(acc_q);
+  }
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int wm = wave / T::WN, wn = wave % T::WN;
@@ -882,7 +925,7 @@ OD_DEV void st_stream(V* p, V v) {
 }
 
 template <bool XBF, bool GBF, bool STREAM>
-__global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, const float* scal, HalfArr ph, HalfArr rh,
+__global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, const float* scal, const int* info, HalfArr ph, HalfArr rh,
                                                HalfArr qh, float a_coef, float b_coef, float lr) {
   constexpr int TJ = 128, TI = 128, KT = 32, PITCH = KT * 2 + 16, PLANE = 128 * PITCH, BUF = 3 * PLANE;
   extern __shared__ __align__(16) char lds[];
@@ -965,6 +1008,12 @@ __global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, con
   constexpr int GE = GBF ? 2 : 4, XE = XBF ? 2 : 4;
   const float s_r = r_scale(d, scal, z);
   const float cr = b_coef / (s_r * kUnitScale), cq = lr / (kUnitScale * kUnitScale);
+  if (matrix_flagged(info, z)) {        // unspecified factors (possibly NaN) never reach X and M
+#pragma unroll
+    for (int f = 0; f < 2; ++f)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { acc_r[f][v] = 0.f; acc_q[f][v] = 0.f; }
+  }
 #pragma unroll
   for (int hv = 0; hv < 2; ++hv) {
     f32x2 mv[8], gv[8], xv[8];
@@ -1130,12 +1179,12 @@ hipError_t launch_back(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const
   return d.g_bf16 ? back_g<SrcBF16>(d, ptrs, prec, scal, p, part, splits, pht, st) : back_g<SrcF32>(d, ptrs, prec, scal, p, part, splits, pht, st);
 }
 
-hipError_t launch_reduce(int nb, WsArr part, int splits, int64_t count, WsArr out, hipStream_t st) {
+hipError_t launch_reduce(int nb, WsArr part, int splits, int64_t count, WsArr out, hipStream_t st, Pred pred) {
   int64_t n4 = count / 4;
   int blocks = (int)((n4 + 255) / 256);
   if (blocks > 2048) blocks = 2048;
   if (blocks < 1) blocks = 1;
-  hipLaunchKernelGGL(k_reduce, dim3(blocks, nb), dim3(256), 0, st, part, splits, count, out);
+  hipLaunchKernelGGL(k_reduce, dim3(blocks, nb), dim3(256), 0, st, part, splits, count, out, pred);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -1171,34 +1220,34 @@ hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits,
 }
 
 template <class T, class Num, bool DEEP, bool CORR>
-static hipError_t apply_tt(int nb, int rows, int r, WsArr a, WsArr w, HalfArr wh, WsArr out, const MatPtrs* ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
+static hipError_t apply_tt(int nb, int rows, int r, WsArr a, WsArr w, HalfArr wh, WsArr out, const MatPtrs* ptrs, HalfArr hn, HalfArr ht, hipStream_t st, Pred pred) {
   constexpr int lds = T::template lds_bytes<Num>();
   hipError_t e = allow_lds(k_apply<T, Num, DEEP, CORR>, lds);
   if (e != hipSuccess) return e;
   MatPtrs none = {};
   dim3 grid(((rows + T::MT - 1) / T::MT) * ((r + T::NT - 1) / T::NT), 1, nb);
-  hipLaunchKernelGGL((k_apply<T, Num, DEEP, CORR>), grid, dim3(T::THREADS), lds, st, rows, r, a, w, wh, out, ptrs ? *ptrs : none, ptrs ? 1 : 0, hn, ht);
+  hipLaunchKernelGGL((k_apply<T, Num, DEEP, CORR>), grid, dim3(T::THREADS), lds, st, rows, r, a, w, wh, out, ptrs ? *ptrs : none, ptrs ? 1 : 0, hn, ht, pred);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
 template <class Num, bool CORR>
-static hipError_t apply_t(int nb, int rows, int r, WsArr a, WsArr w, HalfArr wh, WsArr out, const MatPtrs* ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
+static hipError_t apply_t(int nb, int rows, int r, WsArr a, WsArr w, HalfArr wh, WsArr out, const MatPtrs* ptrs, HalfArr hn, HalfArr ht, hipStream_t st, Pred pred) {
   const int big = ((rows + 127) / 128) * ((r + 127) / 128) * nb;
-  if (big < 512) return apply_tt<TileSmall, Num, true, CORR>(nb, rows, r, a, w, wh, out, ptrs, hn, ht, st);
+  if (big < 512) return apply_tt<TileSmall, Num, true, CORR>(nb, rows, r, a, w, wh, out, ptrs, hn, ht, st, pred);
   // 128 columns per tile: the loop of a column tile ends at its last row of W (upper triangular),
   // so narrower tiles skip more of the zero half than 256-column ones would (measured -10 %)
   // one operand part leaves LDS room for 64-deep steps at two workgroups per CU (measured -13 to
   // -23 %); with two parts the deeper tile halves the occupancy and loses
-  if constexpr (Num::PARTS == 1) return apply_tt<TileSquareDeepK, Num, false, CORR>(nb, rows, r, a, w, wh, out, ptrs, hn, ht, st);
-  else return apply_tt<TileSquare, Num, false, CORR>(nb, rows, r, a, w, wh, out, ptrs, hn, ht, st);
+  if constexpr (Num::PARTS == 1) return apply_tt<TileSquareDeepK, Num, false, CORR>(nb, rows, r, a, w, wh, out, ptrs, hn, ht, st, pred);
+  else return apply_tt<TileSquare, Num, false, CORR>(nb, rows, r, a, w, wh, out, ptrs, hn, ht, st, pred);
 }
-hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs, HalfArr hn, HalfArr ht, int exact, hipStream_t st) {
+hipError_t launch_apply(int nb, int rows, int r, WsArr a, WsArr w, WsArr out, const MatPtrs* q_ptrs, HalfArr hn, HalfArr ht, int exact, hipStream_t st, Pred pred) {
   const HalfArr none{nullptr, 0};
-  return exact ? apply_t<NumBF<3>, false>(nb, rows, r, a, w, none, out, q_ptrs, hn, ht, st) : apply_t<NumBF<2>, false>(nb, rows, r, a, w, none, out, q_ptrs, hn, ht, st);
+  return exact ? apply_t<NumBF<3>, false>(nb, rows, r, a, w, none, out, q_ptrs, hn, ht, st, pred) : apply_t<NumBF<2>, false>(nb, rows, r, a, w, none, out, q_ptrs, hn, ht, st, pred);
 }
-hipError_t launch_apply_correction(int nb, int rows, int r, WsArr a, HalfArr phit, WsArr out, const MatPtrs* q_ptrs, HalfArr hn, HalfArr ht, hipStream_t st) {
+hipError_t launch_apply_correction(int nb, int rows, int r, WsArr a, HalfArr phit, WsArr out, const MatPtrs* q_ptrs, HalfArr hn, HalfArr ht, hipStream_t st, Pred pred) {
   const WsArr unused{nullptr, 0};
-  return apply_t<NumF16, true>(nb, rows, r, a, unused, phit, out, q_ptrs, hn, ht, st);
+  return apply_t<NumF16, true>(nb, rows, r, a, unused, phit, out, q_ptrs, hn, ht, st, pred);
 }
 
 template <class T, class Num, class DirA>
@@ -1248,14 +1297,16 @@ static hipError_t sgemm_pair(int nb, const SgemmArgs& g1, const SgemmArgs& g2, h
 }
 
 hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp, int* info, int info_slot,
-                          hipStream_t st) {
+                          hipStream_t st, Pred pred, int splits, int64_t split_stride) {
   hipError_t e = allow_lds(k_chol256, kCholLds);
   if (e != hipSuccess) return e;
   const int nblk = (r + kLeaf - 1) / kLeaf;
   CholArgs ca = {};
   ca.t = t; ca.w = w; ca.r = r; ca.info = info; ca.info_slot = info_slot;
   ca.src = gram; ca.splits = 1; ca.split_stride = 0;
+  ca.pred = pred;
   if (nblk == 1) {
+    ca.splits = splits; ca.split_stride = split_stride;
     ca.blk = 0;
     hipLaunchKernelGGL(k_chol256, dim3(nb), dim3(kCholThreads), kCholLds, st, ca);
     OD_CHECK_LAUNCH();
@@ -1266,7 +1317,7 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp
     const int64_t count = (int64_t)r * r;          // a multiple of 64
     int blocks = (int)((count / 4 + 255) / 256);
     if (blocks > 256) blocks = 256;
-    hipLaunchKernelGGL(k_zero_pair, dim3(blocks, nb), dim3(256), 0, st, t, w, count);
+    hipLaunchKernelGGL(k_zero_pair, dim3(blocks, nb), dim3(256), 0, st, t, w, count, pred);
     OD_CHECK_LAUNCH();
   }
   // Step p: factor the diagonal block (T_pp, W_pp), then two launches of two independent
@@ -1283,6 +1334,7 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp
     const int o = p * kLeaf, o1 = (p + 1) * kLeaf, rest = r > o1 ? r - o1 : 0;
     const int bw = r - o < kLeaf ? r - o : kLeaf;       // width of block column p
     SgemmArgs panel = {}, prod = {}, trail = {}, wcol = {};
+    panel.pred = prod.pred = trail.pred = wcol.pred = pred;
     panel.r = prod.r = trail.r = wcol.r = r;
     panel.nq = prod.nq = trail.nq = wcol.nq = 1;
     if (rest > 0) {
@@ -1323,12 +1375,12 @@ hipError_t launch_small_first_pass(int nb, int rows, int r, WsArr a0, WsArr gram
   return hipSuccess;
 }
 
-hipError_t launch_corr(int nb, int r, WsArr part, int splits, WsArr t2, WsArr w2, HalfArr phit, float* scal, int scal_slot,
+hipError_t launch_corr(int nb, int r, WsArr part, int splits, WsArr t1, WsArr t2, WsArr w2, HalfArr phit, float* scal, int scal_slot,
                        int* info, int info_slot, hipStream_t st) {
   int64_t count = (int64_t)r * r;
   int blocks = (int)((count / 4 + 255) / 256);
   if (blocks > 1024) blocks = 1024;
-  hipLaunchKernelGGL(k_corr, dim3(blocks, nb), dim3(256), 0, st, r, part, splits, t2, w2, phit, scal, scal_slot, info, info_slot);
+  hipLaunchKernelGGL(k_corr, dim3(blocks, nb), dim3(256), 0, st, r, part, splits, t1, t2, w2, phit, scal, scal_slot, info, info_slot);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -1354,56 +1406,56 @@ hipError_t launch_colnorm(int nb, int n, int r, WsArr rr, const MatPtrs& ptrs, W
 }
 
 template <class T, class Num, bool XBF, bool GBF>
-static hipError_t efx_tt(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr p, WsArr rr, float a_coef,
+static hipError_t efx_tt(const ClassDims& d, const MatPtrs& ptrs, const float* scal, const int* info, WsArr p, WsArr rr, float a_coef,
                          float b_coef, float lr, hipStream_t st) {
   constexpr int lds = T::template lds_bytes<Num>();
   hipError_t e = allow_lds(k_efx<T, Num, XBF, GBF>, lds);
   if (e != hipSuccess) return e;
   dim3 grid(((d.m + T::NT - 1) / T::NT) * ((d.n + T::MT - 1) / T::MT), 1, d.nb);
-  launch_timed(k_efx<T, Num, XBF, GBF>, grid, dim3(T::THREADS), lds, st, d, ptrs, scal, p, rr, a_coef, b_coef, lr);
+  launch_timed(k_efx<T, Num, XBF, GBF>, grid, dim3(T::THREADS), lds, st, d, ptrs, scal, info, p, rr, a_coef, b_coef, lr);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
 template <class Num, bool XBF, bool GBF>
-static hipError_t efx_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr p, WsArr rr, float a_coef,
+static hipError_t efx_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, const int* info, WsArr p, WsArr rr, float a_coef,
                         float b_coef, float lr, hipStream_t st) {
   // small problems: more, smaller tiles (the kernel is a few microseconds of latency per tile)
   if ((int64_t)((d.m + 127) / 128) * ((d.n + 127) / 128) * d.nb < 256)
-    return efx_tt<TileSmall, Num, XBF, GBF>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st);
-  return efx_tt<TileSquare, Num, XBF, GBF>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st);
+    return efx_tt<TileSmall, Num, XBF, GBF>(d, ptrs, scal, info, p, rr, a_coef, b_coef, lr, st);
+  return efx_tt<TileSquare, Num, XBF, GBF>(d, ptrs, scal, info, p, rr, a_coef, b_coef, lr, st);
 }
 template <class Num>
-static hipError_t efx_n(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr p, WsArr rr, float a_coef,
+static hipError_t efx_n(const ClassDims& d, const MatPtrs& ptrs, const float* scal, const int* info, WsArr p, WsArr rr, float a_coef,
                         float b_coef, float lr, hipStream_t st) {
-  if (d.x_bf16) return d.g_bf16 ? efx_t<Num, true, true>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st)
-                                : efx_t<Num, true, false>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st);
-  return d.g_bf16 ? efx_t<Num, false, true>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st)
-                  : efx_t<Num, false, false>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st);
+  if (d.x_bf16) return d.g_bf16 ? efx_t<Num, true, true>(d, ptrs, scal, info, p, rr, a_coef, b_coef, lr, st)
+                                : efx_t<Num, true, false>(d, ptrs, scal, info, p, rr, a_coef, b_coef, lr, st);
+  return d.g_bf16 ? efx_t<Num, false, true>(d, ptrs, scal, info, p, rr, a_coef, b_coef, lr, st)
+                  : efx_t<Num, false, false>(d, ptrs, scal, info, p, rr, a_coef, b_coef, lr, st);
 }
 template <bool XBF, bool GBF>
-static hipError_t efx_h_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, HalfArr ph, HalfArr rh, HalfArr qh,
+static hipError_t efx_h_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, const int* info, HalfArr ph, HalfArr rh, HalfArr qh,
                           float a_coef, float b_coef, float lr, hipStream_t st) {
   constexpr int lds = 2 * 3 * 128 * 80;
   dim3 grid(((d.m + 127) / 128) * ((d.n + 127) / 128), 1, d.nb);
   // also for sets far beyond the Infinity Cache at any rank: nontemporal stores leave no dirty
   // lines behind for the next kernel to wait on (measured on 8192 x 8192: the step is 2-7 % faster)
-  if (d.r > 256 || (int64_t)d.m * d.n * d.nb >= ((int64_t)48 << 20)) launch_timed(k_efx_h<XBF, GBF, true>, grid, dim3(512), lds, st, d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr);
-  else launch_timed(k_efx_h<XBF, GBF, false>, grid, dim3(512), lds, st, d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr);
+  if (d.r > 256 || (int64_t)d.m * d.n * d.nb >= ((int64_t)48 << 20)) launch_timed(k_efx_h<XBF, GBF, true>, grid, dim3(512), lds, st, d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr);
+  else launch_timed(k_efx_h<XBF, GBF, false>, grid, dim3(512), lds, st, d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
-hipError_t launch_efx_h(const ClassDims& d, const MatPtrs& ptrs, const float* scal, HalfArr ph, HalfArr rh, HalfArr qh,
-                        float a_coef, float b_coef, float lr, hipStream_t st) {
-  if (d.x_bf16) return d.g_bf16 ? efx_h_t<true, true>(d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr, st)
-                                : efx_h_t<true, false>(d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr, st);
-  return d.g_bf16 ? efx_h_t<false, true>(d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr, st)
-                  : efx_h_t<false, false>(d, ptrs, scal, ph, rh, qh, a_coef, b_coef, lr, st);
+hipError_t launch_efx_h(const ClassDims& d, const MatPtrs& ptrs, const float* scal, const int* info, HalfArr ph, HalfArr rh,
+                        HalfArr qh, float a_coef, float b_coef, float lr, hipStream_t st) {
+  if (d.x_bf16) return d.g_bf16 ? efx_h_t<true, true>(d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr, st)
+                                : efx_h_t<true, false>(d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr, st);
+  return d.g_bf16 ? efx_h_t<false, true>(d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr, st)
+                  : efx_h_t<false, false>(d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr, st);
 }
 
-hipError_t launch_efx(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p, WsArr rr,
+hipError_t launch_efx(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, const int* info, WsArr p, WsArr rr,
                       float a_coef, float b_coef, float lr, hipStream_t st) {
-  return prec == PREC_BF3 ? efx_n<NumBF<3>>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st)
-                          : efx_n<NumF16>(d, ptrs, scal, p, rr, a_coef, b_coef, lr, st);
+  return prec == PREC_BF3 ? efx_n<NumBF<3>>(d, ptrs, scal, info, p, rr, a_coef, b_coef, lr, st)
+                          : efx_n<NumF16>(d, ptrs, scal, info, p, rr, a_coef, b_coef, lr, st);
 }
 
 }  // namespace od

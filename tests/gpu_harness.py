@@ -8,18 +8,7 @@ import numpy as np
 
 from oracle.orthdion_oracle import OrthDionOracle, bf16_bits_to_f64, rel_fro
 from paper_2605_16341_amd import binding, synth
-
-
-def to_device(arr: np.ndarray, torch, device="cuda:0"):
-    if arr.dtype == np.uint16:
-        return torch.from_numpy(arr.view(np.int16).copy()).to(device).view(torch.bfloat16)
-    return torch.from_numpy(np.ascontiguousarray(arr)).to(device)
-
-
-def to_host(t, torch) -> np.ndarray:
-    if t.dtype == torch.bfloat16:
-        return t.view(torch.int16).cpu().numpy().view(np.uint16)
-    return t.cpu().numpy()
+from paper_2605_16341_amd.device_inputs import to_device, to_host
 
 
 class GpuRun:
@@ -63,6 +52,17 @@ def bf16_ulp_distance(a_bits: np.ndarray, b_bits: np.ndarray) -> np.ndarray:
     return np.abs(key(a_bits) - key(b_bits))
 
 
+def bf16_gap_beyond(a_bits: np.ndarray, b_bits: np.ndarray, spacings: float, slack: float) -> float:
+    """Fraction of entries whose two bf16 values lie further apart than `spacings` bf16
+    spacings (2^-7 of the larger magnitude) plus `slack`.  The distance in ulps alone says
+    little where |x| is tiny: there one spacing is far below the update itself, so two correct
+    updates that differ within the direction's tolerance are many ulps apart; `slack` is that
+    tolerance times the largest update entry."""
+    a, b = bf16_bits_to_f64(a_bits), bf16_bits_to_f64(b_bits)
+    spacing = np.maximum(np.abs(a), np.abs(b)) * 2.0 ** -7
+    return float(np.mean(np.abs(a - b) > spacings * spacing + slack))
+
+
 def compare_step(gpu: Dict[str, np.ndarray], orc: Dict[str, np.ndarray], x_prev: np.ndarray, lr: float) -> Dict[str, float]:
     """Relative Frobenius errors of the GPU results against the oracle's.  The parameter is
     compared through the applied update (X_prev - X_new) / lr, because ||X_new - X_prev||
@@ -79,6 +79,8 @@ def compare_step(gpu: Dict[str, np.ndarray], orc: Dict[str, np.ndarray], x_prev:
         dist = bf16_ulp_distance(gpu["X"], orc["X_bits"])
         res["X_bits_mismatch"] = float(np.mean(dist != 0))
         res["X_max_ulp"] = float(dist.max())
+        slack = 2e-2 * lr * float(np.max(np.abs(orc["D"])))
+        res["X_beyond_one_spacing"] = bf16_gap_beyond(gpu["X"], orc["X_bits"], 1.0, slack)
     else:
         res["update"] = rel_fro((x_as_f64(x_prev) - xg) / lr, orc["D"])
     return res

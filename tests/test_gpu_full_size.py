@@ -1,24 +1,37 @@
 """Parity at the benchmark's full sizes, in the launch configuration bench.py times.
 
-C2 (4096 x 4096, r = 256, 20 steps) is compared with the oracle in full.  For the larger
-matrix sets (C3, C4, C5 shapes; r up to 2048) a full fp64 oracle step would take minutes per
-matrix, so one matrix per distinct shape is stepped once and checked through
-  * properties that identify the result at any size: P^T P = I, Q^T Q = I (unit columns for
-    ColNorm), P (T2 T1) = B Q_prev with an upper-triangular positive-diagonal factor (the
-    thin QR factor is unique), Q (T2 T1) = R;
-  * outputs the oracle computes one by one: sampled rows of B Q_prev, sampled rows of
-    R = B^T P, and sampled rows of the new momentum and parameter from the oracle's own
-    error-feedback and update functions.
-Inputs are generated on the device with the bench's recipe and copied back only in samples.
+C2 (4096 x 4096, r = 256, 20 steps) is compared with the oracle free-running.  For the larger
+matrix sets one matrix per distinct (shape, rank, variant) takes one warm-up step on the GPU
+(so that the momentum is not zero and the warm-start factor is the method's own), its state is
+copied back, the GPU takes a second step and the oracle takes the same step from the copied
+state (teacher-forced `OrthDionOracle.step`).  Compared: P, R, Q, M in relative Frobenius norm
+(the configuration's 2e-2) and element by element (largest deviation against the largest
+entry), X as stored bf16 bits, plus the properties that hold at any size (orthonormal
+factors, positive upper-triangular factor).
+
+Oracle route: ranks up to 512 use the oracle's written-out Householder QR; ranks from 1024
+use its library-QR route (same unique factor, pinned against the written-out one in the CPU
+tests), because the written-out reflections alone take minutes per matrix there.  The QR
+variant of r = 2048 is also checked through sampled rows of the oracle's separate functions.
+Inputs are generated on the device with the bench's recipe.
 """
 import numpy as np
 import pytest
 
-from gpu_harness import bf16_ulp_distance, to_host
+from gpu_harness import bf16_gap_beyond, bf16_ulp_distance
 from oracle.orthdion_oracle import OrthDionOracle, bf16_bits_to_f64, f64_to_bf16_bits, rel_fro
 from paper_2605_16341_amd import binding, synth
+from paper_2605_16341_amd.device_inputs import device_gradients, device_state, to_host
 
 pytestmark = pytest.mark.gpu
+
+FRO_TOL = 2e-2          # the configuration's bar: bf16 parameters and gradients, fp32 state
+# One teacher-forced step is far inside that bar; these are about five times what was observed
+# over all cases below (Frobenius: at most 3.6e-4; largest element-wise deviation relative to
+# the largest entry of the oracle's array: at most 4.6e-4, printed per case).  The element-wise
+# bound is what a few badly wrong rows would fail while passing a Frobenius ratio.
+FRO_SEEN = 2e-3
+MAXABS_TOL = {"P": 2e-3, "R": 2e-3, "Q": 2e-3, "M": 2e-3}
 
 
 def test_config2_4096_rank256_twenty_steps_free_running():
@@ -27,105 +40,128 @@ def test_config2_4096_rank256_twenty_steps_free_running():
     assert res["D"] < 5e-3 and res["M"] < 1e-3
 
 
-def _sampled_check(w, index, variant, sample=48, seed=0):
+def _two_steps(w, index, variant):
+    """State after one warm-up step (host copies), then a second step on the GPU."""
     import torch
-    import bench
     dev = torch.device("cuda:0")
     m, n = w.shapes[index]
-    r = w.r
-    one = synth.Workload(w.name, (w.shapes[index],), r=r, x_dtype=w.x_dtype, mu=w.mu, lr=w.lr)
-    x, mom, q = bench.device_state(torch, one, 0, dev)
-    g0, g1 = bench.device_gradients(torch, one, 0, 2, dev)
-    opt = binding.OrthDion([(m, n)], r, x_dtype="bf16", variant=variant, mu=w.mu, lr=w.lr)
-    opt.step([x], [g0], [mom], [q])            # a first step so that M is not zero
+    one = synth.Workload(w.name, (w.shapes[index],), r=w.r, x_dtype=w.x_dtype, mu=w.mu, lr=w.lr)
+    x, mom, q = device_state(torch, one, 0, dev)
+    g0, g1 = device_gradients(torch, one, 0, 2, dev)
+    opt = binding.OrthDion([(m, n)], w.r, x_dtype="bf16", variant=variant, mu=w.mu, lr=w.lr)
+    opt.step([x], [g0], [mom], [q])
     torch.cuda.synchronize()
     assert opt.info() == [0]
-    x0, m0, q0 = x.clone(), mom.clone(), q.clone()
+    before = {"X": to_host(x, torch), "M": to_host(mom, torch), "Q": to_host(q, torch), "G": to_host(g1, torch)}
     opt.step([x], [g1], [mom], [q])
     torch.cuda.synchronize()
     assert opt.info() == [0]
     f = opt.debug_factors(0)
-    P, R = f["P"].double(), f["R"].double()
-    Qn = q.double()
-    eye = torch.eye(r, device=dev, dtype=torch.float64)
-    B = m0.double() + g1.double()
+    after = {"X": to_host(x, torch), "M": to_host(mom, torch), "Q": to_host(q, torch)}
+    for key in ("P", "R", "T_P1", "T_P2", "T_Q1", "T_Q2"):
+        after[key] = f[key].cpu().numpy()
+    opt.close()
+    del x, mom, q, g0, g1, f
+    torch.cuda.empty_cache()
+    return before, after
 
-    # --- properties.  The second CholeskyQR pass corrects the deviation E it measures with a
-    # Gram matrix of two-part bf16 operands (2^-17 relative rounding each): what it cannot see
-    # is that measurement's own rounding, a few 2^-18 per entry; the bound is for the largest of
-    # up to r^2 = 4M entries (observed: 3.2e-6 to 4.4e-6 at every benchmark shape).  With
-    # ColNorm the warm-start factor has unit but not orthogonal columns, B Q is worse conditioned,
-    # the deviation after the first pass is larger and its second-order remainder shows (1.6e-5
-    # at r = 1024).
-    ORTH_TOL = 1e-5 if variant == "qr" else 4e-5
-    assert float((P.T @ P - eye).abs().max()) < ORTH_TOL
-    t_p = f["T_P2"].double() @ f["T_P1"].double()
-    assert bool((torch.diagonal(t_p) > 0).all())
-    assert float(torch.tril(t_p, -1).abs().max()) <= 1e-6 * float(t_p.abs().max())
-    praw = B @ q0.double()
-    assert float(torch.linalg.norm(P @ t_p - praw) / torch.linalg.norm(praw)) < 2e-2
+
+def _properties(after, r, variant):
+    """What identifies the factors at any size (the thin QR factor with a positive diagonal is
+    unique).  The second CholeskyQR pass measures its deviation with a Gram matrix on split
+    half-precision operands; what it cannot see is that measurement's own rounding."""
+    tol = 1e-5 if variant == "qr" else 4e-5
+    eye = np.eye(r)
+    p = after["P"].astype(np.float64)
+    assert np.abs(p.T @ p - eye).max() < tol
+    t_p = after["T_P2"].astype(np.float64) @ after["T_P1"].astype(np.float64)
+    assert np.all(np.diag(t_p) > 0)
+    assert np.abs(np.tril(t_p, -1)).max() <= 1e-6 * np.abs(t_p).max()
+    qn = after["Q"].astype(np.float64)
+    rr = after["R"].astype(np.float64)
     if variant == "qr":
-        assert float((Qn.T @ Qn - eye).abs().max()) < ORTH_TOL
-        t_q = f["T_Q2"].double() @ f["T_Q1"].double()
-        assert bool((torch.diagonal(t_q) > 0).all())
-        assert float(torch.linalg.norm(Qn @ t_q - R) / torch.linalg.norm(R)) < 1e-4
+        assert np.abs(qn.T @ qn - eye).max() < tol
+        t_q = after["T_Q2"].astype(np.float64) @ after["T_Q1"].astype(np.float64)
+        assert np.all(np.diag(t_q) > 0)
+        assert rel_fro(qn @ t_q, rr) < 1e-4
     else:
-        assert float(((Qn * Qn).sum(0) - 1.0).abs().max()) < 1e-5
-        assert float(torch.linalg.norm(Qn * torch.linalg.norm(R, dim=0)[None, :] - R) / torch.linalg.norm(R)) < 1e-5
-    assert float(torch.linalg.norm(R - B.T @ P) / torch.linalg.norm(R)) < 2e-2
+        assert np.abs((qn * qn).sum(0) - 1.0).max() < 1e-5
+        assert rel_fro(qn * np.linalg.norm(rr, axis=0)[None, :], rr) < 1e-5
 
-    # --- sampled outputs against the oracle's functions
-    rng = np.random.default_rng(seed)
-    rows = np.sort(rng.choice(m, size=min(sample, m), replace=False))
-    cols = np.sort(rng.choice(n, size=min(sample, n), replace=False))
-    rows_t = torch.from_numpy(rows).to(dev)
-    cols_t = torch.from_numpy(cols).to(dev)
-    orc = OrthDionOracle(mu=w.mu, lr=w.lr, variant=variant, x_bf16=True)
-    b_rows = orc.buffer(m0[rows_t].cpu().numpy().astype(np.float64), bf16_bits_to_f64(to_host(g1[rows_t].contiguous(), torch)))
-    q0_np, p_np, r_np, q_np = (t.cpu().numpy().astype(np.float64) for t in (q0, f["P"], f["R"], q))
-    # P_raw rows: (B Q_prev)[rows] must equal (P T_P)[rows]
-    want = orc.project(b_rows, q0_np)
-    got = p_np[rows] @ t_p.cpu().numpy()
-    assert rel_fro(got, want) < 2e-2
-    # R rows: R[cols] = B[:, cols]^T P
-    b_cols = (m0[:, cols_t].double() + g1[:, cols_t].double()).cpu().numpy()
-    assert rel_fro(r_np[cols], orc.back_project(b_cols, p_np)) < 2e-2
-    # new momentum and parameter rows from the GPU's own factors
-    m_want = orc.error_feedback(b_rows, p_np[rows], r_np)
-    assert rel_fro(mom[rows_t].cpu().numpy(), m_want) < 1e-3
-    x_prev = bf16_bits_to_f64(to_host(x0[rows_t].contiguous(), torch))
-    x_want = f64_to_bf16_bits(orc.update(x_prev, p_np[rows], q_np))
-    dist = bf16_ulp_distance(to_host(x[rows_t].contiguous(), torch), x_want)
+
+def _teacher_forced(w, index, variant):
+    before, after = _two_steps(w, index, variant)
+    _properties(after, w.r, variant)
+    orc = OrthDionOracle(mu=w.mu, lr=w.lr, variant=variant, x_bf16=True,
+                         qr="library" if w.r >= 1024 else "householder")
+    o = orc.step(before["X"], before["G"], before["M"].astype(np.float64), before["Q"].astype(np.float64))
+    seen = {}
+    for key in ("P", "R", "Q", "M"):
+        fro = rel_fro(after[key], o[key])
+        worst = float(np.abs(after[key].astype(np.float64) - o[key]).max() / np.abs(o[key]).max())
+        seen[key] = (fro, worst)
+        assert fro <= FRO_TOL and fro <= FRO_SEEN, (w.name, w.shapes[index], w.r, variant, key, fro)
+        assert worst <= MAXABS_TOL[key], (w.name, w.shapes[index], w.r, variant, key, worst)
+    mism = float(np.mean(after["X"] != o["X_bits"]))
+    beyond = bf16_gap_beyond(after["X"], o["X_bits"], 1.0, FRO_TOL * w.lr * float(np.abs(o["D"]).max()))
+    print(f"\n{w.name} {w.shapes[index]} r={w.r} {variant}: "
+          + " ".join(f"{k}: fro {a:.2e} max {b:.2e};" for k, (a, b) in seen.items())
+          + f" X bits differ {mism:.4f}, beyond one spacing {beyond:.2e}")
+    assert mism <= 0.01 and beyond == 0.0        # observed: at most 0.24 % of the entries round the other way
+
+
+@pytest.mark.parametrize("index", [0, 1, 2, 3])
+def test_config3_each_shape_rank512_oracle_step(index):
+    _teacher_forced(synth.WORKLOADS["C3"], index, "qr")
+
+
+@pytest.mark.parametrize("index", [0, 1, 2, 4])
+def test_config4_each_shape_rank1024_oracle_step(index):
+    _teacher_forced(synth.WORKLOADS["C4"], index, "qr")
+
+
+@pytest.mark.parametrize("r,variant", [(16, "qr"), (16, "colnorm"), (64, "qr"), (64, "colnorm"), (256, "qr"),
+                                       (256, "colnorm"), (1024, "qr"), (1024, "colnorm"), (2048, "qr"), (2048, "colnorm")])
+def test_config5_rank_sweep_oracle_step(r, variant):
+    _teacher_forced(synth.WORKLOADS[f"C5-r{r}"], 0, variant)
+
+
+def test_config5_rank2048_qr_properties_and_sampled_rows():
+    """The largest rank once more through the oracle's separate functions on sampled rows and
+    columns (buffer, projection, back-projection, error feedback, update)."""
+    w = synth.WORKLOADS["C5-r2048"]
+    m, n = w.shapes[0]
+    before, after = _two_steps(w, 0, "qr")
+    _properties(after, w.r, "qr")
+    rng = np.random.default_rng(0)
+    rows = np.sort(rng.choice(m, size=48, replace=False))
+    cols = np.sort(rng.choice(n, size=48, replace=False))
+    orc = OrthDionOracle(mu=w.mu, lr=w.lr, variant="qr", x_bf16=True)
+    g = bf16_bits_to_f64(before["G"])
+    m0 = before["M"].astype(np.float64)
+    b_rows = orc.buffer(m0[rows], g[rows])
+    p, rr, qn = (after[k].astype(np.float64) for k in ("P", "R", "Q"))
+    t_p = after["T_P2"].astype(np.float64) @ after["T_P1"].astype(np.float64)
+    assert rel_fro(p[rows] @ t_p, orc.project(b_rows, before["Q"].astype(np.float64))) < FRO_TOL
+    b_cols = orc.buffer(m0[:, cols], g[:, cols])
+    assert rel_fro(rr[cols], orc.back_project(b_cols, p)) < FRO_TOL
+    assert rel_fro(after["M"][rows], orc.error_feedback(b_rows, p[rows], rr)) < 1e-3
+    x_want = f64_to_bf16_bits(orc.update(bf16_bits_to_f64(before["X"][rows]), p[rows], qn))
+    dist = bf16_ulp_distance(after["X"][rows], x_want)
     assert np.mean(dist != 0) < 0.02 and np.mean(dist > 1) < 1e-3
-
-
-@pytest.mark.parametrize("name,index", [("C3", 0), ("C3", 1), ("C3", 2), ("C3", 3)])
-def test_config3_shapes_rank512(name, index):
-    _sampled_check(synth.WORKLOADS[name], index, "qr")
-
-
-@pytest.mark.parametrize("index", [0, 2, 4])
-def test_config4_shapes_rank1024(index):
-    _sampled_check(synth.WORKLOADS["C4"], index, "qr")
-
-
-@pytest.mark.parametrize("r,variant", [(16, "qr"), (64, "colnorm"), (256, "qr"), (1024, "colnorm"), (2048, "qr")])
-def test_config5_rank_sweep(r, variant):
-    _sampled_check(synth.WORKLOADS[f"C5-r{r}"], 0, variant)
 
 
 def test_whole_config3_set_runs_in_one_call():
     """All 96 matrices (4 shape classes, 3 launch batches each) in one handle: every matrix
     gets orthonormal factors and a finite state."""
     import torch
-    import bench
     dev = torch.device("cuda:0")
     w = synth.WORKLOADS["C3"]
     X, M, Q, G = [], [], [], []
     for i in range(len(w.shapes)):
-        x, mom, q = bench.device_state(torch, w, i, dev)
+        x, mom, q = device_state(torch, w, i, dev)
         X.append(x); M.append(mom); Q.append(q)
-        G.append(bench.device_gradients(torch, w, i, 1, dev)[0])
+        G.append(device_gradients(torch, w, i, 1, dev)[0])
     opt = binding.OrthDion(w.shapes, w.r, x_dtype="bf16", mu=w.mu, lr=w.lr)
     opt.step(X, G, M, Q)
     torch.cuda.synchronize()

@@ -18,6 +18,10 @@ from paper_2605_16341_amd import binding, synth
 pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
+# Fraction of bf16 parameter entries whose stored bits may differ from the oracle's after step
+# t (free-running): both sides round an update of about half a spacing, so some entries land
+# on different sides; the bound is about twice what was observed (printed by the tests).
+X_MISMATCH_PER_STEP, X_MISMATCH_BASE = 0.02, 0.02
 
 
 def _free_running(w, variant="qr", ef="dion", precision="auto", steps=None, check_every=1, tol=None):
@@ -43,7 +47,8 @@ def _free_running(w, variant="qr", ef="dion", precision="auto", steps=None, chec
                 for key in ("M", "Q", "P", "R", "D"):
                     assert res[key] <= tol, (w.name, "step", t, "matrix", i, key, res[key])
                 if w.x_dtype == "bf16":
-                    assert res["X_bits_mismatch"] <= 0.02 * (t + 1) + 0.02, (t, res)
+                    print(f"\n{w.name} step {t} matrix {i}: X bits differ {res['X_bits_mismatch']:.5f}")
+                    assert res["X_bits_mismatch"] <= X_MISMATCH_PER_STEP * (t + 1) + X_MISMATCH_BASE, (t, res)
                     xg, xo = gpu.fetch(i, False)["X"], o["X_bits"]
                     gap = np.abs(bf16_bits_to_f64(xg) - bf16_bits_to_f64(xo))
                     # rounding decisions may differ by one spacing per step taken; the update
@@ -113,7 +118,12 @@ def test_teacher_forced_single_steps_bf16():
         res = compare_step(gpu.fetch(0), o, before["X"], w.lr)
         for key in ("M", "Q", "P", "R", "D"):
             assert res[key] <= 2e-3, (t, key, res[key])          # one step is ten times inside the bar
-        assert res["X_bits_mismatch"] <= 0.02 and res["X_max_ulp"] <= 1 or res["X_bits_mismatch"] <= 0.02
+        print(f"\nteacher-forced step {t}: X bits differ {res['X_bits_mismatch']:.5f}, beyond one spacing "
+              f"{res['X_beyond_one_spacing']:.2e}")
+        # observed: 0.4 % of the entries round to the other neighbour; none is further away than
+        # one spacing plus the direction's tolerance
+        assert res["X_bits_mismatch"] <= 0.01
+        assert res["X_beyond_one_spacing"] == 0.0
 
 
 def test_leading_dimensions_larger_than_n():
@@ -189,12 +199,20 @@ def test_rank_deficient_inputs_raise_the_info_word_and_finish():
     gpu = GpuRun(w.shapes, r, "bf16", [st])
     info = gpu.step([zero])                       # B = 0: B Q has rank 0
     assert info[0] > 0
+    # a flagged matrix keeps its parameter, and its momentum becomes a (M + G) = 0 here: the
+    # unspecified factors never reach the caller's state
+    after = gpu.fetch(0, with_factors=False)
+    assert after["X"].tobytes() == st.X.tobytes()
+    assert not np.any(after["M"])
     # rank(B) = 4 < r: the left factor breaks down at column 5
     rng = np.random.default_rng(0)
     low = (rng.standard_normal((m, 4)) @ rng.standard_normal((4, n))).astype(np.float32)
     gpu = GpuRun(w.shapes, r, "bf16", [st])
     info = gpu.step([synth.f32_to_bf16_bits(low)])
     assert info[0] != 0
+    after = gpu.fetch(0, with_factors=False)
+    assert after["X"].tobytes() == st.X.tobytes()
+    assert np.array_equal(after["M"], bf16_bits_to_f64(synth.f32_to_bf16_bits(low)).astype(np.float32))
     # ColNorm with a gradient whose back-projection has a zero column cannot happen with a
     # full-rank left factor; NaN input must flag, not hang
     bad = low.copy(); bad[3, 7] = np.nan
@@ -202,6 +220,57 @@ def test_rank_deficient_inputs_raise_the_info_word_and_finish():
     info = gpu.step([synth.f32_to_bf16_bits(bad)])
     assert info[0] != 0
     torch.cuda.synchronize()
+
+
+def _conditioned_problem(m, n, r, kappa, seed):
+    """Gradient A diag(s) C^T (fp32) and a warm start spanning C[:, :r], so that
+    B Q_prev = A[:, :r] diag(s[:r]) O and R = C[:, :r] diag(s[:r]) O' have condition number
+    s_1 / s_r = kappa exactly (the tail s_{r+1..} lies below s_r)."""
+    rng = np.random.default_rng(seed)
+    k = min(m, n)
+    a = synth.random_orthonormal(m, k, rng)
+    c = synth.random_orthonormal(n, k, rng)
+    s = np.concatenate([np.geomspace(1.0, 1.0 / kappa, r), (0.5 / kappa) * np.arange(1, k - r + 1, dtype=np.float64) ** -0.5])
+    g = ((a * s[None, :]) @ c.T).astype(np.float32)
+    mix = synth.random_orthonormal(r, r, rng)
+    q0 = (c[:, :r] @ mix).astype(np.float32)
+    x = (0.02 * rng.standard_normal((m, n))).astype(np.float32)
+    return synth.MatrixState(x, np.zeros((m, n), dtype=np.float32), q0), g
+
+
+# Observed (printed): deviation from orthonormality at most 1.0e-5 at every kappa; error
+# against the oracle growing with kappa (the factor's trailing columns amplify the operand
+# rounding of B Q) up to 1.2e-5 in exact and 9.4e-3 in fast precision at kappa = 1000, still
+# inside the configurations' bars; kappa = 3000 is reported as rank deficient.
+@pytest.mark.parametrize("kappa", [1e1, 1e2, 1e3, 3e3])
+@pytest.mark.parametrize("precision", ["exact", "fast"])
+@pytest.mark.parametrize("r", [64, 320])
+def test_ill_conditioned_factors_stay_orthonormal_or_are_flagged(kappa, precision, r):
+    """orth() of Alg. 1 lines 2 and 4 must return an orthonormal factor: with condition numbers
+    of B Q_prev and of R from 10 to 3000 the second CholeskyQR pass switches from its
+    first-order form to a second factorisation; whatever cannot be orthonormalised is flagged
+    and leaves X alone - never silently wrong."""
+    m, n = 640, 512
+    st, g = _conditioned_problem(m, n, r, kappa, seed=int(kappa) + r)
+    gpu = GpuRun([(m, n)], r, "f32", [st], precision=precision, mu=0.95, lr=0.01)
+    info = gpu.step([g])
+    out = gpu.fetch(0)
+    if info != [0]:
+        print(f"\nkappa {kappa:g} {precision} r={r}: flagged {info}")
+        assert kappa >= 1e3, (kappa, precision, info)            # moderate conditioning must go through
+        assert out["X"].tobytes() == st.X.tobytes()
+        assert np.allclose(out["M"], g)
+        return
+    p, q = out["P"].astype(np.float64), out["Q"].astype(np.float64)
+    dev_p = float(np.abs(p.T @ p - np.eye(r)).max())
+    dev_q = float(np.abs(q.T @ q - np.eye(r)).max())
+    o = OrthDionOracle(mu=0.95, lr=0.01).step(st.X, g, st.M.astype(np.float64), st.Q.astype(np.float64))
+    errs = {k: rel_fro(out[k], o[k]) for k in ("P", "Q", "M", "R")}
+    print(f"\nkappa {kappa:g} {precision} r={r}: |P^T P - I| {dev_p:.2e} |Q^T Q - I| {dev_q:.2e} "
+          + " ".join(f"{k} {v:.2e}" for k, v in errs.items()))
+    assert dev_p < 2e-5 and dev_q < 2e-5
+    for k, v in errs.items():
+        assert v <= (1e-4 if precision == "exact" else 2e-2), (k, v)
 
 
 def test_orthonormality_and_qr_uniqueness_from_the_debug_factors():

@@ -12,7 +12,7 @@ import numpy as np
 import pytest
 
 from oracle.orthdion_oracle import (OrthDionOracle, bf16_bits_to_f64, col_norm,
-                                    f64_to_bf16_bits, thin_qr_positive)
+                                    f64_to_bf16_bits, rel_fro, thin_qr_library, thin_qr_positive)
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -351,6 +351,41 @@ PINS = [pin_golden_rotation, pin_golden_345, pin_brute_force,
 @pytest.mark.parametrize("pin", PINS, ids=lambda f: f.__name__)
 def test_oracle_pin(pin):
     pin(lambda **kw: OrthDionOracle(**kw))
+
+
+@pytest.mark.parametrize("pin", PINS, ids=lambda f: f.__name__)
+def test_oracle_pin_library_qr_route(pin):
+    """The route the largest parity cases take (numpy's QR with the signs fixed) is held to
+    every pin of the default route: hand-worked goldens, the loop transcription, the lemmas."""
+    pin(lambda **kw: OrthDionOracle(qr="library", **kw))
+
+
+def test_library_qr_route_equals_written_out_reflections():
+    rng = np.random.default_rng(21)
+    for rows, cols in [(6, 6), (300, 40), (513, 128)]:
+        a = rng.standard_normal((rows, cols)) @ np.diag(np.linspace(1.0, 1e-3, cols))
+        a[:, ::3] *= -1.0
+        q, t = thin_qr_positive(a)
+        ql, tl = thin_qr_library(a)
+        close(ql, q, 1e-10); close(tl, t, 1e-11)
+        assert np.all(np.diag(tl) > 0) and np.all(np.tril(tl, -1) == 0)
+    x, g, mom, q0 = rand_problem(5, 96, 160, 24)
+    for variant in ("qr", "colnorm"):
+        a = OrthDionOracle(variant=variant).step(x, g, mom, q0)
+        b = OrthDionOracle(variant=variant, qr="library").step(x, g, mom, q0)
+        for key in ("P", "R", "Q", "M", "X", "D"):
+            close(b[key], a[key], 1e-10)
+
+
+def test_rel_fro_is_the_relative_frobenius_distance():
+    # 3-4-5: ||a - b||_F = 5 against ||b||_F = 10; the reference is the second argument
+    b = np.array([[6.0, 0.0], [0.0, 8.0]])
+    a = b + np.array([[3.0, 0.0], [0.0, -4.0]])
+    assert rel_fro(a, b) == 0.5
+    assert abs(rel_fro(b, a) - 5.0 / math.sqrt(81.0 + 16.0)) < 1e-15
+    assert rel_fro(b, b) == 0.0
+    assert rel_fro(np.array([3.0, 4.0]), np.zeros(2)) == 5.0      # zero reference: absolute distance
+    assert rel_fro(np.array([1.0], dtype=np.float32), np.array([1.0 + 2.0 ** -30])) > 0.0   # compared in fp64
 
 
 # ----------------------------------------------------------------- pieces against libraries
