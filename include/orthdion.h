@@ -221,6 +221,23 @@ int orthdion_rank_policy(float e_t, float ema_prev, int32_t r_min, int32_t r_max
 int orthdion_resize_q(const float* q_old, int64_t n, int32_t r_old, float* q_new, int32_t r_new,
                       const float* pad, void* stream);
 
+/* ---- The step without a workspace argument, for callers that cannot allocate device memory
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc).
+ * Identical to orthdion_step, kernels included, except that the workspace is a device array
+ * inside the library, ORTHDION_STATIC_SCRATCH_BYTES long (128 MiB; every GPU the library runs
+ * on holds it until the process ends).  X, G, M, Q and `stream` as for orthdion_step; the
+ * current device must be the one the buffers and the stream belong to.  Calls no allocating
+ * routine.  A handle whose orthdion_workspace_bytes exceeds the array (one 4096 x 4096 matrix at
+ * r = 256 needs 92 MiB) is refused with ORTHDION_E_WORKSPACE_TOO_SMALL.  All calls on one GPU -
+ * from any handle or stream - share the one array: calls that overlap in time on a GPU race;
+ * enqueue them on one stream, or order the streams with events.  orthdion_get_info,
+ * orthdion_get_diagnostics and orthdion_workspace_layout refer to the array after such a
+ * step (offsets then count from its start, which the library does not expose). */
+#define ORTHDION_STATIC_SCRATCH_BYTES ((size_t)128 << 20)
+size_t orthdion_static_scratch_bytes(void);
+int orthdion_step_static(orthdion_handle h, void* const* X, const void* const* G, float* const* M,
+                         float* const* Q, void* stream);
+
 const char* orthdion_strerror(int status);
 
 int orthdion_destroy(orthdion_handle h);

@@ -29,7 +29,7 @@ EXPORTS = ["orthdion_create", "orthdion_workspace_bytes", "orthdion_set_lr", "or
            "orthdion_set_variant", "orthdion_step", "orthdion_get_info", "orthdion_workspace_layout",
            "orthdion_profile_begin", "orthdion_profile_end", "orthdion_set_diagnostics",
            "orthdion_get_diagnostics", "orthdion_rank_policy", "orthdion_resize_q", "orthdion_strerror",
-           "orthdion_destroy"]
+           "orthdion_destroy", "orthdion_step_static", "orthdion_static_scratch_bytes"]
 
 DIAG = ["b_norm", "r_norm", "tracking_error", "residual_ratio", "inner", "nu", "erank", "g_norm"]
 ORTHDION_NDIAG = len(DIAG)
@@ -95,6 +95,11 @@ def load() -> ctypes.CDLL:
     lib.orthdion_step.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
                                   ctypes.POINTER(vp), vp, sz, vp]
     lib.orthdion_step.restype = ctypes.c_int
+    lib.orthdion_step_static.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                         ctypes.POINTER(vp), vp]
+    lib.orthdion_step_static.restype = ctypes.c_int
+    lib.orthdion_static_scratch_bytes.argtypes = []
+    lib.orthdion_static_scratch_bytes.restype = sz
     lib.orthdion_get_info.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), vp]
     lib.orthdion_get_info.restype = ctypes.c_int
     lib.orthdion_workspace_layout.argtypes = [vp, ctypes.c_int32] + [ctypes.POINTER(sz)] * 6
@@ -182,6 +187,17 @@ def orthdion_step(handle: int, X: Sequence[int], G: Sequence[int], M: Sequence[i
     """X, G, M, Q: device addresses (ints), one per matrix; `stream` a hipStream_t as int."""
     _check(load().orthdion_step(handle, _ptr_array(X), _ptr_array(G), _ptr_array(M), _ptr_array(Q),
                                 ctypes.c_void_p(workspace), workspace_bytes, ctypes.c_void_p(stream)))
+
+
+def orthdion_step_static(handle: int, X: Sequence[int], G: Sequence[int], M: Sequence[int], Q: Sequence[int],
+                         stream: int = 0) -> None:
+    """orthdion_step on the library's own device scratch (no workspace argument)."""
+    _check(load().orthdion_step_static(handle, _ptr_array(X), _ptr_array(G), _ptr_array(M), _ptr_array(Q),
+                                       ctypes.c_void_p(stream)))
+
+
+def orthdion_static_scratch_bytes() -> int:
+    return int(load().orthdion_static_scratch_bytes())
 
 
 def orthdion_get_info(handle: int, nmat: int, stream: int = 0) -> List[int]:
