@@ -144,8 +144,9 @@ int orthdion_workspace_layout(orthdion_handle h, int32_t index, size_t* off_p, s
  *   orthdion_profile_end    waits for the recorded events, then writes, per phase, the summed
  *                           elapsed milliseconds and the number of intervals summed (steps x
  *                           shape-class batches) into two arrays of ORTHDION_NPHASE entries.
- * The two CHOL phases do not depend on m and n and run once for all matrices of one rank r,
- * whatever their shape class: they contribute one interval per step and distinct rank.  For
+ * The CHOL and GUARD phases do not depend on m and n and run once for all matrices of one rank
+ * r, whatever their shape class: they contribute one interval per step and distinct rank
+ * (the GUARD interval is empty for r <= 256, where the guard is part of the FINISH phase).  For
  * r <= 32 the factorisation is part of the first kernel of the ORTH phase that follows (one
  * launch does it together with the triangular product), and the CHOL interval is empty. */
 typedef enum {
@@ -154,14 +155,18 @@ typedef enum {
   ORTHDION_PHASE_PROJ_REDUCE = 2,  /* second stage of the split contraction               */
   ORTHDION_PHASE_GRAM_LEFT = 3,    /* Gram matrix of P_raw                    (line 2)    */
   ORTHDION_PHASE_CHOL_LEFT = 4,    /* its Cholesky factor and inverse; see below          */
-  ORTHDION_PHASE_ORTH_LEFT = 5,    /* rest of P = orth(P_raw), CholeskyQR2    (line 2)    */
-  ORTHDION_PHASE_BACK = 6,         /* kernel: R partials = (M + G)^T P        (line 3)    */
-  ORTHDION_PHASE_BACK_REDUCE = 7,
-  ORTHDION_PHASE_GRAM_RIGHT = 8,   /* Gram matrix of R (QR variant only)      (line 4)    */
-  ORTHDION_PHASE_CHOL_RIGHT = 9,   /* its Cholesky factor and inverse (QR variant only)   */
-  ORTHDION_PHASE_ORTH_RIGHT = 10,  /* rest of Q = orth(R), or ColNorm(R)      (line 4)    */
-  ORTHDION_PHASE_EFX = 11,         /* kernel: error feedback + update         (lines 5-7) */
-  ORTHDION_NPHASE = 12
+  ORTHDION_PHASE_ORTH_LEFT = 5,    /* second CholeskyQR pass of P up to its deviation     */
+  ORTHDION_PHASE_GUARD_LEFT = 6,   /* re-factorisation of ill-conditioned matrices, r > 256 */
+  ORTHDION_PHASE_FINISH_LEFT = 7,  /* P = orth(P_raw) written out             (line 2)    */
+  ORTHDION_PHASE_BACK = 8,         /* kernel: R partials = (M + G)^T P        (line 3)    */
+  ORTHDION_PHASE_BACK_REDUCE = 9,
+  ORTHDION_PHASE_GRAM_RIGHT = 10,  /* Gram matrix of R (QR variant only)      (line 4)    */
+  ORTHDION_PHASE_CHOL_RIGHT = 11,  /* its Cholesky factor and inverse (QR variant only)   */
+  ORTHDION_PHASE_ORTH_RIGHT = 12,  /* second pass of Q up to its deviation (QR variant)   */
+  ORTHDION_PHASE_GUARD_RIGHT = 13, /* as GUARD_LEFT (QR variant only)                     */
+  ORTHDION_PHASE_FINISH_RIGHT = 14,/* Q = orth(R) written out, or ColNorm(R)  (line 4)    */
+  ORTHDION_PHASE_EFX = 15,         /* kernel: error feedback + update         (lines 5-7) */
+  ORTHDION_NPHASE = 16
 } orthdion_phase;
 int orthdion_profile_begin(orthdion_handle h, uint32_t phase_mask, int32_t max_steps);
 int orthdion_profile_end(orthdion_handle h, float* ms_per_phase, int32_t* count_per_phase);

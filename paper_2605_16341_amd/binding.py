@@ -34,8 +34,8 @@ EXPORTS = ["orthdion_create", "orthdion_workspace_bytes", "orthdion_set_lr", "or
 DIAG = ["b_norm", "r_norm", "tracking_error", "residual_ratio", "inner", "nu", "erank", "g_norm"]
 ORTHDION_NDIAG = len(DIAG)
 
-PHASES = ["stats", "proj", "proj_reduce", "gram_left", "chol_left", "orth_left", "back", "back_reduce",
-          "gram_right", "chol_right", "orth_right", "efx"]
+PHASES = ["stats", "proj", "proj_reduce", "gram_left", "chol_left", "orth_left", "guard_left", "finish_left", "back",
+          "back_reduce", "gram_right", "chol_right", "orth_right", "guard_right", "finish_right", "efx"]
 ORTHDION_NPHASE = len(PHASES)
 
 

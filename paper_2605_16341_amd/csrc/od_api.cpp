@@ -227,6 +227,12 @@ static int create_impl(orthdion_handle* out, const orthdion_matdesc* mats, int32
     const int proj_rows = (resolve_prec(*cfg) == od::PREC_F16 && od::proj_uses_flat_tiles((int)m, (int)r, d.nb)) ? 64 : 128;
     b.splits_proj = pick_splits(((m + proj_rows - 1) / proj_rows) * tiles_r, d.nb, n, 128);
     b.splits_back = pick_splits(((n + 127) / 128) * tiles_r, d.nb, m, 128);
+    if (resolve_prec(*cfg) == od::PREC_F16 && od::stream_kernel_eligible(d)) {
+      // one 8-wave workgroup per CU and 128 x 256 / 512 tiles: two rounds of workgroups fill the chip
+      const int64_t tiles_c = (r + od::stream_tile_cols((int)r) - 1) / od::stream_tile_cols((int)r);
+      b.splits_proj = pick_splits(((m + 127) / 128) * tiles_c, d.nb, n, 256);
+      b.splits_back = pick_splits(((n + 127) / 128) * tiles_c, d.nb, m, 256);
+    }
     const int64_t gt = ((r + 127) / 128) * ((r + 127) / 128);
     b.splits_gram_p = pick_splits(gt, d.nb, m, 256);
     b.splits_gram_q = pick_splits(gt, d.nb, n, 256);
@@ -294,13 +300,16 @@ extern "C" int orthdion_set_variant(orthdion_handle h, orthdion_variant v) {
     if ((expr) != hipSuccess) return ORTHDION_E_HIP;  \
   } while (0)
 
-// orth() of `a0` (rows x r) by CholeskyQR2 comes in three pieces, so that the Cholesky step in
-// the middle can be launched once for every matrix of a rank:
+// orth() of `a0` (rows x r) by CholeskyQR2 comes in pieces, so that the two r x r stages in the
+// middle (which do not depend on rows) can be launched once for every matrix of a rank:
 //   orth_gram : Gram matrix of a0, reduced into this batch's slices of the class array
-//   launch_cholinv over the rank class : T1, W1
-//   orth_finish: a1 = a0 W1, then a first-order second pass (Gram of a1, W2 = I - Phi(E),
-//                result = a1 W2 -> a0 | callers' Q).
-static int orth_gram(const Batch& b, char* ws, int rows, size_t off_a0, int64_t st_a, int splits, hipStream_t st) {
+//   class_cholinv over the rank class : T1, W1
+//   orth_second_pass, class_guard, orth_result : see below.
+static int orth_gram(const Batch& b, char* ws, int rows, size_t off_a0, int64_t st_a, int splits, bool fast, int side,
+                     const float* scal, hipStream_t st) {
+  // fast precision has the sampled scale of B at hand: two-term fp16 operands (half the
+  // matrix-core work of the three-way bf16 split at 22 instead of 24 bits)
+  const int mode = fast ? od::kGramH2 : od::kGramBF3;
   WsArr a0{reinterpret_cast<float*>(ws + off_a0), st_a};
   WsArr part{reinterpret_cast<float*>(ws + b.off_part), b.st_part};
   WsArr gram{reinterpret_cast<float*>(ws + b.off_gram), b.st_rr};
@@ -312,10 +321,10 @@ static int orth_gram(const Batch& b, char* ws, int rows, size_t off_a0, int64_t 
   }
   // a single split is the Gram matrix itself: written straight into the class array
   if (splits == 1) {
-    OD_TRY(od::launch_gram(b.d.nb, rows, b.d.r, a0, gram, 1, 1, st));
+    OD_TRY(od::launch_gram(b.d.nb, rows, b.d.r, a0, gram, 1, mode, st, &b.d, scal, side));
     return ORTHDION_OK;
   }
-  OD_TRY(od::launch_gram(b.d.nb, rows, b.d.r, a0, part, splits, 1, st));
+  OD_TRY(od::launch_gram(b.d.nb, rows, b.d.r, a0, part, splits, mode, st, &b.d, scal, side));
   // ordered reduction of the split partial sums on many workgroups: the factorisation runs on
   // one workgroup per matrix and should not spend its time summing
   OD_TRY(od::launch_reduce(b.d.nb, part, splits, (int64_t)b.d.r * b.d.r, gram, st));
@@ -326,9 +335,22 @@ static int orth_gram(const Batch& b, char* ws, int rows, size_t off_a0, int64_t 
 // the class-wide Cholesky step is skipped for them.
 static bool first_pass_in_one_launch(int r) { return r <= 32; }
 
-static int orth_finish(const Batch& b, char* ws, int rows, size_t off_a0, size_t off_a1, int64_t st_a, int splits,
-                       size_t off_t1, size_t off_t2, int info_slot, const MatPtrs* q_out, HalfArr hn, HalfArr ht,
-                       float* scal, int* info, int exact, hipStream_t st) {
+// The rest of orth() after the first factorisation, in three pieces so that the guard in
+// the middle can be launched once for every matrix of a rank:
+//   orth_second_pass : a1 = a0 W1, Gram of a1, k_corr (T2 = I + Phi(E), Phi^T or W2, max|E|);
+//                      r > 256: the summed Gram matrix of a flagged matrix goes to the class array
+//   class_guard      : r > 256 only: Cholesky factor and inverse of I + E for every matrix of the
+//                      class whose max|E| is above kFirstOrderDeviation (T2 and W2 are overwritten)
+//   orth_result      : the correction a1 - a1 Phi(E) (fast precision) or a1 W2, for a flagged
+//                      matrix the full product a1 W2 -> a0 | callers' Q (+ fp16 copies);
+//                      r <= 256: the guard runs here, per batch (one launch: k_chol256 sums the
+//                      partials itself).
+// A matrix is flagged when its first pass left a deviation too large for the first-order form
+// (an ill-conditioned B Q or R).  Every launch of the guard returns at once for the others.
+static bool guard_is_class_wide(int r) { return r > 256; }
+
+static int orth_second_pass(const Batch& b, char* ws, int rows, size_t off_a0, size_t off_a1, int64_t st_a, int splits,
+                            size_t off_t1, size_t off_t2, int info_slot, float* scal, int* info, int exact, hipStream_t st) {
   const int nb = b.d.nb, r = b.d.r;
   WsArr a0{reinterpret_cast<float*>(ws + off_a0), st_a}, a1{reinterpret_cast<float*>(ws + off_a1), st_a};
   WsArr part{reinterpret_cast<float*>(ws + b.off_part), b.st_part};
@@ -341,28 +363,37 @@ static int orth_finish(const Batch& b, char* ws, int rows, size_t off_a0, size_t
     OD_TRY(od::launch_small_first_pass(nb, rows, r, a0, part1, splits, t1, w, a1, part, splits, info, info_slot, st));
   } else {
     OD_TRY(od::launch_apply(nb, rows, r, a0, w, a1, nullptr, none, none, exact, st));
-    OD_TRY(od::launch_gram(nb, rows, r, a1, part, splits, exact, st));
+    OD_TRY(od::launch_gram(nb, rows, r, a1, part, splits, exact ? od::kGramBF3 : od::kGramH2, st, nullptr, nullptr, 2));
   }
-  // fast precision: the second pass as a correction a1 - a1 Phi(E) (one fp16 product; a1 itself
-  // stays in fp32); exact precision: the product a1 (I - Phi(E)) on six-product operands
-  // (Phi^T as fp16 operand words lives in the r x r scratch the factorisation no longer needs)
+  // fast precision: Phi^T as fp16 operand words lives in the r x r scratch the factorisation no
+  // longer needs; exact precision: W2 = I - Phi(E)
   const HalfArr phit{exact ? nullptr : reinterpret_cast<uint16_t*>(ws + b.off_tmp), 2 * b.st_rr};
   OD_TRY(od::launch_corr(nb, r, part, splits, t1, t2, w, phit, scal, 2 + info_slot, info, info_slot, st));
-  // A matrix whose first pass left a deviation too large for the first-order form (an
-  // ill-conditioned B Q or R) gets a true second pass instead: Cholesky factor and inverse of
-  // its I + E (T2 and W2 are overwritten), then the full triangular product.  Every launch of
-  // this branch returns at once for the other matrices.
-  const od::Pred big{scal, 2 + info_slot, od::kFirstOrderDeviation, 1}, small{scal, 2 + info_slot, od::kFirstOrderDeviation, 0};
-  WsArr gram{reinterpret_cast<float*>(ws + b.off_gram), b.st_rr}, tmp{reinterpret_cast<float*>(ws + b.off_tmp), b.st_rr};
-  if (r <= 256) {
-    OD_TRY(od::launch_cholinv(nb, r, part, t2, w, tmp, info, info_slot, st, big, splits, (int64_t)r * r));
-  } else {
+  if (guard_is_class_wide(r)) {
+    const od::Pred big{scal, 2 + info_slot, od::kFirstOrderDeviation, 1};
+    WsArr gram{reinterpret_cast<float*>(ws + b.off_gram), b.st_rr};
     OD_TRY(od::launch_reduce(nb, part, splits, (int64_t)r * r, gram, st, big));
-    OD_TRY(od::launch_cholinv(nb, r, gram, t2, w, tmp, info, info_slot, st, big));
+  }
+  return ORTHDION_OK;
+}
+
+static int orth_result(const Batch& b, char* ws, int rows, size_t off_a0, size_t off_a1, int64_t st_a, int splits,
+                       size_t off_t2, int info_slot, const MatPtrs* q_out, HalfArr hn, HalfArr ht, float* scal, int* info,
+                       int exact, hipStream_t st) {
+  const int nb = b.d.nb, r = b.d.r;
+  WsArr a0{reinterpret_cast<float*>(ws + off_a0), st_a}, a1{reinterpret_cast<float*>(ws + off_a1), st_a};
+  WsArr w{reinterpret_cast<float*>(ws + b.off_w), b.st_rr}, tmp{reinterpret_cast<float*>(ws + b.off_tmp), b.st_rr};
+  WsArr t2{reinterpret_cast<float*>(ws + off_t2), b.st_rr};
+  const od::Pred big{scal, 2 + info_slot, od::kFirstOrderDeviation, 1}, small{scal, 2 + info_slot, od::kFirstOrderDeviation, 0};
+  if (!guard_is_class_wide(r)) {
+    WsArr part{reinterpret_cast<float*>(ws + b.off_part), b.st_part};
+    if (first_pass_in_one_launch(r)) part.base += (int64_t)splits * r * r;
+    OD_TRY(od::launch_cholinv(nb, r, part, t2, w, tmp, info, info_slot, st, big, splits, (int64_t)r * r));
   }
   if (exact) {
     OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, hn, ht, exact, st));
   } else {
+    const HalfArr phit{reinterpret_cast<uint16_t*>(ws + b.off_tmp), 2 * b.st_rr};
     OD_TRY(od::launch_apply_correction(nb, rows, r, a1, phit, a0, q_out, hn, ht, st, small));
     OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, hn, ht, exact, st, big));
   }
@@ -377,6 +408,17 @@ static int class_cholinv(const RankClass& c, char* ws, size_t off_t1, int info_s
   WsArr w{reinterpret_cast<float*>(ws + c.off_w), c.st_rr}, tmp{reinterpret_cast<float*>(ws + c.off_tmp), c.st_rr};
   WsArr t1{reinterpret_cast<float*>(ws + off_t1), c.st_rr};
   OD_TRY(od::launch_cholinv(c.count, c.r, gram, t1, w, tmp, info_all + (size_t)c.slot_base * od::kInfoPerMat, info_slot, st));
+  return ORTHDION_OK;
+}
+
+// The guard of the second pass for every matrix of a rank class above 256 (see orth_second_pass).
+static int class_guard(const RankClass& c, char* ws, size_t off_t2, int info_slot, float* scal_all, int* info_all, hipStream_t st) {
+  if (!guard_is_class_wide(c.r)) return ORTHDION_OK;
+  WsArr gram{reinterpret_cast<float*>(ws + c.off_gram), c.st_rr};
+  WsArr w{reinterpret_cast<float*>(ws + c.off_w), c.st_rr}, tmp{reinterpret_cast<float*>(ws + c.off_tmp), c.st_rr};
+  WsArr t2{reinterpret_cast<float*>(ws + off_t2), c.st_rr};
+  const od::Pred big{scal_all + (size_t)c.slot_base * od::kScalPerMat, 2 + info_slot, od::kFirstOrderDeviation, 1};
+  OD_TRY(od::launch_cholinv(c.count, c.r, gram, t2, w, tmp, info_all + (size_t)c.slot_base * od::kInfoPerMat, info_slot, st, big));
   return ORTHDION_OK;
 }
 
@@ -486,23 +528,35 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     if (!proj_direct) OD_TRY(od::launch_reduce(d.nb, v.part, b.splits_proj, (int64_t)d.m * d.r, v.pa, st));
     OD_PHASE_END(ORTHDION_PHASE_PROJ_REDUCE);
     OD_PHASE_BEGIN(ORTHDION_PHASE_GRAM_LEFT);
-    int rc = orth_gram(b, ws, d.m, b.off_pa, b.st_p, b.splits_gram_p, st);
+    int rc = orth_gram(b, ws, d.m, b.off_pa, b.st_p, b.splits_gram_p, fast, 0, v.scal, st);
     if (rc != ORTHDION_OK) return rc;
     OD_PHASE_END(ORTHDION_PHASE_GRAM_LEFT);
     return ORTHDION_OK;
   };
 
-  // rest of line 2 (P = orth(P_raw)), line 3 (R = (M + G)^T P), and the head of line 4
+  // rest of line 2 (P = orth(P_raw)): second pass up to its deviation
+  auto left_second = [&](int bi) -> int {
+    const Batch& b = h->batches[bi];
+    BatchView v;
+    view_of(b, v);
+    OD_PHASE_BEGIN(ORTHDION_PHASE_ORTH_LEFT);
+    int rc = orth_second_pass(b, ws, b.d.m, b.off_pa, b.off_pb, b.st_p, b.splits_gram_p, b.off_tp1, b.off_tp2, 0, v.scal, v.info,
+                              exact, st);
+    if (rc != ORTHDION_OK) return rc;
+    OD_PHASE_END(ORTHDION_PHASE_ORTH_LEFT);
+    return ORTHDION_OK;
+  };
+  // P itself, line 3 (R = (M + G)^T P), and the head of line 4
   auto middle = [&](int bi) -> int {
     const Batch& b = h->batches[bi];
     const ClassDims& d = b.d;
     BatchView v;
     view_of(b, v);
-    OD_PHASE_BEGIN(ORTHDION_PHASE_ORTH_LEFT);
-    int rc = orth_finish(b, ws, d.m, b.off_pa, b.off_pb, b.st_p, b.splits_gram_p, b.off_tp1, b.off_tp2, 0, nullptr,
+    OD_PHASE_BEGIN(ORTHDION_PHASE_FINISH_LEFT);
+    int rc = orth_result(b, ws, d.m, b.off_pa, b.off_pb, b.st_p, b.splits_gram_p, b.off_tp2, 0, nullptr,
                          fast ? v.ph : none, fast ? v.pht : none, v.scal, v.info, exact, st);
     if (rc != ORTHDION_OK) return rc;
-    OD_PHASE_END(ORTHDION_PHASE_ORTH_LEFT);
+    OD_PHASE_END(ORTHDION_PHASE_FINISH_LEFT);
     OD_PHASE_KERNEL(ORTHDION_PHASE_BACK);
     // as for the projection: a single split goes straight to its place; fast precision still
     // needs the fp16 copy of R, made from there
@@ -515,10 +569,23 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     if (diag) OD_TRY(od::launch_diag_cols(d.nb, d.n, d.r, v.ra, v.part, b.slabs, v.dacc, st));
     if (h->cfg.variant == ORTHDION_QR) {
       OD_PHASE_BEGIN(ORTHDION_PHASE_GRAM_RIGHT);
-      rc = orth_gram(b, ws, d.n, b.off_ra, b.st_r, b.splits_gram_q, st);
+      rc = orth_gram(b, ws, d.n, b.off_ra, b.st_r, b.splits_gram_q, fast, 1, v.scal, st);
       if (rc != ORTHDION_OK) return rc;
       OD_PHASE_END(ORTHDION_PHASE_GRAM_RIGHT);
     }
+    return ORTHDION_OK;
+  };
+
+  // rest of line 4 for the QR variant: second pass of Q = orth(R) up to its deviation
+  auto right_second = [&](int bi) -> int {
+    const Batch& b = h->batches[bi];
+    BatchView v;
+    view_of(b, v);
+    OD_PHASE_BEGIN(ORTHDION_PHASE_ORTH_RIGHT);
+    int rc = orth_second_pass(b, ws, b.d.n, b.off_ra, b.off_rb, b.st_r, b.splits_gram_q, b.off_tq1, b.off_tq2, 1, v.scal, v.info,
+                              exact, st);
+    if (rc != ORTHDION_OK) return rc;
+    OD_PHASE_END(ORTHDION_PHASE_ORTH_RIGHT);
     return ORTHDION_OK;
   };
 
@@ -529,16 +596,16 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     const ClassDims& d = b.d;
     BatchView v;
     view_of(b, v);
-    OD_PHASE_BEGIN(ORTHDION_PHASE_ORTH_RIGHT);
+    OD_PHASE_BEGIN(ORTHDION_PHASE_FINISH_RIGHT);
     if (h->cfg.variant == ORTHDION_QR) {
-      int rc = orth_finish(b, ws, d.n, b.off_ra, b.off_rb, b.st_r, b.splits_gram_q, b.off_tq1, b.off_tq2, 1, &v.ptrs,
+      int rc = orth_result(b, ws, d.n, b.off_ra, b.off_rb, b.st_r, b.splits_gram_q, b.off_tq2, 1, &v.ptrs,
                            fast ? v.qh : none, none, v.scal, v.info, exact, st);
       if (rc != ORTHDION_OK) return rc;
     } else {
       OD_TRY(od::launch_colnorm(d.nb, d.n, d.r, v.ra, v.ptrs, v.part, b.slabs, v.colsq, v.scal, v.info,
                                 fast ? v.qh : none, st));
     }
-    OD_PHASE_END(ORTHDION_PHASE_ORTH_RIGHT);
+    OD_PHASE_END(ORTHDION_PHASE_FINISH_RIGHT);
     if (diag) {
       // nu = sigma_1(Q_new): Gram matrix of the new right factor, then power iteration
       WsArr rb{reinterpret_cast<float*>(ws + b.off_rb), b.st_r};
@@ -546,7 +613,7 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
       WsArr tq1{reinterpret_cast<float*>(ws + b.off_tq1), b.st_rr}, tq2{reinterpret_cast<float*>(ws + b.off_tq2), b.st_rr};
       if (h->cfg.variant == ORTHDION_QR) OD_TRY(od::launch_diag_trace(d.nb, d.r, tq1, tq2, v.dacc, st));
       OD_TRY(od::launch_gather_q(d.nb, d.n, d.r, v.ptrs, rb, st));
-      OD_TRY(od::launch_gram(d.nb, d.n, d.r, rb, v.part, b.splits_gram_q, 1, st));
+      OD_TRY(od::launch_gram(d.nb, d.n, d.r, rb, v.part, b.splits_gram_q, od::kGramBF3, st));
       OD_TRY(od::launch_reduce(d.nb, v.part, b.splits_gram_q, (int64_t)d.r * d.r, gram, st));
       OD_TRY(od::launch_power(d.nb, d.r, gram, tmp, 128, v.dacc, st));
       OD_TRY(od::launch_diag_final(d.nb, v.dpart, v.dacc, h->cfg.variant == ORTHDION_COLNORM ? 1 : 0,
@@ -570,11 +637,21 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     if ((rc = class_cholinv(c, ws, c.off_tp1, 0, info_all, st)) != ORTHDION_OK) return rc;
     OD_PHASE_END(ORTHDION_PHASE_CHOL_LEFT);
     for (int b2 : c.batches)
+      if ((rc = left_second(b2)) != ORTHDION_OK) return rc;
+    OD_PHASE_BEGIN(ORTHDION_PHASE_GUARD_LEFT);
+    if ((rc = class_guard(c, ws, c.off_tp2, 0, scal_all, info_all, st)) != ORTHDION_OK) return rc;
+    OD_PHASE_END(ORTHDION_PHASE_GUARD_LEFT);
+    for (int b2 : c.batches)
       if ((rc = middle(b2)) != ORTHDION_OK) return rc;
     if (h->cfg.variant == ORTHDION_QR) {
       OD_PHASE_BEGIN(ORTHDION_PHASE_CHOL_RIGHT);
       if ((rc = class_cholinv(c, ws, c.off_tq1, 1, info_all, st)) != ORTHDION_OK) return rc;
       OD_PHASE_END(ORTHDION_PHASE_CHOL_RIGHT);
+      for (int b2 : c.batches)
+        if ((rc = right_second(b2)) != ORTHDION_OK) return rc;
+      OD_PHASE_BEGIN(ORTHDION_PHASE_GUARD_RIGHT);
+      if ((rc = class_guard(c, ws, c.off_tq2, 1, scal_all, info_all, st)) != ORTHDION_OK) return rc;
+      OD_PHASE_END(ORTHDION_PHASE_GUARD_RIGHT);
     }
     for (int b2 : c.batches)
       if ((rc = tail(b2)) != ORTHDION_OK) return rc;

@@ -94,6 +94,33 @@ struct NumF16 {
   }
 };
 
+// The value times a power-of-two scale split into two fp16 terms, hi + lo (22 significant
+// bits), three products (hi hi, hi lo, lo hi): close to the three-way bf16 split at half
+// its matrix-core work.  The scale must bring the data near the top of fp16's range: a term
+// below 2^-14 (hi) or 2^-24 (lo) loses bits, which only matters for entries far below the rest.
+struct NumH2 {
+  static constexpr int PARTS = 2;
+  static constexpr bool F16 = true;
+  OD_DEV static void pack(const float* x, float scale, u32x4* out) {
+    u32x4 hi, lo;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const float a = __builtin_amdgcn_fmed3f(x[2 * i] * scale, -65504.f, 65504.f);
+      const float b = __builtin_amdgcn_fmed3f(x[2 * i + 1] * scale, -65504.f, 65504.f);
+      f16x2 h;
+      h[0] = (_Float16)a;
+      h[1] = (_Float16)b;
+      f16x2 l;
+      l[0] = (_Float16)(a - (float)h[0]);
+      l[1] = (_Float16)(b - (float)h[1]);
+      hi[i] = __builtin_bit_cast(uint32_t, h);
+      lo[i] = __builtin_bit_cast(uint32_t, l);
+    }
+    out[0] = hi;
+    out[1] = lo;
+  }
+};
+
 template <int S>
 struct NumBF {
   static constexpr int PARTS = S;

@@ -75,6 +75,11 @@ hipError_t launch_stats(const ClassDims& d, const MatPtrs& ptrs, float* scal, in
 // whether launch_proj (fast precision) works on 64-row tiles for this shape class: the
 // caller sizes the number of splits accordingly
 bool proj_uses_flat_tiles(int m, int r, int nb);
+// whether launch_proj / launch_back (fast precision) take the direct-to-LDS kernel for this shape
+// class (128-row tiles, stream_tile_cols(r) columns, one workgroup per CU): the caller sizes
+// the number of splits accordingly
+bool stream_kernel_eligible(const ClassDims& d);
+int stream_tile_cols(int r);
 // P_raw partials: part[split][m][r] = (M+G)[:, k-range] * Q[k-range, :]
 hipError_t launch_proj(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal,
                        WsArr part, int splits, HalfArr qht, hipStream_t st);
@@ -88,7 +93,13 @@ hipError_t launch_reduce(int nb, WsArr part, int splits, int64_t count, WsArr ou
 hipError_t launch_reduce_r(const ClassDims& d, WsArr part, int splits, WsArr out, HalfArr rh, const float* scal, hipStream_t st);
 
 // Gram partials: part[split][r][r] = A[k-range, :]^T A[k-range, :], A is rows x r (ld r)
-hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits, int exact, hipStream_t st);
+// Operand format (`mode`): kGramBF2 / kGramBF3 two- / three-way split bf16 (3 / 6 products,
+// 16 / 24 bits), kGramH2 two-term scaled fp16 (3 products, 22 bits).  kGramH2 needs the
+// operand's scale: `side` 0 = P_raw, 1 = R (scale derived from the sampled scale of B in
+// `scal`, shape in `d`), 2 = a nearly orthonormal factor (fixed scale, d and scal unused).
+enum : int { kGramBF2 = 0, kGramBF3 = 1, kGramH2 = 2 };
+hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits, int mode, hipStream_t st,
+                       const ClassDims* d = nullptr, const float* scal = nullptr, int side = -1);
 // out = A * W, A rows x r, W r x r upper triangular (both ld r); the result goes to the
 // callers' Q buffers when q_ptrs is given, else to the workspace array `out`.
 // With hn.base / ht.base non-null the result is also stored as fp16 scaled by 2^10, in

@@ -7,7 +7,12 @@
 
 #include <hip/hip_ext.h>
 
+#include <cstdio>
+#include <cstdlib>
+#include <cstring>
+
 #include "od_chol.h"
+#include "od_dma.h"
 #include "od_gemm.h"
 
 namespace od {
@@ -269,8 +274,21 @@ __global__ __launch_bounds__(256) void k_reduce_r(ClassDims d, WsArr part, int s
 // ------------------------------------------------------------------------------------
 // Gram matrix A^T A (split over rows)                 CholeskyQR for orth(), Alg. 1 l. 2, 4
 // ------------------------------------------------------------------------------------
+// Power-of-two scale of a Gram operand in the two-term fp16 format.  side 0: P_raw = B Q, whose
+// rms is at most rms(B) sqrt(n / r) for an orthonormal Q; side 1: R = B^T P, at most
+// rms(B) sqrt(m / r); both brought to about 2^6 .. 2^7, which leaves 2^9 of headroom for
+// entries above the rms and saturates beyond.  side 2: a nearly orthonormal factor (entries
+// at most about one): 2^12.
+constexpr float kGramUnitScale = 4096.f;
+OD_DEV float gram_operand_scale(const ClassDims& d, const float* scal, int side, int z) {
+  if (side == 2) return kGramUnitScale;
+  const float sb = b_scale(d, scal, z);
+  const float ratio = side == 0 ? (float)d.n / (float)d.r : (float)d.m / (float)d.r;
+  return ldexpf(sb, 6 - ilogbf(ratio) / 2);
+}
+
 template <class T, class Num>
-__global__ __launch_bounds__(T::THREADS) void k_gram(int rows, int r, WsArr a, WsArr part, int splits) {
+__global__ __launch_bounds__(T::THREADS) void k_gram(int rows, int r, WsArr a, WsArr part, int splits, ClassDims d, const float* scal, int side) {
   static_assert(T::MT == T::NT, "the tile grid of a symmetric result must be symmetric");
   extern __shared__ __align__(16) char lds[];
   const int tiles = (r + T::NT - 1) / T::NT;
@@ -287,7 +305,17 @@ __global__ __launch_bounds__(T::THREADS) void k_gram(int rows, int r, WsArr a, W
   const int kbeg = split_begin(rows, splits, T::KT, split, &kend);
   f32x16 acc[T::FM][T::FN];
   zero_acc<T>(acc);
-  gemm_mainloop_deep<T, Num, KSF, SrcF32, KSF, SrcF32, 3>(s, s, tm * T::MT, tn * T::NT, kbeg, kend, 1.f, 1.f, lds, acc);
+  const float sc = Num::F16 ? gram_operand_scale(d, scal, side, z) : 1.f;
+  gemm_mainloop_deep<T, Num, KSF, SrcF32, KSF, SrcF32, 3>(s, s, tm * T::MT, tn * T::NT, kbeg, kend, sc, sc, lds, acc);
+  if constexpr (Num::F16) {
+    const float inv = 1.f / (sc * sc);
+#pragma unroll
+    for (int fm = 0; fm < T::FM; ++fm)
+#pragma unroll
+      for (int fn = 0; fn < T::FN; ++fn)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) acc[fm][fn][v] *= inv;
+  }
   float* out = part.base + (int64_t)z * part.stride + (int64_t)split * r * r;
   for_each_acc<T>(acc, tm * T::MT, tn * T::NT, [&](int row, int col, float v) {
     if (row < r && col < r) out[(int64_t)row * r + col] = v;
@@ -1054,6 +1082,390 @@ __global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, con
   }
 }
 
+// ------------------------------------------------------------------------------------
+// The same pass with direct-to-LDS operand loads (r a multiple of 32).  Tile: 128 rows i x
+// 128 columns j, 4 waves; wave (wi, wj) owns rows 64 wi .. +63 and columns 64 wj .. +63 of BOTH
+// products: eight 32 x 32 accumulators (two row blocks x even / odd columns x {P R^T, P Q^T}),
+// six LDS operand reads for eight matrix-core products per 16-deep step (0.75 per product,
+// against 1.25 with 32 x 64 wave tiles).  Three LDS stages of 32-deep P, R, Q tiles are kept
+// in flight by `dma16` (od_dma.h), one barrier per step.  The R / Q rows arrive permuted so
+// that operand row rho of parity f is column 2 rho + f: lane c then owns the adjacent columns
+// 2c, 2c + 1 and every wave instruction of the epilogue moves whole 256-byte (M) or 128-byte
+// (G, X) row segments, as in k_efx_h.  Two workgroups per CU (72 KB of LDS each): one streams
+// M, G, X while the other multiplies.
+// ------------------------------------------------------------------------------------
+template <bool XBF, bool GBF, bool STREAM>
+__global__ __launch_bounds__(256, 2) void k_efx_d(ClassDims d, MatPtrs ptrs, const float* scal, const int* info, HalfArr ph, HalfArr rh,
+                                                  HalfArr qh, float a_coef, float b_coef, float lr) {
+  constexpr int TI = 128, TJ = 128, KT = 32, ROWB = KT * 2, ST = 3;
+  constexpr int PLANE = 128 * ROWB, STAGE = 3 * PLANE;       // R | Q | P
+  constexpr int CPW = 3 * 8 / 4;                              // 1 KB chunks per wave and stage
+  extern __shared__ __align__(16) char lds[];
+  const int tiles_i = (d.m + TI - 1) / TI;
+  int ti = blockIdx.x % tiles_i, tj = blockIdx.x / tiles_i;
+  if (d.r > 256) {
+    // bands of eight tile columns, one contiguous range of that order per XCD (see k_efx_h)
+    const int tiles_j = (d.n + TJ - 1) / TJ;
+    const int logical = xcd_contiguous(blockIdx.x, gridDim.x);
+    const int band = logical / (tiles_i * 8);
+    const int in_band = logical - band * tiles_i * 8;
+    const int bw = min(8, tiles_j - band * 8);
+    ti = in_band / bw;
+    tj = band * 8 + in_band % bw;
+  }
+  const int z = blockIdx.z;
+  const int tid = threadIdx.x, lane = tid & 63, c = lane & 31;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wi = wave & 1, wj = wave >> 1;
+
+  // ---- this lane's share of every stage: chunk = 16 LDS rows of one of the three tiles
+  const uint16_t* gp[CPW];
+  uint32_t loff[CPW];
+  const uint32_t lds0 = lds_offset_of(lds);
+#pragma unroll
+  for (int q = 0; q < CPW; ++q) {
+    const int chunk = wave + 4 * q;                 // 0..7 R, 8..15 Q, 16..23 P
+    const int which = chunk >> 3, rel = chunk & 7;
+    const int row = rel * 16 + (lane >> 2), slot = lane & 3;
+    const int kg = slot ^ swz32(row);
+    int grow;
+    const uint16_t* base;
+    if (which == 2) {
+      grow = min(ti * TI + row, d.m - 1);
+      base = ph.base + (int64_t)z * ph.stride;
+    } else {
+      const int col = (row & 64) + 2 * (row & 31) + ((row >> 5) & 1);     // LDS row -> tile column
+      grow = min(tj * TJ + col, d.n - 1);
+      base = (which == 0 ? rh.base + (int64_t)z * rh.stride : qh.base + (int64_t)z * qh.stride);
+    }
+    gp[q] = base + (int64_t)grow * d.r + kg * 8;
+    loff[q] = lds0 + which * PLANE + rel * 1024;
+  }
+  const int nsteps = d.r / KT;
+  auto issue = [&](int step) {
+    const uint32_t boff = (uint32_t)(step % ST) * STAGE;
+#pragma unroll
+    for (int q = 0; q < CPW; ++q) dma16(gp[q] + step * KT, loff[q] + boff);
+  };
+
+  f32x16 acc_r[2][2], acc_q[2][2];
+#pragma unroll
+  for (int fm = 0; fm < 2; ++fm)
+#pragma unroll
+    for (int f = 0; f < 2; ++f)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) { acc_r[fm][f][v] = 0.f; acc_q[fm][f][v] = 0.f; }
+
+#pragma unroll
+  for (int s = 0; s < ST - 1; ++s)
+    if (s < nsteps) issue(s);
+
+  const int prow = wi * 64 + c, jrow = wj * 64 + c;
+  for (int i = 0; i < nsteps; ++i) {
+    // stage i has landed when at most the loads of the one younger stage are outstanding
+    if (i + ST - 2 < nsteps) __builtin_amdgcn_s_waitcnt(vmcnt_only((ST - 2) * CPW));
+    else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (i + ST - 1 < nsteps) issue(i + ST - 1);       // into the buffer every wave has finished reading
+    const char* base = lds + (i % ST) * STAGE;
+#pragma unroll
+    for (int kk = 0; kk < KT / 16; ++kk) {
+      const int kg = 2 * kk + (lane >> 5);
+      u32x4 fp[2], fr[2], fq[2];
+#pragma unroll
+      for (int f = 0; f < 2; ++f) {
+        const int rp = prow + 32 * f, rj = jrow + 32 * f;
+        fp[f] = *reinterpret_cast<const u32x4*>(base + 2 * PLANE + rp * ROWB + ((kg ^ swz32(rp)) * 16));
+        fr[f] = *reinterpret_cast<const u32x4*>(base + rj * ROWB + ((kg ^ swz32(rj)) * 16));
+        fq[f] = *reinterpret_cast<const u32x4*>(base + PLANE + rj * ROWB + ((kg ^ swz32(rj)) * 16));
+      }
+#pragma unroll
+      for (int fm = 0; fm < 2; ++fm)
+#pragma unroll
+        for (int f = 0; f < 2; ++f) {
+          acc_r[fm][f] = mfma_32x32x16<true>(fp[fm], fr[f], acc_r[fm][f]);
+          acc_q[fm][f] = mfma_32x32x16<true>(fp[fm], fq[f], acc_q[fm][f]);
+        }
+    }
+  }
+
+  // ---- epilogue: 2 row blocks x 16 rows x 2 adjacent columns per lane, in four parts of 8
+  // rows; within a part every load is issued before the first store
+  const int j0 = tj * TJ + 64 * wj + 2 * c;
+  float* __restrict__ Mz = ptrs.M[z];
+  const char* __restrict__ Gz = reinterpret_cast<const char*>(ptrs.G[z]);
+  char* __restrict__ Xz = reinterpret_cast<char*>(ptrs.X[z]);
+  constexpr int GE = GBF ? 2 : 4, XE = XBF ? 2 : 4;
+  const float s_r = r_scale(d, scal, z);
+  const float cr = b_coef / (s_r * kUnitScale), cq = lr / (kUnitScale * kUnitScale);
+  if (matrix_flagged(info, z)) {        // unspecified factors (possibly NaN) never reach X and M
+#pragma unroll
+    for (int fm = 0; fm < 2; ++fm)
+#pragma unroll
+      for (int f = 0; f < 2; ++f)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) { acc_r[fm][f][v] = 0.f; acc_q[fm][f][v] = 0.f; }
+  }
+#pragma unroll
+  for (int part = 0; part < 4; ++part) {
+    const int fm = part >> 1, hv = part & 1;
+    f32x2 mv[8], gv[8], xv[8];
+    uint32_t gpk[8], xpk[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int v = 8 * hv + u;
+      const int i = ti * TI + 64 * wi + 32 * fm + acc_row(v, lane);
+      mv[u] = f32x2{0.f, 0.f};
+      gpk[u] = 0u; xpk[u] = 0u; gv[u] = f32x2{0.f, 0.f}; xv[u] = f32x2{0.f, 0.f};
+      if (i < d.m && j0 < d.n) {
+        mv[u] = ld_stream<STREAM>(reinterpret_cast<const f32x2*>(Mz + (int64_t)i * d.ldm + j0));
+        if constexpr (GBF) gpk[u] = ld_stream<STREAM>(reinterpret_cast<const uint32_t*>(Gz + ((int64_t)i * d.ldg + j0) * GE));
+        else gv[u] = ld_stream<STREAM>(reinterpret_cast<const f32x2*>(Gz + ((int64_t)i * d.ldg + j0) * GE));
+        if constexpr (XBF) xpk[u] = ld_stream<STREAM>(reinterpret_cast<const uint32_t*>(Xz + ((int64_t)i * d.ldx + j0) * XE));
+        else xv[u] = ld_stream<STREAM>(reinterpret_cast<const f32x2*>(Xz + ((int64_t)i * d.ldx + j0) * XE));
+      }
+    }
+#pragma unroll
+    for (int u = 0; u < 8; ++u) {
+      const int v = 8 * hv + u;
+      const int i = ti * TI + 64 * wi + 32 * fm + acc_row(v, lane);
+      if (i < d.m && j0 < d.n) {
+        f32x2 g = gv[u], x = xv[u];
+        if constexpr (GBF) g = f32x2{bf16_lo(gpk[u]), bf16_hi(gpk[u])};
+        if constexpr (XBF) x = f32x2{bf16_lo(xpk[u]), bf16_hi(xpk[u])};
+        f32x2 mo, xo;
+#pragma unroll
+        for (int e = 0; e < 2; ++e) {
+          mo[e] = a_coef * (mv[u][e] + g[e]) - cr * acc_r[fm][e][v];
+          xo[e] = x[e] - cq * acc_q[fm][e][v];
+        }
+        st_stream<STREAM>(reinterpret_cast<f32x2*>(Mz + (int64_t)i * d.ldm + j0), mo);
+        if constexpr (XBF) st_stream<STREAM>(reinterpret_cast<uint32_t*>(Xz + ((int64_t)i * d.ldx + j0) * XE), pack_bf16_rne(xo[0], xo[1]));
+        else st_stream<STREAM>(reinterpret_cast<f32x2*>(Xz + ((int64_t)i * d.ldx + j0) * XE), xo);
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------
+// Projection and back-projection with every global load direct to LDS (fast precision, bf16
+// gradients, r >= 128):
+//   TRANS = false   out[i][c] = sum_j (M + G)[i][j] Qt[c][j]     P_raw = B Q      (Alg. 1 line 2)
+//   TRANS = true    out[j][c] = sum_i (M + G)[i][j] Pt[c][i]     R = B^T P        (Alg. 1 line 3)
+// One workgroup (8 waves, 2 x 4) computes 128 output rows x NT columns over a K range; wave
+// tile 64 x NT / 4.  Per 32-deep step:
+//   * the factor operand (Qt / Pt: fp16 words, k contiguous) arrives by `dma16` in the swizzled
+//     layout of od_dma.h, two stages;
+//   * the streamed operand arrives raw - the fp32 tile of M and the bf16 tile of G, exactly as
+//     they lie in memory - by `dma16` into three staging stages, so two steps of HBM traffic
+//     (48 KB per CU) are in flight with no staging registers and no compiler-scheduled waits;
+//     all threads then turn one raw stage into fp16 operand words of (M + G) * scale in a
+//     double-buffered operand tile while the matrix cores work on the previous one;
+//   * TRANS: the operand tile keeps memory's [k = i][j] order and the wave reads its
+//     [row = j][8 consecutive k] fragments with the LDS transpose read (`ds_read_b64_tr_b16`:
+//     within 16 lanes, lane c receives element c % 4 of the 8 bytes addressed by lanes
+//     4 e + c / 4, e = 0..3; so lanes 4 e + q address row k0 + e, columns j0 + 4 q .. + 3, and
+//     lane c receives k0 .. k0 + 3 of column j0 + c); rows are 320 bytes apart so that the four
+//     rows a half-wave touches fall into different banks.
+// One barrier per step.  Waits count loads: per step and wave kCB factor loads, then kNR raw loads.
+// ------------------------------------------------------------------------------------
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+
+template <bool TRANS, int NT>
+__global__ __launch_bounds__(512, 1) void k_stream_d(ClassDims d, MatPtrs ptrs, const float* scal, WsArr part, int splits, HalfArr fh) {
+  constexpr int MT = 128, KT = 32, ROWB = 64, SB = 2, SR = 3;
+  constexpr int FN = NT / 128;                                // 32-column accumulator blocks per wave
+  constexpr int B_STAGE = NT * ROWB, RAW_M = MT * KT * 4, RAW_G = MT * KT * 2, RAW_STAGE = RAW_M + RAW_G;
+  constexpr int A_PITCH = TRANS ? 320 : ROWB, A_ROWS = TRANS ? KT : MT, A_BYTES = A_ROWS * A_PITCH;
+  constexpr int OFF_RAW = SB * B_STAGE, OFF_A = OFF_RAW + SR * RAW_STAGE;
+  constexpr int kCB = NT / 16 / 8, kNR = 3;                   // 1 KB chunks per wave: factor stage, raw stage (2 of M, 1 of G)
+  extern __shared__ __align__(16) char lds[];
+  const int Mdim = TRANS ? d.n : d.m, Kdim = TRANS ? d.m : d.n;
+  const int tiles_n = (d.r + NT - 1) / NT;
+  // Workgroups go to the 8 XCDs round robin by their flattened index.  Each XCD gets one
+  // contiguous range of the order (matrix, split, row panel, column tile): the workgroups that
+  // run side by side under one L2 then read the same k range of the same factor operand (and
+  // the column tiles of a row panel the same raw tile), instead of 16 different ones.
+  const int per_z = (int)gridDim.x * (int)gridDim.y;
+  const int logical = xcd_contiguous((int)blockIdx.x + (int)gridDim.x * ((int)blockIdx.y + (int)gridDim.y * (int)blockIdx.z),
+                                     per_z * (int)gridDim.z);
+  const int z = logical / per_z, in_z = logical - z * per_z;
+  const int split = in_z / (int)gridDim.x, bid = in_z - split * (int)gridDim.x;
+  const int tn = bid % tiles_n, tm = bid / tiles_n;
+  const int tid = threadIdx.x, lane = tid & 63;
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int wm = wave >> 2, wn = wave & 3;
+  int kend;
+  const int kbeg = split_begin(Kdim, splits, KT, split, &kend);
+  const int nsteps = kend > kbeg ? (kend - kbeg + KT - 1) / KT : 0;
+  const float sa = b_scale(d, scal, z);
+  const uint32_t lds0 = lds_offset_of(lds);
+  const float* Mz = ptrs.M[z];
+  const uint16_t* Gz = reinterpret_cast<const uint16_t*>(ptrs.G[z]);
+  const uint16_t* Fz = fh.base + (int64_t)z * fh.stride;      // [r][Kdim]
+
+  // ---- factor operand: chunk = 16 rows (output columns) x 64 bytes
+  const uint16_t* fp[kCB];
+  uint32_t foff[kCB];
+#pragma unroll
+  for (int q = 0; q < kCB; ++q) {
+    const int chunk = wave + 8 * q;
+    const int row = chunk * 16 + (lane >> 2), kg = (lane & 3) ^ swz32(row);
+    fp[q] = Fz + (int64_t)min(tn * NT + row, d.r - 1) * Kdim + kg * 8;
+    foff[q] = lds0 + chunk * 1024;
+  }
+  // ---- raw operand: M chunks of 1 KB (not TRANS: 8 rows x 128 B; TRANS: 2 rows x 512 B), G
+  // chunks of 1 KB (16 rows x 64 B; 4 rows x 256 B).  Wave w moves M chunks w and w + 8 and G chunk w.
+  // Addresses are clamped into the matrix; what lies outside is zeroed at conversion.
+  int64_t raw_off[kNR];          // element offset of this lane's 16 bytes at k step 0
+  uint32_t roff[kNR];
+#pragma unroll
+  for (int q = 0; q < kNR; ++q) {
+    const bool isg = q == 2;
+    const int chunk = isg ? wave : wave + 8 * q;
+    int row, col;                // within the tile: row along the matrix's rows, col along its columns
+    if (!TRANS) {
+      row = isg ? chunk * 16 + (lane >> 2) : chunk * 8 + (lane >> 3);
+      col = isg ? (lane & 3) * 8 : (lane & 7) * 4;
+    } else {
+      row = isg ? chunk * 4 + (lane >> 4) : chunk * 2 + (lane >> 5);
+      col = isg ? (lane & 15) * 8 : (lane & 31) * 4;
+    }
+    // not TRANS: rows are output rows (fixed), columns advance with k; TRANS: the other way round
+    const int grow = TRANS ? row : min(tm * MT + row, d.m - 1);
+    const int gcol = TRANS ? min(tm * MT + col, d.n - (isg ? 8 : 4)) : col;
+    raw_off[q] = (int64_t)grow * (isg ? d.ldg : d.ldm) + gcol;
+    roff[q] = lds0 + OFF_RAW + (isg ? RAW_M : 0) + chunk * 1024;
+  }
+  auto issue_f = [&](int step) {
+    const uint32_t boff = (uint32_t)(step % SB) * B_STAGE;
+    const int k0 = min(kbeg + step * KT, Kdim - KT);          // a clamped step only meets zeros of the other operand
+#pragma unroll
+    for (int q = 0; q < kCB; ++q) dma16(fp[q] + k0, foff[q] + boff);
+  };
+  auto issue_raw = [&](int step) {
+    const uint32_t boff = (uint32_t)(step % SR) * RAW_STAGE;
+    const int k0 = kbeg + step * KT;
+#pragma unroll
+    for (int q = 0; q < kNR; ++q) {
+      const bool isg = q == 2;
+      int64_t off;
+      if (!TRANS) off = raw_off[q] + min(k0, d.n - KT);        // clamped like the factor operand
+      else off = raw_off[q] + (int64_t)min(k0, d.m - KT) * (isg ? d.ldg : d.ldm);
+      if (isg) dma16(Gz + off, roff[q] + boff);
+      else dma16(Mz + off, roff[q] + boff);
+    }
+  };
+  // A step whose k range was clamped re-reads earlier k positions: conversion zeroes every k
+  // outside [k0, kend) of the step, and every row / column outside the matrix.
+  auto convert = [&](int step) {
+    const char* raw = lds + OFF_RAW + (step % SR) * RAW_STAGE;
+    char* abuf = lds + OFF_A + (step & 1) * A_BYTES;
+    const int k0 = kbeg + step * KT;
+    const int kld = TRANS ? min(k0, d.m - KT) : min(k0, d.n - KT);       // where the loaded tile really starts
+#pragma unroll
+    for (int h = 0; h < 2; ++h) {
+      const int e = tid + 512 * h;                             // 16 bytes of M = 4 elements each
+      const f32x4 mv = *reinterpret_cast<const f32x4*>(raw + e * 16);
+      const u32x2 gv = *reinterpret_cast<const u32x2*>(raw + RAW_M + e * 8);
+      int row, col;                                            // tile row along the matrix's rows, column along its columns
+      if (!TRANS) { row = e >> 3; col = (e & 7) * 4; }
+      else { row = e >> 5; col = (e & 31) * 4; }
+      const int kk = (TRANS ? row : col) + kld;                // global k of the first element
+      float x[4] = {mv[0] + bf16_lo(gv[0]), mv[1] + bf16_hi(gv[0]), mv[2] + bf16_lo(gv[1]), mv[3] + bf16_hi(gv[1])};
+      bool ok;
+      if (!TRANS) ok = tm * MT + row < d.m && kk >= k0 && kk < kend;       // k advances in groups of 4 inside multiples of 8
+      else ok = kk >= k0 && kk < kend && tm * MT + col < d.n;
+      if (!TRANS && tm * MT + row >= d.m) ok = false;
+      u32x2 w = {0u, 0u};
+      if (ok) { w[0] = pack_f16_sat(x[0] * sa, x[1] * sa); w[1] = pack_f16_sat(x[2] * sa, x[3] * sa); }
+      if (!TRANS) {
+        const int kg = col >> 3;
+        *reinterpret_cast<u32x2*>(abuf + row * ROWB + ((kg ^ swz32(row)) * 16) + (col & 4) * 2) = w;
+      } else {
+        *reinterpret_cast<u32x2*>(abuf + row * A_PITCH + col * 2) = w;
+      }
+    }
+  };
+
+  f32x16 acc[2][FN];
+#pragma unroll
+  for (int fm = 0; fm < 2; ++fm)
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) acc[fm][fn][v] = 0.f;
+
+  if (nsteps > 0) {
+    issue_f(0);
+    issue_raw(0);
+    if (nsteps > 1) issue_raw(1);
+    if (nsteps > 2) issue_raw(2);
+    if (nsteps > 2) __builtin_amdgcn_s_waitcnt(vmcnt_only(2 * kNR));
+    else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    convert(0);
+  }
+  const int arow = wm * 64 + (lane & 31), brow = wn * (NT / 4) + (lane & 31);
+  for (int i = 0; i < nsteps; ++i) {
+    // factor stage i and raw stage i + 1 have landed when only raw stage i + 2 is outstanding
+    if (i + 2 < nsteps) __builtin_amdgcn_s_waitcnt(vmcnt_only(kNR));
+    else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+    if (i + 1 < nsteps) issue_f(i + 1);
+    if (i + 3 < nsteps) issue_raw(i + 3);
+    if (i + 1 < nsteps) convert(i + 1);
+    const char* ab = lds + OFF_A + (i & 1) * A_BYTES;
+    const char* bb = lds + (i % SB) * B_STAGE;
+#pragma unroll
+    for (int kk = 0; kk < KT / 16; ++kk) {
+      const int kg = 2 * kk + (lane >> 5);
+      u32x4 af[2], bf[FN];
+#pragma unroll
+      for (int f = 0; f < 2; ++f) {
+        if constexpr (!TRANS) {
+          const int r0 = arow + 32 * f;
+          af[f] = *reinterpret_cast<const u32x4*>(ab + r0 * ROWB + ((kg ^ swz32(r0)) * 16));
+        } else {
+          // lane l = 16 b + i: addresses row k = 16 kk + 8 (b >> 1) + i / 4 (+ 4), columns j0 + 16 (b & 1) + 4 (i % 4)
+          const int b = lane >> 4, ii = lane & 15;
+          const int k = 16 * kk + 8 * (b >> 1) + (ii >> 2);
+          const int j = wm * 64 + 32 * f + 16 * (b & 1) + 4 * (ii & 3);
+          const char* p0 = ab + k * A_PITCH + j * 2;
+          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p0));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((__attribute__((address_space(3))) s16x4*)(p0 + 4 * A_PITCH));
+          const u32x2 l2 = __builtin_bit_cast(u32x2, lo), h2 = __builtin_bit_cast(u32x2, hi);
+          af[f] = u32x4{l2[0], l2[1], h2[0], h2[1]};
+        }
+      }
+#pragma unroll
+      for (int f = 0; f < FN; ++f) {
+        const int r0 = brow + 32 * f;
+        bf[f] = *reinterpret_cast<const u32x4*>(bb + r0 * ROWB + ((kg ^ swz32(r0)) * 16));
+      }
+#pragma unroll
+      for (int fm = 0; fm < 2; ++fm)
+#pragma unroll
+        for (int fn = 0; fn < FN; ++fn) acc[fm][fn] = mfma_32x32x16<true>(af[fm], bf[fn], acc[fm][fn]);
+    }
+  }
+  const float inv = 1.f / (sa * kUnitScale);
+  float* out = part.base + (int64_t)z * part.stride + (int64_t)split * Mdim * d.r;
+#pragma unroll
+  for (int fm = 0; fm < 2; ++fm)
+#pragma unroll
+    for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+      for (int v = 0; v < 16; ++v) {
+        const int row = tm * MT + wm * 64 + fm * 32 + acc_row(v, lane);
+        const int col = tn * NT + wn * (NT / 4) + fn * 32 + acc_col(lane);
+        if (row < Mdim && col < d.r) out[(int64_t)row * d.r + col] = acc[fm][fn][v] * inv;
+      }
+}
+
 // ====================================================================================
 // launchers
 // ====================================================================================
@@ -1078,6 +1490,16 @@ static void launch_timed(K kernel, dim3 grid, dim3 block, int lds, hipStream_t s
   } else {
     hipLaunchKernelGGL(kernel, grid, block, lds, st, args...);
   }
+}
+
+// Development switch: ORTHDION_KERNELS="efx=old,..." selects the previous kernel of a phase,
+// so that two generations can be timed in one process.  Unset in normal use.
+static bool kernel_choice(const char* phase, const char* value) {
+  const char* env = std::getenv("ORTHDION_KERNELS");
+  if (env == nullptr) return false;
+  char key[64];
+  std::snprintf(key, sizeof(key), "%s=%s", phase, value);
+  return std::strstr(env, key) != nullptr;
 }
 
 template <class K>
@@ -1147,7 +1569,28 @@ static hipError_t proj_g(const ClassDims& d, const MatPtrs& ptrs, Prec prec, con
   }
   return proj_t<TileWide, NumF16, GSrc>(d, ptrs, scal, part, splits, qht, st);
 }
+template <bool TRANS, int NT>
+static hipError_t stream_d_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr part, int splits, HalfArr fh, hipStream_t st) {
+  constexpr int lds = 2 * NT * 64 + 3 * (128 * 32 * 6) + 2 * (TRANS ? 32 * 320 : 128 * 64);
+  hipError_t e = allow_lds(k_stream_d<TRANS, NT>, lds);
+  if (e != hipSuccess) return e;
+  const int Mdim = TRANS ? d.n : d.m;
+  dim3 grid(((Mdim + 127) / 128) * ((d.r + NT - 1) / NT), splits, d.nb);
+  launch_timed(k_stream_d<TRANS, NT>, grid, dim3(512), lds, st, d, ptrs, scal, part, splits, fh);
+  OD_CHECK_LAUNCH();
+  return hipSuccess;
+}
+// shapes the direct-to-LDS contraction takes (fast precision only): bf16 gradients, a rank
+// that fills its 256- or 512-column tiles reasonably, at least one whole 32-deep step
+bool stream_kernel_eligible(const ClassDims& d) {
+  return d.g_bf16 && d.r >= 192 && d.m >= 32 && d.n >= 32 && !kernel_choice("stream", "old");
+}
+int stream_tile_cols(int r) { return r <= 256 ? 256 : 512; }
+
 hipError_t launch_proj(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr part, int splits, HalfArr qht, hipStream_t st) {
+  if (prec == PREC_F16 && stream_kernel_eligible(d))
+    return stream_tile_cols(d.r) == 256 ? stream_d_t<false, 256>(d, ptrs, scal, part, splits, qht, st)
+                                        : stream_d_t<false, 512>(d, ptrs, scal, part, splits, qht, st);
   return d.g_bf16 ? proj_g<SrcBF16>(d, ptrs, prec, scal, part, splits, qht, st) : proj_g<SrcF32>(d, ptrs, prec, scal, part, splits, qht, st);
 }
 
@@ -1176,6 +1619,9 @@ static hipError_t back_g(const ClassDims& d, const MatPtrs& ptrs, Prec prec, con
   return back_t<TileWide, NumF16, GSrc>(d, ptrs, scal, p, part, splits, pht, st);
 }
 hipError_t launch_back(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p, WsArr part, int splits, HalfArr pht, hipStream_t st) {
+  if (prec == PREC_F16 && stream_kernel_eligible(d))
+    return stream_tile_cols(d.r) == 256 ? stream_d_t<true, 256>(d, ptrs, scal, part, splits, pht, st)
+                                        : stream_d_t<true, 512>(d, ptrs, scal, part, splits, pht, st);
   return d.g_bf16 ? back_g<SrcBF16>(d, ptrs, prec, scal, p, part, splits, pht, st) : back_g<SrcF32>(d, ptrs, prec, scal, p, part, splits, pht, st);
 }
 
@@ -1199,24 +1645,31 @@ hipError_t launch_reduce_r(const ClassDims& d, WsArr part, int splits, WsArr out
 }
 
 template <class T, class Num>
-static hipError_t gram_tt(int nb, int rows, int r, WsArr a, WsArr part, int splits, hipStream_t st) {
+static hipError_t gram_tt(int nb, int rows, int r, WsArr a, WsArr part, int splits, hipStream_t st, const ClassDims& d, const float* scal, int side) {
   constexpr int lds = T::template lds_bytes<Num>();
   hipError_t e = allow_lds(k_gram<T, Num>, lds);
   if (e != hipSuccess) return e;
   int tiles = (r + T::NT - 1) / T::NT;
-  hipLaunchKernelGGL((k_gram<T, Num>), dim3(tiles * (tiles + 1) / 2, splits, nb), dim3(T::THREADS), lds, st, rows, r, a, part, splits);
+  hipLaunchKernelGGL((k_gram<T, Num>), dim3(tiles * (tiles + 1) / 2, splits, nb), dim3(T::THREADS), lds, st, rows, r, a, part, splits, d, scal, side);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
 template <class Num>
-static hipError_t gram_t(int nb, int rows, int r, WsArr a, WsArr part, int splits, hipStream_t st) {
+static hipError_t gram_t(int nb, int rows, int r, WsArr a, WsArr part, int splits, hipStream_t st, const ClassDims& d, const float* scal, int side) {
   // few large tiles leave most of the chip idle: use small ones until the grid fills it
   const int big = ((r + 127) / 128) * ((r + 127) / 128) * splits * nb;
-  if (big < 512) return gram_tt<TileSmall, Num>(nb, rows, r, a, part, splits, st);
-  return gram_tt<TileSquare, Num>(nb, rows, r, a, part, splits, st);
+  if (big < 512) return gram_tt<TileSmall, Num>(nb, rows, r, a, part, splits, st, d, scal, side);
+  return gram_tt<TileSquare, Num>(nb, rows, r, a, part, splits, st, d, scal, side);
 }
-hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits, int exact, hipStream_t st) {
-  return exact ? gram_t<NumBF<3>>(nb, rows, r, a, part, splits, st) : gram_t<NumBF<2>>(nb, rows, r, a, part, splits, st);
+hipError_t launch_gram(int nb, int rows, int r, WsArr a, WsArr part, int splits, int mode, hipStream_t st, const ClassDims* d,
+                       const float* scal, int side) {
+  const ClassDims none = {};
+  if (mode == kGramH2) {
+    if (side != 2 && (d == nullptr || scal == nullptr)) return hipErrorInvalidValue;
+    return gram_t<NumH2>(nb, rows, r, a, part, splits, st, d ? *d : none, scal, side);
+  }
+  return mode == kGramBF3 ? gram_t<NumBF<3>>(nb, rows, r, a, part, splits, st, none, nullptr, -1)
+                          : gram_t<NumBF<2>>(nb, rows, r, a, part, splits, st, none, nullptr, -1);
 }
 
 template <class T, class Num, bool DEEP, bool CORR>
@@ -1435,8 +1888,19 @@ static hipError_t efx_n(const ClassDims& d, const MatPtrs& ptrs, const float* sc
 template <bool XBF, bool GBF>
 static hipError_t efx_h_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, const int* info, HalfArr ph, HalfArr rh, HalfArr qh,
                           float a_coef, float b_coef, float lr, hipStream_t st) {
-  constexpr int lds = 2 * 3 * 128 * 80;
   dim3 grid(((d.m + 127) / 128) * ((d.n + 127) / 128), 1, d.nb);
+  const bool stream = d.r > 256 || (int64_t)d.m * d.n * d.nb >= ((int64_t)48 << 20);
+  // ranks that are whole 32-deep steps take the direct-to-LDS kernel
+  if (d.r % 32 == 0 && d.r >= 64 && !kernel_choice("efx", "old")) {
+    constexpr int lds_d = 3 * 3 * 128 * 64;
+    hipError_t e = stream ? allow_lds(k_efx_d<XBF, GBF, true>, lds_d) : allow_lds(k_efx_d<XBF, GBF, false>, lds_d);
+    if (e != hipSuccess) return e;
+    if (stream) launch_timed(k_efx_d<XBF, GBF, true>, grid, dim3(256), lds_d, st, d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr);
+    else launch_timed(k_efx_d<XBF, GBF, false>, grid, dim3(256), lds_d, st, d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr);
+    OD_CHECK_LAUNCH();
+    return hipSuccess;
+  }
+  constexpr int lds = 2 * 3 * 128 * 80;
   // also for sets far beyond the Infinity Cache at any rank: nontemporal stores leave no dirty
   // lines behind for the next kernel to wait on (measured on 8192 x 8192: the step is 2-7 % faster)
   if (d.r > 256 || (int64_t)d.m * d.n * d.nb >= ((int64_t)48 << 20)) launch_timed(k_efx_h<XBF, GBF, true>, grid, dim3(512), lds, st, d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr);

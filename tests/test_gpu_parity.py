@@ -354,8 +354,9 @@ def test_phase_profile_counts_and_leaves_results_alone():
             prof = binding.orthdion_profile_end(gpu.opt.handle)
             assert set(prof) == set(binding.PHASES)
             for name, (ms, count) in prof.items():
-                assert ms > 0.0, name
-                assert count == (2 if name.startswith("chol_") else 2 * 3), (name, count)
+                # the class-wide guard intervals are empty up to r = 256 (there the guard is part of "finish")
+                assert ms > 0.0 or name.startswith("guard_"), name
+                assert count == (2 if name.startswith(("chol_", "guard_")) else 2 * 3), (name, count)
             with pytest.raises(binding.OrthDionError):
                 binding.orthdion_profile_end(gpu.opt.handle)
         runs.append([gpu.fetch(i, with_factors=False) for i in range(nmat)])
