@@ -30,6 +30,7 @@ typedef Tile<256, 256, 32, 2, 2> TileHuge;    // back-projection, r > 256: wave 
 typedef Tile<128, 128, 64, 2, 2> TileSquareDeepK;   // single-part operands: half the k steps at the same LDS footprint
 typedef Tile<64, 64, 64, 2, 2> TileSmall;      // wave tile 32 x 32: small problems that need many workgroups
 
+typedef short s16x4 __attribute__((ext_vector_type(4)));    // result of the LDS transpose read
 constexpr float kUnitScale = 1024.f;           // scale of orthonormal / unit-column factors in fp16
 
 OD_DEV bool pred_on(const Pred& p, int z) {
@@ -1270,11 +1271,9 @@ __global__ __launch_bounds__(256, 2) void k_efx_d(ClassDims d, MatPtrs ptrs, con
 //     rows a half-wave touches fall into different banks.
 // One barrier per step.  Waits count loads: per step and wave kCB factor loads, then kNR raw loads.
 // ------------------------------------------------------------------------------------
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-
-template <bool TRANS, int NT>
+template <bool TRANS, int NT, int SB>
 __global__ __launch_bounds__(512, 1) void k_stream_d(ClassDims d, MatPtrs ptrs, const float* scal, WsArr part, int splits, HalfArr fh) {
-  constexpr int MT = 128, KT = 32, ROWB = 64, SB = 2, SR = 3;
+  constexpr int MT = 128, KT = 32, ROWB = 64, SR = 3;
   constexpr int FN = NT / 128;                                // 32-column accumulator blocks per wave
   constexpr int B_STAGE = NT * ROWB, RAW_M = MT * KT * 4, RAW_G = MT * KT * 2, RAW_STAGE = RAW_M + RAW_G;
   constexpr int A_PITCH = TRANS ? 320 : ROWB, A_ROWS = TRANS ? KT : MT, A_BYTES = A_ROWS * A_PITCH;
@@ -1398,11 +1397,12 @@ __global__ __launch_bounds__(512, 1) void k_stream_d(ClassDims d, MatPtrs ptrs, 
       for (int v = 0; v < 16; ++v) acc[fm][fn][v] = 0.f;
 
   if (nsteps > 0) {
-    issue_f(0);
     issue_raw(0);
+    issue_f(0);
     if (nsteps > 1) issue_raw(1);
+    if (SB == 3 && nsteps > 1) issue_f(1);
     if (nsteps > 2) issue_raw(2);
-    if (nsteps > 2) __builtin_amdgcn_s_waitcnt(vmcnt_only(2 * kNR));
+    if (nsteps > 2) __builtin_amdgcn_s_waitcnt(vmcnt_only(2 * kNR + (SB == 3 ? kCB : 0)));
     else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
@@ -1410,12 +1410,13 @@ __global__ __launch_bounds__(512, 1) void k_stream_d(ClassDims d, MatPtrs ptrs, 
   }
   const int arow = wm * 64 + (lane & 31), brow = wn * (NT / 4) + (lane & 31);
   for (int i = 0; i < nsteps; ++i) {
-    // factor stage i and raw stage i + 1 have landed when only raw stage i + 2 is outstanding
-    if (i + 2 < nsteps) __builtin_amdgcn_s_waitcnt(vmcnt_only(kNR));
+    // factor stage i and raw stage i + 1 have landed when only raw stage i + 2 (and, with three
+    // factor stages, factor stage i + 1 issued before it) is outstanding
+    if (i + 2 < nsteps) __builtin_amdgcn_s_waitcnt(vmcnt_only(kNR + (SB == 3 ? kCB : 0)));
     else __builtin_amdgcn_s_waitcnt(vmcnt_only(0));
     __builtin_amdgcn_s_barrier();
     asm volatile("" ::: "memory");
-    if (i + 1 < nsteps) issue_f(i + 1);
+    if (i + SB - 1 < nsteps) issue_f(i + SB - 1);
     if (i + 3 < nsteps) issue_raw(i + 3);
     if (i + 1 < nsteps) convert(i + 1);
     const char* ab = lds + OFF_A + (i & 1) * A_BYTES;
@@ -1571,12 +1572,13 @@ static hipError_t proj_g(const ClassDims& d, const MatPtrs& ptrs, Prec prec, con
 }
 template <bool TRANS, int NT>
 static hipError_t stream_d_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr part, int splits, HalfArr fh, hipStream_t st) {
-  constexpr int lds = 2 * NT * 64 + 3 * (128 * 32 * 6) + 2 * (TRANS ? 32 * 320 : 128 * 64);
-  hipError_t e = allow_lds(k_stream_d<TRANS, NT>, lds);
+  constexpr int SB = NT == 512 ? 2 : 3;
+  constexpr int lds = SB * NT * 64 + 3 * (128 * 32 * 6) + 2 * (TRANS ? 32 * 320 : 128 * 64);
+  hipError_t e = allow_lds(k_stream_d<TRANS, NT, SB>, lds);
   if (e != hipSuccess) return e;
   const int Mdim = TRANS ? d.n : d.m;
   dim3 grid(((Mdim + 127) / 128) * ((d.r + NT - 1) / NT), splits, d.nb);
-  launch_timed(k_stream_d<TRANS, NT>, grid, dim3(512), lds, st, d, ptrs, scal, part, splits, fh);
+  launch_timed(k_stream_d<TRANS, NT, SB>, grid, dim3(512), lds, st, d, ptrs, scal, part, splits, fh);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }

@@ -126,6 +126,30 @@ def test_teacher_forced_single_steps_bf16():
         assert res["X_beyond_one_spacing"] == 0.0
 
 
+@pytest.mark.parametrize("count,m,n,r", [(24, 1024, 1280, 256), (12, 1152, 1024, 320)])
+def test_large_batches_take_the_full_chip_kernels_and_match_the_oracle(count, m, n, r):
+    """Enough equal matrices that the orthogonalisation runs on its one-workgroup-per-CU kernels
+    (256 x 256 Gram tiles, 128 x 256 tiles of the triangular products): two steps, the oracle
+    restarted from the GPU's state before each, on the first, a middle and the last matrix."""
+    w = synth.Workload(f"batch{count}x{m}x{n}r{r}", tuple([(m, n)] * count), r=r, x_dtype="bf16", steps=2)
+    streams = [synth.make_stream(w, i) for i in range(count)]
+    states = [synth.make_state(w, i) for i in range(count)]
+    gpu = GpuRun(w.shapes, w.r, "bf16", states, mu=w.mu, lr=w.lr)
+    orc = oracle_for(w)
+    probe = (0, count // 2 + 1, count - 1)
+    for t in range(w.steps):
+        before = {i: gpu.fetch(i, with_factors=False) for i in probe}
+        grads = [st.gradient(t) for st in streams]
+        assert gpu.step(grads) == [0] * count
+        for i in probe:
+            b = before[i]
+            o = orc.step(b["X"], grads[i], b["M"].astype(np.float64), b["Q"].astype(np.float64))
+            res = compare_step(gpu.fetch(i), o, b["X"], w.lr)
+            for key in ("M", "Q", "P", "R", "D"):
+                assert res[key] <= 2e-3, (t, i, key, res[key])
+            assert res["X_bits_mismatch"] <= 0.01 and res["X_beyond_one_spacing"] == 0.0, (t, i, res)
+
+
 def test_leading_dimensions_larger_than_n():
     import torch
     m, n, r, ld = 128, 96, 16, 160
