@@ -295,12 +295,18 @@ __global__ __launch_bounds__(T::THREADS) void k_gram(int rows, int r, WsArr a, W
   const int tiles = (r + T::NT - 1) / T::NT;
   // The result is symmetric: only the tiles (tm, tn) with tm <= tn are computed, row by row
   // of the tile grid, and an off-diagonal tile is stored a second time, transposed.
-  // All tiles of one row split read the same rows of A: they get consecutive places on one XCD.
-  const int logical = xcd_contiguous(blockIdx.x + gridDim.x * blockIdx.y, gridDim.x * gridDim.y);
+  // All tiles of one row split read the same rows of A.  Workgroups go to the 8 XCDs round robin
+  // by their flattened index; each XCD gets one contiguous range of the order (matrix, split,
+  // tile), so those tiles run under one L2 and A comes from HBM once.  (Taken per matrix, 20
+  // workgroups spread over all XCDs: the counters showed three times the input fetched.)
+  const int per_z = (int)gridDim.x * (int)gridDim.y;
+  const int flat = xcd_contiguous((int)blockIdx.x + (int)gridDim.x * ((int)blockIdx.y + (int)gridDim.y * (int)blockIdx.z),
+                                  per_z * (int)gridDim.z);
+  const int z = flat / per_z, logical = flat - z * per_z;
   int tm = 0, tn = logical % (int)gridDim.x;
   while (tn >= tiles - tm) { tn -= tiles - tm; ++tm; }
   tn += tm;
-  const int split = logical / (int)gridDim.x, z = blockIdx.z;
+  const int split = logical / (int)gridDim.x;
   SrcF32 s{a.base + (int64_t)z * a.stride, rows, r, r};
   int kend;
   const int kbeg = split_begin(rows, splits, T::KT, split, &kend);

@@ -62,5 +62,18 @@ def device_state(torch, w: synth.Workload, index: int, dev):
         mom = torch.zeros(m, n, device=dev)
     else:
         mom = w.momentum_std * torch.randn(m, n, device=dev, generator=gen)
-    q, _ = torch.linalg.qr(torch.randn(n, w.r, device=dev, generator=gen))
-    return x, mom, q.contiguous()
+    return x, mom, _orthonormal_columns(torch, torch.randn(n, w.r, device=dev, generator=gen))
+
+
+def _orthonormal_columns(torch, a):
+    """Orthonormal basis of the columns of the Gaussian matrix `a` (well conditioned) by two
+    rounds of Cholesky QR in fp64: products on the device, the r x r factorisation on the host.
+    (The device QR of the solver library is avoided: under rocprofv3 counter collection it
+    aborts for some of the benchmark shapes.)"""
+    q = a.double()
+    for _ in range(2):
+        gram = (q.T @ q).cpu()
+        lower = torch.linalg.cholesky(gram)
+        w = torch.linalg.solve_triangular(lower, torch.eye(gram.shape[0], dtype=torch.float64), upper=False).T
+        q = q @ w.to(a.device)
+    return q.float().contiguous()
