@@ -1101,12 +1101,12 @@ __global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, con
 // (G, X) row segments, as in k_efx_h.  Two workgroups per CU (72 KB of LDS each): one streams
 // M, G, X while the other multiplies.
 // ------------------------------------------------------------------------------------
-template <bool XBF, bool GBF, bool STREAM>
-__global__ __launch_bounds__(256, 2) void k_efx_d(ClassDims d, MatPtrs ptrs, const float* scal, const int* info, HalfArr ph, HalfArr rh,
-                                                  HalfArr qh, float a_coef, float b_coef, float lr) {
-  constexpr int TI = 128, TJ = 128, KT = 32, ROWB = KT * 2, ST = 3;
-  constexpr int PLANE = 128 * ROWB, STAGE = 3 * PLANE;       // R | Q | P
-  constexpr int CPW = 3 * 8 / 4;                              // 1 KB chunks per wave and stage
+template <bool XBF, bool GBF, bool STREAM, int WI>
+__global__ __launch_bounds__(128 * WI, (WI == 2 ? 2 : 1)) void k_efx_d(ClassDims d, MatPtrs ptrs, const float* scal, const int* info, HalfArr ph,
+                                                                     HalfArr rh, HalfArr qh, float a_coef, float b_coef, float lr) {
+  constexpr int TI = 64 * WI, TJ = 128, KT = 32, ROWB = KT * 2, ST = 3, NW = 2 * WI;
+  constexpr int PLANE = 128 * ROWB, STAGE = 2 * PLANE + TI * ROWB;       // R | Q | P
+  constexpr int CPW = (16 + TI / 16) / NW;                    // 1 KB chunks per wave and stage
   extern __shared__ __align__(16) char lds[];
   const int tiles_i = (d.m + TI - 1) / TI;
   int ti = blockIdx.x % tiles_i, tj = blockIdx.x / tiles_i;
@@ -1123,7 +1123,7 @@ __global__ __launch_bounds__(256, 2) void k_efx_d(ClassDims d, MatPtrs ptrs, con
   const int z = blockIdx.z;
   const int tid = threadIdx.x, lane = tid & 63, c = lane & 31;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wi = wave & 1, wj = wave >> 1;
+  const int wi = wave % WI, wj = wave / WI;
 
   // ---- this lane's share of every stage: chunk = 16 LDS rows of one of the three tiles
   const uint16_t* gp[CPW];
@@ -1131,8 +1131,8 @@ __global__ __launch_bounds__(256, 2) void k_efx_d(ClassDims d, MatPtrs ptrs, con
   const uint32_t lds0 = lds_offset_of(lds);
 #pragma unroll
   for (int q = 0; q < CPW; ++q) {
-    const int chunk = wave + 4 * q;                 // 0..7 R, 8..15 Q, 16..23 P
-    const int which = chunk >> 3, rel = chunk & 7;
+    const int chunk = wave + NW * q;                // 0..7 R, 8..15 Q, 16.. P
+    const int which = chunk < 16 ? chunk >> 3 : 2, rel = chunk < 16 ? chunk & 7 : chunk - 16;
     const int row = rel * 16 + (lane >> 2), slot = lane & 3;
     const int kg = slot ^ swz32(row);
     int grow;
@@ -1724,7 +1724,7 @@ static hipError_t sgemm_tt(int nb, const SgemmArgs& g, hipStream_t st) {
 template <class Num, class DirA>
 static hipError_t sgemm_t(int nb, const SgemmArgs& g, hipStream_t st) {
   const int big = ((g.Mc + 127) / 128) * ((g.Nc + 127) / 128) * nb * g.nq;
-  if (big < 512) return sgemm_tt<TileSmall, Num, DirA>(nb, g, st);
+  if (big < 256) return sgemm_tt<TileSmall, Num, DirA>(nb, g, st);      // one 128 x 128 tile per CU fills the chip
   return sgemm_tt<TileSquare, Num, DirA>(nb, g, st);
 }
 static hipError_t sgemm(int nb, const SgemmArgs& g, bool a_kc, int exact, hipStream_t st) {
@@ -1753,7 +1753,7 @@ static hipError_t sgemm_pair(int nb, const SgemmArgs& g1, const SgemmArgs& g2, h
   if (!has2) return sgemm(nb, g1, false, 1, st);
   if (!has1) return sgemm(nb, g2, true, 1, st);
   const int big = (((g1.Mc + 127) / 128) * ((g1.Nc + 127) / 128) + ((g2.Mc + 127) / 128) * ((g2.Nc + 127) / 128)) * nb;
-  if (big < 512) return sgemm_pair_tt<TileSmall>(nb, g1, g2, st);
+  if (big < 256) return sgemm_pair_tt<TileSmall>(nb, g1, g2, st);
   return sgemm_pair_tt<TileSquare>(nb, g1, g2, st);
 }
 
@@ -1900,11 +1900,24 @@ static hipError_t efx_h_t(const ClassDims& d, const MatPtrs& ptrs, const float* 
   const bool stream = d.r > 256 || (int64_t)d.m * d.n * d.nb >= ((int64_t)48 << 20);
   // ranks that are whole 32-deep steps take the direct-to-LDS kernel
   if (d.r % 32 == 0 && d.r >= 64 && !kernel_choice("efx", "old")) {
+    // r > 256: 256-row tiles (one 8-wave workgroup per CU) while they still fill the chip twice:
+    // a third less operand traffic into LDS per product than 128-row tiles
+    const int64_t tall = (int64_t)((d.m + 255) / 256) * ((d.n + 127) / 128) * d.nb;
+    if (d.r > 256 && tall >= 512 && !kernel_choice("efx", "dma128")) {
+      constexpr int lds_t = 3 * (2 * 128 + 256) * 64;
+      hipError_t e = stream ? allow_lds(k_efx_d<XBF, GBF, true, 4>, lds_t) : allow_lds(k_efx_d<XBF, GBF, false, 4>, lds_t);
+      if (e != hipSuccess) return e;
+      const dim3 tgrid(((d.m + 255) / 256) * ((d.n + 127) / 128), 1, d.nb);
+      if (stream) launch_timed(k_efx_d<XBF, GBF, true, 4>, tgrid, dim3(512), lds_t, st, d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr);
+      else launch_timed(k_efx_d<XBF, GBF, false, 4>, tgrid, dim3(512), lds_t, st, d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr);
+      OD_CHECK_LAUNCH();
+      return hipSuccess;
+    }
     constexpr int lds_d = 3 * 3 * 128 * 64;
-    hipError_t e = stream ? allow_lds(k_efx_d<XBF, GBF, true>, lds_d) : allow_lds(k_efx_d<XBF, GBF, false>, lds_d);
+    hipError_t e = stream ? allow_lds(k_efx_d<XBF, GBF, true, 2>, lds_d) : allow_lds(k_efx_d<XBF, GBF, false, 2>, lds_d);
     if (e != hipSuccess) return e;
-    if (stream) launch_timed(k_efx_d<XBF, GBF, true>, grid, dim3(256), lds_d, st, d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr);
-    else launch_timed(k_efx_d<XBF, GBF, false>, grid, dim3(256), lds_d, st, d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr);
+    if (stream) launch_timed(k_efx_d<XBF, GBF, true, 2>, grid, dim3(256), lds_d, st, d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr);
+    else launch_timed(k_efx_d<XBF, GBF, false, 2>, grid, dim3(256), lds_d, st, d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr);
     OD_CHECK_LAUNCH();
     return hipSuccess;
   }
