@@ -35,9 +35,9 @@ SWEEP = [("C2", 30), ("C4", 10), ("C5-r16", 30), ("C5-r256", 20), ("C5-r1024", 1
 # Kernel groups: the phases orthdion_profile_begin can bracket, gathered by the kernel that
 # does their work, and the name prefixes of those kernels in a rocprofv3 counter summary.
 GROUPS = {
-    "k_proj": (["proj"], ["od::k_proj<"]),
-    "k_back": (["back"], ["od::k_back<"]),
-    "k_efx": (["efx"], ["od::k_efx_h<", "od::k_efx<"]),
+    "k_proj": (["proj"], ["od::k_proj<", "od::k_stream_d<false"]),
+    "k_back": (["back"], ["od::k_back<", "od::k_stream_d<true"]),
+    "k_efx": (["efx"], ["od::k_efx_d<", "od::k_efx_h<", "od::k_efx<"]),
     "k_gram (first pass)": (["gram_left", "gram_right"], []),
     "cholesky chain (k_chol256, k_sgemm_pair)": (["chol_left", "chol_right"], ["od::k_chol256", "od::k_sgemm", "od::k_zero_pair"]),
     "rest of orth (k_apply, k_gram, k_corr | ColNorm)": (["orth_left", "orth_right", "guard_left", "guard_right", "finish_left", "finish_right"],
@@ -239,7 +239,12 @@ def measure(torch, binding, synth, dev, name, variant, precision, steps, warmup,
     dom_launches = sum(prof[p][1] for p in GROUPS[dominant][0] if p in prof) // steps
 
     fast_path = precision == "fast" or (precision == "auto" and w.x_dtype == "bf16")
-    kname = dominant if dominant != "k_efx" else ("k_efx_h" if fast_path else "k_efx")
+    # the kernel the library's launchers pick for this group (same rules as od_kernels.hip)
+    kname = dominant
+    if fast_path and dominant == "k_efx":
+        kname = "k_efx_d" if (w.r % 32 == 0 and w.r >= 64) else "k_efx_h"
+    if fast_path and dominant in ("k_proj", "k_back") and w.x_dtype == "bf16" and w.r >= 192:
+        kname = "k_stream_d<%s>" % ("false" if dominant == "k_proj" else "true")
     nbytes, flops = group_work(w, variant, dominant)
     hbm_frac_k = nbytes / (dom_ms * 1e-3) / 1e9 / HBM_PEAK_GBS
     mfma_frac_k = flops / (dom_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS
