@@ -297,8 +297,9 @@ OD_DEV int diag_tile_factor(f32x16& d_io, f32x16& zt_out, int lane) {
   return bad;
 }
 
-__global__ __launch_bounds__(kCholThreads) void k_chol256(CholArgs a) {
-  extern __shared__ __align__(16) char lds_raw[];
+// The factorisation of block `a.blk` of matrix `z` by one workgroup of kCholThreads threads;
+// `lds_raw`: kCholLds bytes.
+OD_DEV void chol256_block(const CholArgs& a, int z, char* lds_raw) {
   float* Wt = reinterpret_cast<float*>(lds_raw);                         // W_JJ^T, [i][k], buffer J & 1
   char* panel = lds_raw + kCholOffPanel;                                 // T(J, K)^T pre-split, one tile per K
   char* vpanel = lds_raw + kCholOffVPanel;                               // V(J, I) pre-split, one tile per I; before
@@ -307,7 +308,7 @@ __global__ __launch_bounds__(kCholThreads) void k_chol256(CholArgs a) {
   int* s_ready = published + kCNT;                                       // S(J, J+1) has its last update and is in the stash
   char* stash = lds_raw + kCholOffStash;                                 // buffer J & 1
 
-  const int z = blockIdx.x, tid = threadIdx.x, lane = tid & 63;
+  const int tid = threadIdx.x, lane = tid & 63;
   // uniform over the workgroup, before any barrier or LDS hand-off
   if (a.pred.scal != nullptr && (a.pred.scal[z * kScalPerMat + a.pred.slot] > a.pred.thr) != (a.pred.want != 0)) return;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -555,6 +556,11 @@ __global__ __launch_bounds__(kCholThreads) void k_chol256(CholArgs a) {
     // the next step rewrites the panels and the other Wt buffer
     lds_barrier();
   }
+}
+
+__global__ __launch_bounds__(kCholThreads) void k_chol256(CholArgs a) {
+  extern __shared__ __align__(16) char lds_raw[];
+  chol256_block(a, blockIdx.x, lds_raw);
 }
 
 }  // namespace od

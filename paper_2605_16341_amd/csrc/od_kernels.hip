@@ -658,6 +658,25 @@ __global__ __launch_bounds__(T::THREADS) void k_sgemm_pair(SgemmArgs g1, SgemmAr
   else sgemm_tile<T, Num, DirA2>(g2, blockIdx.x - tiles1, blockIdx.z, lds);
 }
 
+// Look-ahead of the blocked factorisation: workgroup 0 of a matrix factors the next diagonal
+// block (whose own update has already been applied) while the others apply the rest of the
+// current block's trailing update (g1, g2) and finish block column p of the inverse (g3).
+// The products run on the first T::THREADS threads of their workgroups; the surplus waves end
+// at once (a barrier counts only the waves that are still alive).
+template <class T>
+__global__ __launch_bounds__(kCholThreads) void k_chol_ahead(CholArgs ca, SgemmArgs g1, SgemmArgs g2, SgemmArgs g3, int tiles1, int tiles2) {
+  extern __shared__ __align__(16) char lds[];
+  typedef NumBF<3> Num;
+  if (blockIdx.x == 0) {
+    chol256_block(ca, blockIdx.z, lds);
+    return;
+  }
+  if ((int)threadIdx.x >= T::THREADS) return;
+  const int bx = (int)blockIdx.x - 1;
+  if (bx < tiles1) sgemm_tile<T, Num, KSF>(g1, bx, blockIdx.z, lds);
+  else if (bx < tiles1 + tiles2) sgemm_tile<T, Num, KSF>(g2, bx - tiles1, blockIdx.z, lds);
+  else sgemm_tile<T, Num, KC>(g3, bx - tiles1 - tiles2, blockIdx.z, lds);
+}
 
 constexpr int kLeaf = kCholMax;   // diagonal block of the blocked factorisation
 
@@ -1781,17 +1800,23 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp
     hipLaunchKernelGGL(k_zero_pair, dim3(blocks, nb), dim3(256), 0, st, t, w, count, pred);
     OD_CHECK_LAUNCH();
   }
-  // Step p: factor the diagonal block (T_pp, W_pp), then two launches of two independent
-  // products each:
+  // Step p: the diagonal block (T_pp, W_pp) is factored; then
   //   (1) the panel of the factor      T(p, rest) = W_pp^T G(p, rest)
-  //       and, for the inverse,        tmp(0:p, p) = T(0:p, p) W_pp
-  //   (2) the trailing update          G(rest, rest) -= T(p, rest)^T T(p, rest)
-  //       and block column p of W      W(0:p, p) = -W(0:p, 0:p) tmp(0:p, p)
-  // (the inverse of [[A, b], [0, c]] is [[A^-1, -A^-1 b c^-1], [0, c^-1]]).
+  //       and, for the inverse,        tmp(0:p, p) = T(0:p, p) W_pp              (one launch)
+  //   (2) the update of the next diagonal block alone
+  //                                    G(p+1, p+1) -= T(p, p+1)^T T(p, p+1)      (one short launch)
+  //   (3) one launch: the factorisation of block p + 1, beside the rest of the trailing update
+  //       G(rest, rest) -= T(p, rest)^T T(p, rest) and block column p of the inverse,
+  //       W(0:p, p) = -W(0:p, 0:p) tmp(0:p, p)
+  // (the inverse of [[A, b], [0, c]] is [[A^-1, -A^-1 b c^-1], [0, c^-1]]).  The serial chain is
+  // the factorisations and launches (1), (2); the bulk of the update hides behind a factorisation.
+  auto tiles_of = [](const SgemmArgs& g, int mt) { return g.Mc > 0 && g.Nc > 0 && g.Kc > 0 ? ((g.Mc + mt - 1) / mt) * ((g.Nc + mt - 1) / mt) : 0; };
   for (int p = 0; p < nblk; ++p) {
-    ca.blk = p;
-    hipLaunchKernelGGL(k_chol256, dim3(nb), dim3(kCholThreads), kCholLds, st, ca);
-    OD_CHECK_LAUNCH();
+    if (p == 0) {
+      ca.blk = 0;
+      hipLaunchKernelGGL(k_chol256, dim3(nb), dim3(kCholThreads), kCholLds, st, ca);
+      OD_CHECK_LAUNCH();
+    }
     const int o = p * kLeaf, o1 = (p + 1) * kLeaf, rest = r > o1 ? r - o1 : 0;
     const int bw = r - o < kLeaf ? r - o : kLeaf;       // width of block column p
     SgemmArgs panel = {}, prod = {}, trail = {}, wcol = {};
@@ -1815,7 +1840,34 @@ hipError_t launch_cholinv(int nb, int r, WsArr gram, WsArr t, WsArr w, WsArr tmp
       wcol.Mc = o; wcol.Nc = bw; wcol.Kc = o; wcol.alpha = -1.f; wcol.beta = 0.f;
     }
     if ((e = sgemm_pair(nb, panel, prod, st)) != hipSuccess) return e;
-    if ((e = sgemm_pair(nb, trail, wcol, st)) != hipSuccess) return e;
+    if (rest == 0) {
+      if ((e = sgemm_pair(nb, trail, wcol, st)) != hipSuccess) return e;
+      continue;
+    }
+    // the trailing update in three pieces: the next diagonal block, the columns right of it
+    // (all rows), and the rows below it (its own columns)
+    const int nb1 = rest < kLeaf ? rest : kLeaf, o2 = o1 + nb1;
+    SgemmArgs diag = trail, right = trail, below = trail;
+    diag.Mc = nb1; diag.Nc = nb1;
+    right.b_c0 = o2; right.c_c0 = o2; right.Nc = rest - nb1;
+    below.a_r0 = o2; below.c_r0 = o2; below.Mc = rest - nb1; below.Nc = nb1;
+    if ((e = sgemm(nb, diag, false, 1, st)) != hipSuccess) return e;
+    ca.blk = p + 1;
+    const int big = (tiles_of(right, 128) + tiles_of(below, 128) + tiles_of(wcol, 128)) * nb;
+    if (big < 256) {
+      typedef TileSmall T;
+      constexpr int lds = T::lds_bytes<NumBF<3>>() > kCholLds ? T::lds_bytes<NumBF<3>>() : kCholLds;
+      if ((e = allow_lds(k_chol_ahead<T>, lds)) != hipSuccess) return e;
+      const int t1 = tiles_of(right, T::MT), t2 = tiles_of(below, T::MT), t3 = tiles_of(wcol, T::MT);
+      hipLaunchKernelGGL(k_chol_ahead<T>, dim3(1 + t1 + t2 + t3, 1, nb), dim3(kCholThreads), lds, st, ca, right, below, wcol, t1, t2);
+    } else {
+      typedef TileSquare T;
+      constexpr int lds = T::lds_bytes<NumBF<3>>() > kCholLds ? T::lds_bytes<NumBF<3>>() : kCholLds;
+      if ((e = allow_lds(k_chol_ahead<T>, lds)) != hipSuccess) return e;
+      const int t1 = tiles_of(right, T::MT), t2 = tiles_of(below, T::MT), t3 = tiles_of(wcol, T::MT);
+      hipLaunchKernelGGL(k_chol_ahead<T>, dim3(1 + t1 + t2 + t3, 1, nb), dim3(kCholThreads), lds, st, ca, right, below, wcol, t1, t2);
+    }
+    OD_CHECK_LAUNCH();
   }
   return hipSuccess;
 }
