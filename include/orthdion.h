@@ -127,6 +127,26 @@ int orthdion_step(orthdion_handle h, void* const* X, const void* const* G, float
  * at column -k. */
 int orthdion_get_info(orthdion_handle h, int32_t* info_host, void* stream);
 
+/* Waits for `stream`, then copies the per-matrix warning bits of the last step to
+ * warn_host[nmat] (host array).  A warning does not invalidate the step: the results are
+ * delivered, but with less accuracy than the precision mode promises.  The fast precision
+ * reads B = M + G (Alg. 1 line 1) and R (line 3) as fp16 under power-of-two scales that are
+ * derived from 32 sampled rows of B; the pass that sees every entry anyway checks the sample.
+ *   ORTHDION_WARN_B_CLIPPED     an entry of B exceeded the fp16 range under its scale and was
+ *                               clipped in the projection and back-projection
+ *   ORTHDION_WARN_R_CLIPPED     the same for an entry of R in the error-feedback product
+ *   ORTHDION_WARN_B_SCALE_BLIND every sampled row of B was zero although B is not: no scale
+ *                               was applied, small entries may have been flushed
+ *   ORTHDION_WARN_WAIT_EXPIRED  a bounded wait inside the Cholesky kernel ran out (a defect,
+ *                               not a property of the data); orthdion_get_info reports the
+ *                               matrix as broken down as well
+ * Exact precision never clips (no scale is involved); its words stay zero. */
+#define ORTHDION_WARN_B_CLIPPED 1u
+#define ORTHDION_WARN_R_CLIPPED 2u
+#define ORTHDION_WARN_B_SCALE_BLIND 4u
+#define ORTHDION_WARN_WAIT_EXPIRED 8u
+int orthdion_get_warnings(orthdion_handle h, uint32_t* warn_host, void* stream);
+
 /* Debug / test hook: byte offsets inside the workspace of what the last step left for
  * matrix `index`: P (m x r fp32), R (n x r fp32), and the two triangular factors of each
  * CholeskyQR2 orthogonalisation (r x r fp32 each; orth(.)'s triangular factor is

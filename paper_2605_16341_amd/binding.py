@@ -29,7 +29,7 @@ EXPORTS = ["orthdion_create", "orthdion_workspace_bytes", "orthdion_set_lr", "or
            "orthdion_set_variant", "orthdion_step", "orthdion_get_info", "orthdion_workspace_layout",
            "orthdion_profile_begin", "orthdion_profile_end", "orthdion_set_diagnostics",
            "orthdion_get_diagnostics", "orthdion_rank_policy", "orthdion_resize_q", "orthdion_strerror",
-           "orthdion_destroy", "orthdion_step_static", "orthdion_static_scratch_bytes"]
+           "orthdion_destroy", "orthdion_step_static", "orthdion_static_scratch_bytes", "orthdion_get_warnings"]
 
 DIAG = ["b_norm", "r_norm", "tracking_error", "residual_ratio", "inner", "nu", "erank", "g_norm"]
 ORTHDION_NDIAG = len(DIAG)
@@ -102,6 +102,8 @@ def load() -> ctypes.CDLL:
     lib.orthdion_static_scratch_bytes.restype = sz
     lib.orthdion_get_info.argtypes = [vp, ctypes.POINTER(ctypes.c_int32), vp]
     lib.orthdion_get_info.restype = ctypes.c_int
+    lib.orthdion_get_warnings.argtypes = [vp, ctypes.POINTER(ctypes.c_uint32), vp]
+    lib.orthdion_get_warnings.restype = ctypes.c_int
     lib.orthdion_workspace_layout.argtypes = [vp, ctypes.c_int32] + [ctypes.POINTER(sz)] * 6
     lib.orthdion_workspace_layout.restype = ctypes.c_int
     lib.orthdion_profile_begin.argtypes = [vp, ctypes.c_uint32, ctypes.c_int32]
@@ -206,6 +208,15 @@ def orthdion_get_info(handle: int, nmat: int, stream: int = 0) -> List[int]:
     return list(out)
 
 
+WARN_B_CLIPPED, WARN_R_CLIPPED, WARN_B_SCALE_BLIND, WARN_WAIT_EXPIRED = 1, 2, 4, 8
+
+
+def orthdion_get_warnings(handle: int, nmat: int, stream: int = 0) -> List[int]:
+    out = (ctypes.c_uint32 * nmat)()
+    _check(load().orthdion_get_warnings(handle, out, ctypes.c_void_p(stream)))
+    return list(out)
+
+
 def orthdion_workspace_layout(handle: int, index: int) -> dict:
     vals = [ctypes.c_size_t() for _ in range(6)]
     _check(load().orthdion_workspace_layout(handle, int(index), *[ctypes.byref(v) for v in vals]))
@@ -305,6 +316,10 @@ class OrthDion:
     def info(self, stream=None) -> List[int]:
         st = stream if stream is not None else self._torch.cuda.current_stream().cuda_stream
         return orthdion_get_info(self.handle, self.nmat, st)
+
+    def warnings(self, stream=None) -> List[int]:
+        st = stream if stream is not None else self._torch.cuda.current_stream().cuda_stream
+        return orthdion_get_warnings(self.handle, self.nmat, st)
 
     def set_diagnostics(self, enable: bool) -> None:
         orthdion_set_diagnostics(self.handle, enable)

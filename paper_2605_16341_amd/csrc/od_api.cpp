@@ -563,7 +563,7 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     const bool back_direct = b.splits_back == 1;
     OD_TRY(od::launch_back(d, v.ptrs, prec, v.scal, v.pa, back_direct ? v.ra : v.part, b.splits_back, v.pht, st));
     OD_PHASE_BEGIN(ORTHDION_PHASE_BACK_REDUCE);
-    if (fast) OD_TRY(od::launch_reduce_r(d, back_direct ? v.ra : v.part, b.splits_back, v.ra, v.rh, v.scal, st));
+    if (fast) OD_TRY(od::launch_reduce_r(d, back_direct ? v.ra : v.part, b.splits_back, v.ra, v.rh, v.scal, v.info, st));
     else if (!back_direct) OD_TRY(od::launch_reduce(d.nb, v.part, b.splits_back, (int64_t)d.n * d.r, v.ra, st));
     OD_PHASE_END(ORTHDION_PHASE_BACK_REDUCE);
     if (diag) OD_TRY(od::launch_diag_cols(d.nb, d.n, d.r, v.ra, v.part, b.slabs, v.dacc, st));
@@ -732,6 +732,24 @@ extern "C" int orthdion_get_info(orthdion_handle h, int32_t* info_host, void* st
     else if (w[1] != 0) v = -w[1];
     else if (w[2] != 0) v = -w[2];
     info_host[i] = v;
+  }
+  return ORTHDION_OK;
+}
+
+extern "C" int orthdion_get_warnings(orthdion_handle h, uint32_t* warn_host, void* stream) {
+  if (!h || !warn_host) return ORTHDION_E_NULL_PTR;
+  if (!h->last_ws) return ORTHDION_E_NO_STEP;
+  hipStream_t st = reinterpret_cast<hipStream_t>(stream);
+  const int nmat = (int)h->mats.size();
+  std::vector<int> raw;
+  const int rc_alloc = no_throw([&] { raw.resize((size_t)nmat * od::kInfoPerMat); return (int)ORTHDION_OK; });
+  if (rc_alloc != ORTHDION_OK) return rc_alloc;
+  const char* ws = reinterpret_cast<const char*>(h->last_ws);
+  OD_TRY(hipMemcpyAsync(raw.data(), ws + h->off_info, raw.size() * sizeof(int), hipMemcpyDeviceToHost, st));
+  OD_TRY(hipStreamSynchronize(st));
+  for (int i = 0; i < nmat; ++i) {
+    const Batch& b = h->batches[h->batch_of[i]];
+    warn_host[i] = (uint32_t)raw[(size_t)(b.slot_base + h->slot_of[i]) * od::kInfoPerMat + od::kWarnSlot];
   }
   return ORTHDION_OK;
 }

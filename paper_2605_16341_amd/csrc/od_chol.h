@@ -181,12 +181,15 @@ OD_DEV void lds_signal_add(int* word, int lane) {
   __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
   if (lane == 0) __hip_atomic_fetch_add(word, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
 }
-OD_DEV void lds_wait_ge(int* word, int target) {
+// Returns false when the bound ran out (the caller reports it; the kernel still ends).
+OD_DEV bool lds_wait_ge(int* word, int target) {
+  bool seen = false;
   for (int spins = 0; spins < kCholSpinLimit; ++spins) {
-    if (__hip_atomic_load(word, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= target) break;
+    if (__hip_atomic_load(word, __ATOMIC_ACQUIRE, __HIP_MEMORY_SCOPE_WORKGROUP) >= target) { seen = true; break; }
     __builtin_amdgcn_s_sleep(1);
   }
   __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+  return seen;
 }
 
 // ---------------------------------------------------------------------------------------
@@ -490,13 +493,14 @@ OD_DEV void chol256_block(const CholArgs& a, int z, char* lds_raw) {
     }
   }
   lds_barrier();
+  bool expired = false;
   for (int J = 0; J < nt; ++J) {
     if (diag_wave) {
       // ---- the serial chain stays in this wave: T(J, J+1) = W_JJ^T S(J, J+1) from the stash,
       // tile (J+1, J+1) -= T^T T (both fp32 products with the accumulator as k-side operand,
       // see panel_tile), then its factorisation.  The workers form T(J, J+1) again for the panel.
       if (J + 1 < nt) {
-        if (J > 0) lds_wait_ge(s_ready + J, 1);
+        if (J > 0 && !lds_wait_ge(s_ready + J, 1)) expired = true;
         const f32x16 sj = load_dtile(stash + (J & 1) * 4096, lane);
         f32x16 dn = load_dtile(vpanel + (J + 1) * kPTile, lane);
         const float* wt = Wt + (J & 1) * kCTileF;
@@ -538,7 +542,7 @@ OD_DEV void chol256_block(const CholArgs& a, int z, char* lds_raw) {
       }
       // ---- (c) once all nt - 1 tiles of the step are published:
       // S(I, K) -= T(J, I)^T T(J, K) for J < I < K;  S'(K, I) += T(J, K)^T V(J, I) for I <= J < K
-      lds_wait_ge(published + J, nt - 1);
+      if (!lds_wait_ge(published + J, nt - 1)) expired = true;
 #pragma unroll
       for (int s = 0; s < kCSlots; ++s) {
         const int I = (int)(ownI >> (4 * s)) & 15, K = (int)(ownK >> (4 * s)) & 15;
@@ -555,6 +559,12 @@ OD_DEV void chol256_block(const CholArgs& a, int z, char* lds_raw) {
     }
     // the next step rewrites the panels and the other Wt buffer
     lds_barrier();
+  }
+  // a wait that ran out means a tile was used before its producer finished: the factors of this
+  // matrix are wrong, which the breakdown word says (the warning bit says why)
+  if (expired && lane == 0) {
+    atomicOr(&a.info[z * kInfoPerMat + kWarnSlot], kWarnWaitExpired);
+    atomicCAS(&a.info[z * kInfoPerMat + a.info_slot], 0, o + 1);
   }
 }
 

@@ -55,8 +55,14 @@ struct Pred {
 constexpr int kScalPerMat = 40;
 constexpr int kScalSample = 8;
 // info layout per matrix (ints): [0] left-factor breakdown column, [1] right-factor
-// breakdown column (1-based, 0 = none), [2] zero-column flag of ColNorm, [3] spare
+// breakdown column (1-based, 0 = none), [2] zero-column flag of ColNorm, [3] warning bits
+// (results are delivered, but with less accuracy than the precision mode promises)
 constexpr int kInfoPerMat = 4;
+constexpr int kWarnSlot = 3;
+constexpr int kWarnBClipped = 1;       // an entry of B = M + G exceeded the fp16 range under its sampled scale
+constexpr int kWarnRClipped = 2;       // the same for R = B^T P
+constexpr int kWarnBScaleBlind = 4;    // the sampled rows of B were all zero although B is not
+constexpr int kWarnWaitExpired = 8;    // a bounded wait inside the Cholesky kernel ran out
 // Second CholeskyQR pass: up to kFirstOrderDeviation (largest entry of the first pass's
 // G - I) the pass is the first-order correction I - Phi(E), whose O(E^2) remainder then stays
 // near the rounding of the measurement itself; above it, up to kMaxGramDeviation, a second
@@ -90,7 +96,7 @@ hipError_t launch_back(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const
 hipError_t launch_reduce(int nb, WsArr part, int splits, int64_t count, WsArr out, hipStream_t st, Pred pred = Pred{nullptr, 0, 0.f, 0});
 // the same for R (n x r), also written as pre-scaled fp16 [n][r]; with one split `part` may be
 // `out` itself (the back-projection wrote R in place): then only the fp16 copy is written
-hipError_t launch_reduce_r(const ClassDims& d, WsArr part, int splits, WsArr out, HalfArr rh, const float* scal, hipStream_t st);
+hipError_t launch_reduce_r(const ClassDims& d, WsArr part, int splits, WsArr out, HalfArr rh, const float* scal, int* info, hipStream_t st);
 
 // Gram partials: part[split][r][r] = A[k-range, :]^T A[k-range, :], A is rows x r (ld r)
 // Operand format (`mode`): kGramBF2 / kGramBF3 two- / three-way split bf16 (3 / 6 products,
@@ -157,8 +163,9 @@ hipError_t launch_colnorm(int nb, int n, int r, WsArr rr, const MatPtrs& ptrs, W
 hipError_t launch_efx(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, const int* info, WsArr p,
                       WsArr rr, float a_coef, float b_coef, float lr, hipStream_t st);
 
-// the same pass from the pre-scaled fp16 factors (fast precision)
-hipError_t launch_efx_h(const ClassDims& d, const MatPtrs& ptrs, const float* scal, const int* info, HalfArr ph, HalfArr rh,
+// the same pass from the pre-scaled fp16 factors (fast precision); also checks every entry of
+// B against its sampled fp16 scale and sets the warning bits of `info`
+hipError_t launch_efx_h(const ClassDims& d, const MatPtrs& ptrs, const float* scal, int* info, HalfArr ph, HalfArr rh,
                         HalfArr qh, float a_coef, float b_coef, float lr, hipStream_t st);
 
 // ---- optional diagnostics (od_diag.hip) ----

@@ -255,13 +255,14 @@ __global__ __launch_bounds__(256) void k_reduce(WsArr part, int splits, int64_t 
 }
 
 // the same for R, which is also stored as pre-scaled fp16 for the error-feedback kernel
-__global__ __launch_bounds__(256) void k_reduce_r(ClassDims d, WsArr part, int splits, WsArr out, HalfArr rh, const float* scal) {
+__global__ __launch_bounds__(256) void k_reduce_r(ClassDims d, WsArr part, int splits, WsArr out, HalfArr rh, const float* scal, int* info) {
   const int z = blockIdx.y;
   const float* src = part.base + (int64_t)z * part.stride;
   float* dst = out.base + (int64_t)z * out.stride;
   uint16_t* dh = rh.base + (int64_t)z * rh.stride;
   const int64_t count = (int64_t)d.n * d.r, n4 = count / 4;
   const float sr = r_scale(d, scal, z);
+  float rmax = 0.f;
   for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n4; i += (int64_t)gridDim.x * 256) {
     f32x4 s = reinterpret_cast<const f32x4*>(src)[i];
 #pragma unroll 8
@@ -269,7 +270,10 @@ __global__ __launch_bounds__(256) void k_reduce_r(ClassDims d, WsArr part, int s
     if (dst != src) reinterpret_cast<f32x4*>(dst)[i] = s;     // in place (one split): only the fp16 copy is new
     u32x2 h = {pack_f16_sat(s[0] * sr, s[1] * sr), pack_f16_sat(s[2] * sr, s[3] * sr)};
     reinterpret_cast<u32x2*>(dh)[i] = h;
+    rmax = fmaxf(rmax, fmaxf(fmaxf(fabsf(s[0]), fabsf(s[1])), fmaxf(fabsf(s[2]), fabsf(s[3]))));
   }
+  // a clipped entry (or a NaN) is reported, not hidden
+  if (!(rmax * sr <= 65504.f)) atomicOr(&info[z * kInfoPerMat + kWarnSlot], kWarnRClipped);
 }
 
 // ------------------------------------------------------------------------------------
@@ -879,6 +883,23 @@ OD_DEV bool matrix_flagged(const int* info, int z) {
   return (w[0] | w[1] | w[2]) != 0;
 }
 
+// The fast-precision contractions read B = M + G as fp16 under a scale sampled from 32 rows.
+// The pass that sees every entry of B anyway (error feedback) checks the sample: `bmax` is the
+// largest |B| this lane has met.
+OD_DEV void report_b_range(const ClassDims& d, const float* scal, int* info, int z, float bmax) {
+  const float sb = b_scale(d, scal, z);
+  int warn = 0;
+  if (!(bmax * sb <= 65504.f)) warn |= kWarnBClipped;
+  if (bmax > 0.f) {
+    const f32x4* p = reinterpret_cast<const f32x4*>(scal + z * kScalPerMat + kScalSample);
+    f32x4 acc4 = p[0];
+#pragma unroll
+    for (int i = 1; i < kStatRows / 4; ++i) acc4 += p[i];
+    if ((acc4[0] + acc4[1]) + (acc4[2] + acc4[3]) == 0.f) warn |= kWarnBScaleBlind;
+  }
+  if (warn != 0) atomicOr(&info[z * kInfoPerMat + kWarnSlot], warn);
+}
+
 template <class T, class Num, bool XBF, bool GBF>
 __global__ __launch_bounds__(T::THREADS) void k_efx(ClassDims d, MatPtrs ptrs, const float* scal, const int* info, WsArr p, WsArr rr,
                                                     float a_coef, float b_coef, float lr) {
@@ -979,7 +1000,7 @@ OD_DEV void st_stream(V* p, V v) {
 }
 
 template <bool XBF, bool GBF, bool STREAM>
-__global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, const float* scal, const int* info, HalfArr ph, HalfArr rh,
+__global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, const float* scal, int* info, HalfArr ph, HalfArr rh,
                                                HalfArr qh, float a_coef, float b_coef, float lr) {
   constexpr int TJ = 128, TI = 128, KT = 32, PITCH = KT * 2 + 16, PLANE = 128 * PITCH, BUF = 3 * PLANE;
   extern __shared__ __align__(16) char lds[];
@@ -1068,6 +1089,7 @@ __global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, con
 #pragma unroll
       for (int v = 0; v < 16; ++v) { acc_r[f][v] = 0.f; acc_q[f][v] = 0.f; }
   }
+  float bmax = 0.f;
 #pragma unroll
   for (int hv = 0; hv < 2; ++hv) {
     f32x2 mv[8], gv[8], xv[8];
@@ -1097,7 +1119,9 @@ __global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, con
         f32x2 mo, xo;
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-          mo[e] = a_coef * (mv[u][e] + g[e]) - cr * acc_r[e][v];
+          const float bval = mv[u][e] + g[e];
+          bmax = fmaxf(bmax, fabsf(bval));
+          mo[e] = a_coef * bval - cr * acc_r[e][v];
           xo[e] = x[e] - cq * acc_q[e][v];
         }
         st_stream<STREAM>(reinterpret_cast<f32x2*>(Mz + (int64_t)i * d.ldm + j0), mo);
@@ -1106,6 +1130,7 @@ __global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, con
       }
     }
   }
+  report_b_range(d, scal, info, z, bmax);
 }
 
 // ------------------------------------------------------------------------------------
@@ -1121,7 +1146,7 @@ __global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, con
 // M, G, X while the other multiplies.
 // ------------------------------------------------------------------------------------
 template <bool XBF, bool GBF, bool STREAM, int WI>
-__global__ __launch_bounds__(128 * WI, (WI == 2 ? 2 : 1)) void k_efx_d(ClassDims d, MatPtrs ptrs, const float* scal, const int* info, HalfArr ph,
+__global__ __launch_bounds__(128 * WI, (WI == 2 ? 2 : 1)) void k_efx_d(ClassDims d, MatPtrs ptrs, const float* scal, int* info, HalfArr ph,
                                                                      HalfArr rh, HalfArr qh, float a_coef, float b_coef, float lr) {
   constexpr int TI = 64 * WI, TJ = 128, KT = 32, ROWB = KT * 2, ST = 3, NW = 2 * WI;
   constexpr int PLANE = 128 * ROWB, STAGE = 2 * PLANE + TI * ROWB;       // R | Q | P
@@ -1233,6 +1258,7 @@ __global__ __launch_bounds__(128 * WI, (WI == 2 ? 2 : 1)) void k_efx_d(ClassDims
 #pragma unroll
         for (int v = 0; v < 16; ++v) { acc_r[fm][f][v] = 0.f; acc_q[fm][f][v] = 0.f; }
   }
+  float bmax = 0.f;
 #pragma unroll
   for (int part = 0; part < 4; ++part) {
     const int fm = part >> 1, hv = part & 1;
@@ -1263,7 +1289,9 @@ __global__ __launch_bounds__(128 * WI, (WI == 2 ? 2 : 1)) void k_efx_d(ClassDims
         f32x2 mo, xo;
 #pragma unroll
         for (int e = 0; e < 2; ++e) {
-          mo[e] = a_coef * (mv[u][e] + g[e]) - cr * acc_r[fm][e][v];
+          const float bval = mv[u][e] + g[e];
+          bmax = fmaxf(bmax, fabsf(bval));
+          mo[e] = a_coef * bval - cr * acc_r[fm][e][v];
           xo[e] = x[e] - cq * acc_q[fm][e][v];
         }
         st_stream<STREAM>(reinterpret_cast<f32x2*>(Mz + (int64_t)i * d.ldm + j0), mo);
@@ -1272,6 +1300,7 @@ __global__ __launch_bounds__(128 * WI, (WI == 2 ? 2 : 1)) void k_efx_d(ClassDims
       }
     }
   }
+  report_b_range(d, scal, info, z, bmax);
 }
 
 // ------------------------------------------------------------------------------------
@@ -1662,11 +1691,11 @@ hipError_t launch_reduce(int nb, WsArr part, int splits, int64_t count, WsArr ou
   return hipSuccess;
 }
 
-hipError_t launch_reduce_r(const ClassDims& d, WsArr part, int splits, WsArr out, HalfArr rh, const float* scal, hipStream_t st) {
+hipError_t launch_reduce_r(const ClassDims& d, WsArr part, int splits, WsArr out, HalfArr rh, const float* scal, int* info, hipStream_t st) {
   int64_t n4 = (int64_t)d.n * d.r / 4;
   int blocks = (int)((n4 + 255) / 256);
   if (blocks > 2048) blocks = 2048;
-  hipLaunchKernelGGL(k_reduce_r, dim3(blocks, d.nb), dim3(256), 0, st, d, part, splits, out, rh, scal);
+  hipLaunchKernelGGL(k_reduce_r, dim3(blocks, d.nb), dim3(256), 0, st, d, part, splits, out, rh, scal, info);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -1946,7 +1975,7 @@ static hipError_t efx_n(const ClassDims& d, const MatPtrs& ptrs, const float* sc
                   : efx_t<Num, false, false>(d, ptrs, scal, info, p, rr, a_coef, b_coef, lr, st);
 }
 template <bool XBF, bool GBF>
-static hipError_t efx_h_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, const int* info, HalfArr ph, HalfArr rh, HalfArr qh,
+static hipError_t efx_h_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, int* info, HalfArr ph, HalfArr rh, HalfArr qh,
                           float a_coef, float b_coef, float lr, hipStream_t st) {
   dim3 grid(((d.m + 127) / 128) * ((d.n + 127) / 128), 1, d.nb);
   const bool stream = d.r > 256 || (int64_t)d.m * d.n * d.nb >= ((int64_t)48 << 20);
@@ -1981,7 +2010,7 @@ static hipError_t efx_h_t(const ClassDims& d, const MatPtrs& ptrs, const float* 
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
-hipError_t launch_efx_h(const ClassDims& d, const MatPtrs& ptrs, const float* scal, const int* info, HalfArr ph, HalfArr rh,
+hipError_t launch_efx_h(const ClassDims& d, const MatPtrs& ptrs, const float* scal, int* info, HalfArr ph, HalfArr rh,
                         HalfArr qh, float a_coef, float b_coef, float lr, hipStream_t st) {
   if (d.x_bf16) return d.g_bf16 ? efx_h_t<true, true>(d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr, st)
                                 : efx_h_t<true, false>(d, ptrs, scal, info, ph, rh, qh, a_coef, b_coef, lr, st);

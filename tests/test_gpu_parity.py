@@ -150,6 +150,35 @@ def test_large_batches_take_the_full_chip_kernels_and_match_the_oracle(count, m,
             assert res["X_bits_mismatch"] <= 0.01 and res["X_beyond_one_spacing"] == 0.0, (t, i, res)
 
 
+def test_operand_range_warnings_of_the_fast_precision():
+    """The fp16 scale of B comes from 32 sampled rows (rows 0, 20, 40, ... of 640).  An entry
+    far above the sampled rms in a row the sample misses is clipped - and reported; sampled rows
+    that are all zero leave B without a scale - reported; ordinary data reports nothing."""
+    w = synth.Workload("warn", ((640, 512),), r=128, x_dtype="bf16", steps=1)
+    stream, st = synth.make_stream(w, 0), synth.make_state(w, 0)
+    g = stream.gradient(0)
+    gpu = GpuRun(w.shapes, w.r, "bf16", [st], mu=w.mu, lr=w.lr)
+    assert gpu.step([g]) == [0]
+    assert gpu.opt.warnings() == [0]
+
+    huge = g.copy()
+    huge[7, 300] = synth.f32_to_bf16_bits(np.array([3.0e4], dtype=np.float32))[0]      # rms of G is 1e-2
+    gpu = GpuRun(w.shapes, w.r, "bf16", [st], mu=w.mu, lr=w.lr)
+    gpu.step([huge])
+    assert gpu.opt.warnings()[0] & binding.WARN_B_CLIPPED
+
+    blind = g.copy()
+    blind[::20, :] = 0                                   # every sampled row
+    gpu = GpuRun(w.shapes, w.r, "bf16", [st], mu=w.mu, lr=w.lr)
+    gpu.step([blind])
+    assert gpu.opt.warnings()[0] & binding.WARN_B_SCALE_BLIND
+
+    # exact precision involves no scale: nothing to warn about, and the outlier is handled
+    gpu = GpuRun(w.shapes, w.r, "bf16", [st], precision="exact", mu=w.mu, lr=w.lr)
+    gpu.step([huge])
+    assert gpu.opt.warnings() == [0]
+
+
 def test_leading_dimensions_larger_than_n():
     import torch
     m, n, r, ld = 128, 96, 16, 160
