@@ -39,7 +39,7 @@ GROUPS = {
     "k_back": (["back"], ["od::k_back<", "od::k_stream_d<true"]),
     "k_efx": (["efx"], ["od::k_efx_d<", "od::k_efx_h<", "od::k_efx<"]),
     "k_gram (first pass)": (["gram_left", "gram_right"], []),
-    "cholesky chain (k_chol256, k_sgemm_pair)": (["chol_left", "chol_right"], ["od::k_chol256", "od::k_sgemm", "od::k_zero_pair"]),
+    "cholesky chain (k_chol256, k_chol_ahead, k_sgemm_pair)": (["chol_left", "chol_right"], ["od::k_chol256", "od::k_chol_ahead", "od::k_sgemm", "od::k_zero_pair"]),
     "rest of orth (k_apply, k_gram, k_corr | ColNorm)": (["orth_left", "orth_right", "guard_left", "guard_right", "finish_left", "finish_right"],
                                                          ["od::k_apply<", "od::k_corr", "od::k_colsq", "od::k_colnorm"]),
     "k_reduce": (["proj_reduce", "back_reduce"], ["od::k_reduce"]),
