@@ -4,6 +4,7 @@
 #include "../../include/orthdion.h"
 
 #include <cmath>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -53,6 +54,21 @@ int pick_splits(int64_t tiles, int nb, int64_t k, int kt_min) {
   if (want > 32) want = 32;
   if (want < 1) want = 1;
   return (int)want;
+}
+
+// Splits for a kernel that runs one workgroup per CU, in rounds of 256 workgroups.  A workgroup's
+// time is proportional to 1 / splits, so rounds / splits measures the launch; the fewest splits
+// (least partial-sum traffic) within 15 % of the best are taken.
+int pick_splits_one_per_cu(int64_t tiles, int nb, int64_t k, int kt_min) {
+  int64_t cap = k / kt_min;
+  if (cap < 1) cap = 1;
+  if (cap > 32) cap = 32;
+  auto cost = [&](int s) { return (double)((tiles * nb * s + 255) / 256) / (double)s; };
+  double best = cost(1);
+  for (int s = 2; s <= (int)cap; ++s) best = cost(s) < best ? cost(s) : best;
+  for (int s = 1; s <= (int)cap; ++s)
+    if (cost(s) <= 1.15 * best) return s;
+  return 1;
 }
 
 }  // namespace
@@ -228,10 +244,10 @@ static int create_impl(orthdion_handle* out, const orthdion_matdesc* mats, int32
     b.splits_proj = pick_splits(((m + proj_rows - 1) / proj_rows) * tiles_r, d.nb, n, 128);
     b.splits_back = pick_splits(((n + 127) / 128) * tiles_r, d.nb, m, 128);
     if (resolve_prec(*cfg) == od::PREC_F16 && od::stream_kernel_eligible(d)) {
-      // one 8-wave workgroup per CU and 128 x 256 / 512 tiles: two rounds of workgroups fill the chip
+      // one 8-wave workgroup per CU and 128 x 256 / 512 tiles
       const int64_t tiles_c = (r + od::stream_tile_cols((int)r) - 1) / od::stream_tile_cols((int)r);
-      b.splits_proj = pick_splits(((m + 127) / 128) * tiles_c, d.nb, n, 256);
-      b.splits_back = pick_splits(((n + 127) / 128) * tiles_c, d.nb, m, 256);
+      b.splits_proj = pick_splits_one_per_cu(((m + 127) / 128) * tiles_c, d.nb, n, 256);
+      b.splits_back = pick_splits_one_per_cu(((n + 127) / 128) * tiles_c, d.nb, m, 256);
     }
     const int64_t gt = ((r + 127) / 128) * ((r + 127) / 128);
     b.splits_gram_p = pick_splits(gt, d.nb, m, 256);
