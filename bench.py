@@ -235,6 +235,14 @@ def measure(torch, binding, synth, dev, name, variant, precision, steps, warmup,
         raise RuntimeError(f"numerical breakdown flagged in {name}: {info}")
     elapsed = t1 - t0
     ms_per_step = 1e3 * elapsed / steps
+    # the same number of steps once more without any event on the stream: every recorded event
+    # is a barrier packet between two kernels, which a step of a few hundred microseconds feels
+    torch.cuda.synchronize()
+    t2 = time.perf_counter()
+    for t in range(steps):
+        one_step(t)
+    torch.cuda.synchronize()
+    ms_per_step_plain = 1e3 * (time.perf_counter() - t2) / steps
     dom_ms = sum(prof[p][0] for p in GROUPS[dominant][0] if p in prof) / steps      # per step
     dom_launches = sum(prof[p][1] for p in GROUPS[dominant][0] if p in prof) // steps
 
@@ -255,6 +263,7 @@ def measure(torch, binding, synth, dev, name, variant, precision, steps, warmup,
     step_bytes, step_flops, step_flops_qr = step_work(w, variant)
     rec = {
         "workload": w.name, "variant": variant, "steps": steps, "ms_per_step": ms_per_step, "steps_per_s": steps / elapsed,
+        "ms_per_step_without_events": ms_per_step_plain,
         "data": data, "nmat": nmat, "r": w.r, "elements": w.elements, "x_dtype": w.x_dtype, "mu": w.mu, "lr": w.lr,
         "shapes": sorted({f"{m}x{n}" for m, n in w.shapes}), "fast_path": fast_path,
         "roofline": {
@@ -323,7 +332,8 @@ def main():
     head["whole_step"]["hbm_frac_of_copy"] = head["whole_step"]["algorithmic_GBps"] / copy_gbps
     out = {
         "metric": METRIC, "value": head["steps_per_s"], "unit": "steps/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": head["ms_per_step"], "higher_is_better": True, "scaling": "weak",
+        "warmup": args.warmup, "ms_per_step": head["ms_per_step"],
+        "ms_per_step_without_events": head["ms_per_step_without_events"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None,
         "dtype": "f16" if head["fast_path"] else "bf16",
         "data": head["data"],
@@ -346,6 +356,7 @@ def main():
                 continue
             rf, ws = rec["roofline"], rec["whole_step"]
             sweep.append({"workload": name, "r": rec["r"], "steps": k, "ms_per_step": rec["ms_per_step"],
+                          "ms_per_step_without_events": rec["ms_per_step_without_events"],
                           "steps_per_s": rec["steps_per_s"], "dominant_kernel": rf["kernel"], "bound": rf["bound"],
                           "kernel_frac": rf["frac"], "kernel_hbm_frac": rf["hbm_frac"], "kernel_mfma_frac": rf["mfma_frac"],
                           "kernel_share_of_step": rf["share_of_step"], "traffic": rf["traffic"],

@@ -56,14 +56,15 @@ int pick_splits(int64_t tiles, int nb, int64_t k, int kt_min) {
   return (int)want;
 }
 
-// Splits for a kernel that runs one workgroup per CU, in rounds of 256 workgroups.  A workgroup's
-// time is proportional to 1 / splits, so rounds / splits measures the launch; the fewest splits
-// (least partial-sum traffic) within 15 % of the best are taken.
-int pick_splits_one_per_cu(int64_t tiles, int nb, int64_t k, int kt_min) {
+// Splits for a kernel whose workgroups run in rounds of `slots` (256 CUs times the workgroups
+// that fit one CU).  A workgroup's time is proportional to 1 / splits, so rounds / splits
+// measures the launch; the fewest splits (least partial-sum traffic) within 15 % of the best
+// are taken.
+int pick_splits_by_rounds(int64_t tiles, int nb, int64_t k, int kt_min, int64_t slots) {
   int64_t cap = k / kt_min;
   if (cap < 1) cap = 1;
   if (cap > 32) cap = 32;
-  auto cost = [&](int s) { return (double)((tiles * nb * s + 255) / 256) / (double)s; };
+  auto cost = [&](int s) { return (double)((tiles * nb * s + slots - 1) / slots) / (double)s; };
   double best = cost(1);
   for (int s = 2; s <= (int)cap; ++s) best = cost(s) < best ? cost(s) : best;
   for (int s = 1; s <= (int)cap; ++s)
@@ -246,12 +247,21 @@ static int create_impl(orthdion_handle* out, const orthdion_matdesc* mats, int32
     if (resolve_prec(*cfg) == od::PREC_F16 && od::stream_kernel_eligible(d)) {
       // one 8-wave workgroup per CU and 128 x 256 / 512 tiles
       const int64_t tiles_c = (r + od::stream_tile_cols((int)r) - 1) / od::stream_tile_cols((int)r);
-      b.splits_proj = pick_splits_one_per_cu(((m + 127) / 128) * tiles_c, d.nb, n, 256);
-      b.splits_back = pick_splits_one_per_cu(((n + 127) / 128) * tiles_c, d.nb, m, 256);
+      b.splits_proj = pick_splits_by_rounds(((m + 127) / 128) * tiles_c, d.nb, n, 256, 256);
+      b.splits_back = pick_splits_by_rounds(((n + 127) / 128) * tiles_c, d.nb, m, 256, 256);
     }
-    const int64_t gt = ((r + 127) / 128) * ((r + 127) / 128);
-    b.splits_gram_p = pick_splits(gt, d.nb, m, 256);
-    b.splits_gram_q = pick_splits(gt, d.nb, n, 256);
+    // Gram tiles on and above the diagonal (the ones that are computed)
+    const int64_t gt1 = (r + 127) / 128;
+    const int64_t gt = gt1 * (gt1 + 1) / 2;
+    if (r <= 32) {
+      // one 32 x 32 tile, one thread per row: 256-row slabs (k_small_gram, k_small_first_pass)
+      b.splits_gram_p = pick_splits(1, d.nb, m, 256);
+      b.splits_gram_q = pick_splits(1, d.nb, n, 256);
+    } else {
+      // two workgroups of the Gram kernel fit one CU
+      b.splits_gram_p = pick_splits_by_rounds(gt, d.nb, m, 256, 512);
+      b.splits_gram_q = pick_splits_by_rounds(gt, d.nb, n, 256, 512);
+    }
     if (b.splits_gram_p > 32) b.splits_gram_p = 32;
     if (b.splits_gram_q > 32) b.splits_gram_q = 32;
     b.slabs = (int)((n + 31) / 32);           // row slabs of the column-norm kernels: many, so the grid fills the chip
