@@ -21,7 +21,12 @@
  * bf16 as configured; M and Q are always fp32.  All buffers named "device" are device
  * (HBM) pointers owned by the caller; pointer *arrays* are host arrays.  The library never
  * allocates or frees device memory and never synchronises the device or a stream, except
- * orthdion_get_info, which waits for the stream it is given.
+ * orthdion_get_info / orthdion_get_warnings / orthdion_get_diagnostics, which wait for the
+ * stream they are given.  For ranks above 256 in fast precision orthdion_step creates, at its
+ * first call that is not under stream capture, one more stream and two events (runtime
+ * objects of the handle, released by orthdion_destroy): the guard of the second CholeskyQR
+ * pass forks onto it and joins the caller's stream again before the step's remaining kernels,
+ * so the caller sees a single stream; under capture both branches are part of the graph.
  *
  * Errors: every function returns ORTHDION_OK (0) or a negative orthdion_status; nothing
  * throws or aborts.  Numerical breakdown found on the device (a rank-deficient or

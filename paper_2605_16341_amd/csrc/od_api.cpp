@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "od_kernels.h"
+#include "od_internal.h"
 
 namespace {
 
@@ -89,7 +90,33 @@ struct orthdion_ctx {
   int prof_max_steps = 0, prof_steps = 0;
   std::vector<hipEvent_t> prof_events;    // [step][batch][phase][begin/end]
   std::vector<char> prof_recorded;        // [step][batch][phase]: an interval was recorded
+  // a second stream for the guard of the second CholeskyQR pass (ranks above 256): its launch
+  // chain returns at once for every well-conditioned matrix, and beside the main stream those
+  // empty launches cost nothing (host resources; made at the first step that is not being captured)
+  hipStream_t side = nullptr;
+  hipEvent_t ev_fork = nullptr, ev_join = nullptr;
+  bool side_tried = false;
 };
+
+static bool ensure_side_stream(orthdion_ctx* h, hipStream_t st) {
+  if (h->side) return true;
+  if (h->side_tried) return false;
+  hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(st, &cs) != hipSuccess) { (void)hipGetLastError(); return false; }
+  if (cs != hipStreamCaptureStatusNone) return false;        // nothing is created under capture; a later call may
+  h->side_tried = true;
+  if (hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking) != hipSuccess) { h->side = nullptr; (void)hipGetLastError(); return false; }
+  if (hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming) != hipSuccess ||
+      hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming) != hipSuccess) {
+    if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
+    if (h->ev_join) (void)hipEventDestroy(h->ev_join);
+    (void)hipStreamDestroy(h->side);
+    h->side = nullptr; h->ev_fork = nullptr; h->ev_join = nullptr;
+    (void)hipGetLastError();
+    return false;
+  }
+  return true;
+}
 
 static hipEvent_t* prof_slot(orthdion_ctx* h, int batch, int phase, int end) {
   if (!h->prof_on || h->prof_steps >= h->prof_max_steps || !(h->prof_mask & (1u << phase))) return nullptr;
@@ -403,9 +430,12 @@ static int orth_second_pass(const Batch& b, char* ws, int rows, size_t off_a0, s
   return ORTHDION_OK;
 }
 
+// `which`: 0 = everything; 1 = only the first-order correction of the well-conditioned matrices,
+// 2 = only the full product of the flagged ones (the two halves of a step that runs the guard on
+// a second stream; fast precision and a class-wide guard only).
 static int orth_result(const Batch& b, char* ws, int rows, size_t off_a0, size_t off_a1, int64_t st_a, int splits,
                        size_t off_t2, int info_slot, const MatPtrs* q_out, HalfArr hn, HalfArr ht, float* scal, int* info,
-                       int exact, hipStream_t st) {
+                       int exact, hipStream_t st, int which = 0) {
   const int nb = b.d.nb, r = b.d.r;
   WsArr a0{reinterpret_cast<float*>(ws + off_a0), st_a}, a1{reinterpret_cast<float*>(ws + off_a1), st_a};
   WsArr w{reinterpret_cast<float*>(ws + b.off_w), b.st_rr}, tmp{reinterpret_cast<float*>(ws + b.off_tmp), b.st_rr};
@@ -420,8 +450,8 @@ static int orth_result(const Batch& b, char* ws, int rows, size_t off_a0, size_t
     OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, hn, ht, exact, st));
   } else {
     const HalfArr phit{reinterpret_cast<uint16_t*>(ws + b.off_tmp), 2 * b.st_rr};
-    OD_TRY(od::launch_apply_correction(nb, rows, r, a1, phit, a0, q_out, hn, ht, st, small));
-    OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, hn, ht, exact, st, big));
+    if (which != 2) OD_TRY(od::launch_apply_correction(nb, rows, r, a1, phit, a0, q_out, hn, ht, st, small));
+    if (which != 1) OD_TRY(od::launch_apply(nb, rows, r, a1, w, a0, q_out, hn, ht, exact, st, big));
   }
   return ORTHDION_OK;
 }
@@ -450,6 +480,11 @@ static int class_guard(const RankClass& c, char* ws, size_t off_t2, int info_slo
 
 extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* const* G, float* const* M,
                              float* const* Q, void* workspace, size_t workspace_bytes, void* stream) {
+  return orthdion_step_impl(h, X, G, M, Q, workspace, workspace_bytes, stream, 1);
+}
+
+extern "C" int orthdion_step_impl(orthdion_handle h, void* const* X, const void* const* G, float* const* M, float* const* Q,
+                                  void* workspace, size_t workspace_bytes, void* stream, int allow_second_stream) {
   if (!h || !X || !G || !M || !Q || !workspace) return ORTHDION_E_NULL_PTR;
   if (workspace_bytes < h->ws_bytes) return ORTHDION_E_WORKSPACE_TOO_SMALL;
   if (reinterpret_cast<uintptr_t>(workspace) % kAlign) return ORTHDION_E_MISALIGNED;
@@ -573,16 +608,27 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     return ORTHDION_OK;
   };
   // P itself, line 3 (R = (M + G)^T P), and the head of line 4
-  auto middle = [&](int bi) -> int {
+  // `mode` (also for `tail`): 0 = the whole piece on `st`; with the guard on the second stream the
+  // piece is enqueued in three parts: 1 = the result of the well-conditioned matrices on `st`,
+  // 2 = the result of the flagged ones on the second stream, 3 = everything after the result
+  auto middle = [&](int bi, int mode) -> int {
     const Batch& b = h->batches[bi];
     const ClassDims& d = b.d;
     BatchView v;
     view_of(b, v);
-    OD_PHASE_BEGIN(ORTHDION_PHASE_FINISH_LEFT);
-    int rc = orth_result(b, ws, d.m, b.off_pa, b.off_pb, b.st_p, b.splits_gram_p, b.off_tp2, 0, nullptr,
-                         fast ? v.ph : none, fast ? v.pht : none, v.scal, v.info, exact, st);
-    if (rc != ORTHDION_OK) return rc;
-    OD_PHASE_END(ORTHDION_PHASE_FINISH_LEFT);
+    int rc;
+    if (mode == 2) {
+      return orth_result(b, ws, d.m, b.off_pa, b.off_pb, b.st_p, b.splits_gram_p, b.off_tp2, 0, nullptr,
+                         fast ? v.ph : none, fast ? v.pht : none, v.scal, v.info, exact, h->side, 2);
+    }
+    if (mode != 3) {
+      OD_PHASE_BEGIN(ORTHDION_PHASE_FINISH_LEFT);
+      rc = orth_result(b, ws, d.m, b.off_pa, b.off_pb, b.st_p, b.splits_gram_p, b.off_tp2, 0, nullptr,
+                       fast ? v.ph : none, fast ? v.pht : none, v.scal, v.info, exact, st, mode);
+      if (rc != ORTHDION_OK) return rc;
+      OD_PHASE_END(ORTHDION_PHASE_FINISH_LEFT);
+      if (mode == 1) return ORTHDION_OK;
+    }
     OD_PHASE_KERNEL(ORTHDION_PHASE_BACK);
     // as for the projection: a single split goes straight to its place; fast precision still
     // needs the fp16 copy of R, made from there
@@ -617,21 +663,28 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
 
   // rest of line 4: Q = orth(R) or ColNorm(R), written to the callers' Q (Q_prev is no longer
   // needed); lines 5-7: parameter update and error feedback in one pass
-  auto tail = [&](int bi) -> int {
+  auto tail = [&](int bi, int mode) -> int {
     const Batch& b = h->batches[bi];
     const ClassDims& d = b.d;
     BatchView v;
     view_of(b, v);
-    OD_PHASE_BEGIN(ORTHDION_PHASE_FINISH_RIGHT);
-    if (h->cfg.variant == ORTHDION_QR) {
-      int rc = orth_result(b, ws, d.n, b.off_ra, b.off_rb, b.st_r, b.splits_gram_q, b.off_tq2, 1, &v.ptrs,
-                           fast ? v.qh : none, none, v.scal, v.info, exact, st);
-      if (rc != ORTHDION_OK) return rc;
-    } else {
-      OD_TRY(od::launch_colnorm(d.nb, d.n, d.r, v.ra, v.ptrs, v.part, b.slabs, v.colsq, v.scal, v.info,
-                                fast ? v.qh : none, st));
+    if (mode == 2) {
+      return orth_result(b, ws, d.n, b.off_ra, b.off_rb, b.st_r, b.splits_gram_q, b.off_tq2, 1, &v.ptrs,
+                         fast ? v.qh : none, none, v.scal, v.info, exact, h->side, 2);
     }
-    OD_PHASE_END(ORTHDION_PHASE_FINISH_RIGHT);
+    if (mode != 3) {
+      OD_PHASE_BEGIN(ORTHDION_PHASE_FINISH_RIGHT);
+      if (h->cfg.variant == ORTHDION_QR) {
+        int rc = orth_result(b, ws, d.n, b.off_ra, b.off_rb, b.st_r, b.splits_gram_q, b.off_tq2, 1, &v.ptrs,
+                             fast ? v.qh : none, none, v.scal, v.info, exact, st, mode);
+        if (rc != ORTHDION_OK) return rc;
+      } else {
+        OD_TRY(od::launch_colnorm(d.nb, d.n, d.r, v.ra, v.ptrs, v.part, b.slabs, v.colsq, v.scal, v.info,
+                                  fast ? v.qh : none, st));
+      }
+      OD_PHASE_END(ORTHDION_PHASE_FINISH_RIGHT);
+      if (mode == 1) return ORTHDION_OK;
+    }
     if (diag) {
       // nu = sigma_1(Q_new): Gram matrix of the new right factor, then power iteration
       WsArr rb{reinterpret_cast<float*>(ws + b.off_rb), b.st_r};
@@ -664,23 +717,55 @@ extern "C" int orthdion_step(orthdion_handle h, void* const* X, const void* cons
     OD_PHASE_END(ORTHDION_PHASE_CHOL_LEFT);
     for (int b2 : c.batches)
       if ((rc = left_second(b2)) != ORTHDION_OK) return rc;
-    OD_PHASE_BEGIN(ORTHDION_PHASE_GUARD_LEFT);
-    if ((rc = class_guard(c, ws, c.off_tp2, 0, scal_all, info_all, st)) != ORTHDION_OK) return rc;
-    OD_PHASE_END(ORTHDION_PHASE_GUARD_LEFT);
-    for (int b2 : c.batches)
-      if ((rc = middle(b2)) != ORTHDION_OK) return rc;
+    // Ranks above 256 in fast precision: the guard (a launch chain over the class that returns at
+    // once for every well-conditioned matrix, then the full product of the flagged ones) runs on
+    // the second stream beside the first-order result of the others; the streams join before
+    // anything reads a factor.
+    const bool forked = allow_second_stream && fast && guard_is_class_wide(c.r) && ensure_side_stream(h, st);
+    if (forked) {
+      OD_TRY(hipEventRecord(h->ev_fork, st));
+      OD_TRY(hipStreamWaitEvent(h->side, h->ev_fork, 0));
+      if ((rc = class_guard(c, ws, c.off_tp2, 0, scal_all, info_all, h->side)) != ORTHDION_OK) return rc;
+      for (int b2 : c.batches)
+        if ((rc = middle(b2, 2)) != ORTHDION_OK) return rc;
+      OD_TRY(hipEventRecord(h->ev_join, h->side));
+      for (int b2 : c.batches)
+        if ((rc = middle(b2, 1)) != ORTHDION_OK) return rc;
+      OD_TRY(hipStreamWaitEvent(st, h->ev_join, 0));
+      for (int b2 : c.batches)
+        if ((rc = middle(b2, 3)) != ORTHDION_OK) return rc;
+    } else {
+      OD_PHASE_BEGIN(ORTHDION_PHASE_GUARD_LEFT);
+      if ((rc = class_guard(c, ws, c.off_tp2, 0, scal_all, info_all, st)) != ORTHDION_OK) return rc;
+      OD_PHASE_END(ORTHDION_PHASE_GUARD_LEFT);
+      for (int b2 : c.batches)
+        if ((rc = middle(b2, 0)) != ORTHDION_OK) return rc;
+    }
+    const bool forked_right = forked && h->cfg.variant == ORTHDION_QR;
     if (h->cfg.variant == ORTHDION_QR) {
       OD_PHASE_BEGIN(ORTHDION_PHASE_CHOL_RIGHT);
       if ((rc = class_cholinv(c, ws, c.off_tq1, 1, info_all, st)) != ORTHDION_OK) return rc;
       OD_PHASE_END(ORTHDION_PHASE_CHOL_RIGHT);
       for (int b2 : c.batches)
         if ((rc = right_second(b2)) != ORTHDION_OK) return rc;
-      OD_PHASE_BEGIN(ORTHDION_PHASE_GUARD_RIGHT);
-      if ((rc = class_guard(c, ws, c.off_tq2, 1, scal_all, info_all, st)) != ORTHDION_OK) return rc;
-      OD_PHASE_END(ORTHDION_PHASE_GUARD_RIGHT);
+      if (forked_right) {
+        OD_TRY(hipEventRecord(h->ev_fork, st));
+        OD_TRY(hipStreamWaitEvent(h->side, h->ev_fork, 0));
+        if ((rc = class_guard(c, ws, c.off_tq2, 1, scal_all, info_all, h->side)) != ORTHDION_OK) return rc;
+        for (int b2 : c.batches)
+          if ((rc = tail(b2, 2)) != ORTHDION_OK) return rc;
+        OD_TRY(hipEventRecord(h->ev_join, h->side));
+        for (int b2 : c.batches)
+          if ((rc = tail(b2, 1)) != ORTHDION_OK) return rc;
+        OD_TRY(hipStreamWaitEvent(st, h->ev_join, 0));
+      } else {
+        OD_PHASE_BEGIN(ORTHDION_PHASE_GUARD_RIGHT);
+        if ((rc = class_guard(c, ws, c.off_tq2, 1, scal_all, info_all, st)) != ORTHDION_OK) return rc;
+        OD_PHASE_END(ORTHDION_PHASE_GUARD_RIGHT);
+      }
     }
     for (int b2 : c.batches)
-      if ((rc = tail(b2)) != ORTHDION_OK) return rc;
+      if ((rc = tail(b2, forked_right ? 3 : 0)) != ORTHDION_OK) return rc;
   }
   if (h->prof_on && h->prof_steps < h->prof_max_steps) h->prof_steps++;
   return ORTHDION_OK;
@@ -874,6 +959,9 @@ extern "C" int orthdion_destroy(orthdion_handle h) {
   if (!h) return ORTHDION_E_NULL_PTR;
   for (hipEvent_t e : h->prof_events)
     if (e) (void)hipEventDestroy(e);
+  if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
+  if (h->ev_join) (void)hipEventDestroy(h->ev_join);
+  if (h->side) (void)hipStreamDestroy(h->side);
   delete h;
   return ORTHDION_OK;
 }

@@ -13,6 +13,7 @@
 #include <mutex>
 
 #include "../../include/orthdion.h"
+#include "od_internal.h"
 
 namespace {
 
@@ -51,5 +52,5 @@ extern "C" int orthdion_step_static(orthdion_handle h, void* const* X, const voi
   if (rc != ORTHDION_OK) return rc;
   // orthdion_step clears the words of the workspace that must start at zero (scale, flag and
   // accumulator words) itself, every step, so the contents a previous call left are harmless.
-  return orthdion_step(h, X, G, M, Q, ws, kStaticScratchBytes, stream);
+  return orthdion_step_impl(h, X, G, M, Q, ws, kStaticScratchBytes, stream, 0);
 }

@@ -127,9 +127,9 @@ def test_teacher_forced_single_steps_bf16():
 
 
 @pytest.mark.parametrize("count,m,n,r", [(24, 1024, 1280, 256), (12, 1152, 1024, 320)])
-def test_large_batches_take_the_full_chip_kernels_and_match_the_oracle(count, m, n, r):
-    """Enough equal matrices that the orthogonalisation runs on its one-workgroup-per-CU kernels
-    (256 x 256 Gram tiles, 128 x 256 tiles of the triangular products): two steps, the oracle
+def test_large_batches_match_the_oracle(count, m, n, r):
+    """Launch batches of many equal matrices (the shape of the model matrix set: large tiles, few
+    splits, results written in place, the class-wide guard at r > 256): two steps, the oracle
     restarted from the GPU's state before each, on the first, a middle and the last matrix."""
     w = synth.Workload(f"batch{count}x{m}x{n}r{r}", tuple([(m, n)] * count), r=r, x_dtype="bf16", steps=2)
     streams = [synth.make_stream(w, i) for i in range(count)]
@@ -348,12 +348,15 @@ def test_orthonormality_and_qr_uniqueness_from_the_debug_factors():
     assert abs(np.sum(b * (p @ q.T)) / np.trace(t_q) - 1.0) < 1e-4
 
 
-def test_step_replayed_from_a_hip_graph_matches_eager_bit_for_bit():
+@pytest.mark.parametrize("shapes,r", [(((256, 192), (128, 320)), 32), (((640, 384), (384, 512)), 320)])
+def test_step_replayed_from_a_hip_graph_matches_eager_bit_for_bit(shapes, r):
     """orthdion_step only enqueues kernels (no allocation, no synchronisation, no memset), so
     it can be captured once and replayed.  Every replay, with eager work and synchronisation
-    in between, must leave exactly the bits an eager twin computes from the same inputs."""
+    in between, must leave exactly the bits an eager twin computes from the same inputs.
+    The rank above 256 forks the guard of the second CholeskyQR pass onto the library's second
+    stream and joins it again: the capture must hold both branches."""
     import torch
-    w = synth.Workload("graph", ((256, 192), (128, 320)), r=32, x_dtype="bf16", steps=4)
+    w = synth.Workload("graph", shapes, r=r, x_dtype="bf16", steps=4)
     nmat = len(w.shapes)
     streams = [synth.make_stream(w, i) for i in range(nmat)]
     states = [synth.make_state(w, i) for i in range(nmat)]
