@@ -348,13 +348,14 @@ def test_orthonormality_and_qr_uniqueness_from_the_debug_factors():
     assert abs(np.sum(b * (p @ q.T)) / np.trace(t_q) - 1.0) < 1e-4
 
 
-@pytest.mark.parametrize("shapes,r", [(((256, 192), (128, 320)), 32), (((640, 384), (384, 512)), 320)])
+@pytest.mark.parametrize("shapes,r", [(((256, 192), (128, 320)), 32), (((640, 384), (384, 512)), 320),
+                                      (((1024, 640), (640, 1024)), 512)])
 def test_step_replayed_from_a_hip_graph_matches_eager_bit_for_bit(shapes, r):
     """orthdion_step only enqueues kernels (no allocation, no synchronisation, no memset), so
     it can be captured once and replayed.  Every replay, with eager work and synchronisation
     in between, must leave exactly the bits an eager twin computes from the same inputs.
-    The rank above 256 forks the guard of the second CholeskyQR pass onto the library's second
-    stream and joins it again: the capture must hold both branches."""
+    The ranks above 256 fork the guard of the second CholeskyQR pass onto the library's second
+    stream and join it again: the capture must hold both branches."""
     import torch
     w = synth.Workload("graph", shapes, r=r, x_dtype="bf16", steps=4)
     nmat = len(w.shapes)
