@@ -633,9 +633,10 @@ extern "C" int orthdion_step_impl(orthdion_handle h, void* const* X, const void*
     // as for the projection: a single split goes straight to its place; fast precision still
     // needs the fp16 copy of R, made from there
     const bool back_direct = b.splits_back == 1;
-    OD_TRY(od::launch_back(d, v.ptrs, prec, v.scal, v.pa, back_direct ? v.ra : v.part, b.splits_back, v.pht, st));
+    const bool copy_in_kernel = od::back_writes_fp16_copy(d, prec, b.splits_back);
+    OD_TRY(od::launch_back(d, v.ptrs, prec, v.scal, v.pa, back_direct ? v.ra : v.part, b.splits_back, v.pht, st, v.rh, v.info));
     OD_PHASE_BEGIN(ORTHDION_PHASE_BACK_REDUCE);
-    if (fast) OD_TRY(od::launch_reduce_r(d, back_direct ? v.ra : v.part, b.splits_back, v.ra, v.rh, v.scal, v.info, st));
+    if (fast && !copy_in_kernel) OD_TRY(od::launch_reduce_r(d, back_direct ? v.ra : v.part, b.splits_back, v.ra, v.rh, v.scal, v.info, st));
     else if (!back_direct) OD_TRY(od::launch_reduce(d.nb, v.part, b.splits_back, (int64_t)d.n * d.r, v.ra, st));
     OD_PHASE_END(ORTHDION_PHASE_BACK_REDUCE);
     if (diag) OD_TRY(od::launch_diag_cols(d.nb, d.n, d.r, v.ra, v.part, b.slabs, v.dacc, st));

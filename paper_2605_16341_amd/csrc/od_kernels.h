@@ -90,8 +90,13 @@ int stream_tile_cols(int r);
 hipError_t launch_proj(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal,
                        WsArr part, int splits, HalfArr qht, hipStream_t st);
 // R partials: part[split][n][r] = (M+G)[k-range, :]^T * P[k-range, :]
+// Where back_writes_fp16_copy holds (fast precision, one split, the direct-to-LDS kernel) and
+// `rh`, `info` are given, the launch also writes R as pre-scaled fp16 and checks its range, and
+// launch_reduce_r is not needed.
+bool back_writes_fp16_copy(const ClassDims& d, Prec prec, int splits);
 hipError_t launch_back(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal,
-                       WsArr p, WsArr part, int splits, HalfArr pht, hipStream_t st);
+                       WsArr p, WsArr part, int splits, HalfArr pht, hipStream_t st, HalfArr rh = HalfArr{nullptr, 0},
+                       int* info = nullptr);
 // out[i] = sum_s part[s * count + i], i < count, per matrix
 hipError_t launch_reduce(int nb, WsArr part, int splits, int64_t count, WsArr out, hipStream_t st, Pred pred = Pred{nullptr, 0, 0.f, 0});
 // the same for R (n x r), also written as pre-scaled fp16 [n][r]; with one split `part` may be

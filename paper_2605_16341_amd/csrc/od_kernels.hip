@@ -1326,7 +1326,8 @@ __global__ __launch_bounds__(128 * WI, (WI == 2 ? 2 : 1)) void k_efx_d(ClassDims
 // One barrier per step.  Waits count loads: per step and wave kCB factor loads, then kNR raw loads.
 // ------------------------------------------------------------------------------------
 template <bool TRANS, int NT, int SB>
-__global__ __launch_bounds__(512, 1) void k_stream_d(ClassDims d, MatPtrs ptrs, const float* scal, WsArr part, int splits, HalfArr fh) {
+__global__ __launch_bounds__(512, 1) void k_stream_d(ClassDims d, MatPtrs ptrs, const float* scal, WsArr part, int splits, HalfArr fh, HalfArr rh,
+                                                  int* info) {
   constexpr int MT = 128, KT = 32, ROWB = 64, SR = 3;
   constexpr int FN = NT / 128;                                // 32-column accumulator blocks per wave
   constexpr int B_STAGE = NT * ROWB, RAW_M = MT * KT * 4, RAW_G = MT * KT * 2, RAW_STAGE = RAW_M + RAW_G;
@@ -1519,6 +1520,28 @@ __global__ __launch_bounds__(512, 1) void k_stream_d(ClassDims d, MatPtrs ptrs, 
         const int col = tn * NT + wn * (NT / 4) + fn * 32 + acc_col(lane);
         if (row < Mdim && col < d.r) out[(int64_t)row * d.r + col] = acc[fm][fn][v] * inv;
       }
+  // A single split of the back-projection is R itself: its pre-scaled fp16 copy (what
+  // k_reduce_r would make in a pass of its own) is written here, with the same range check.
+  if (TRANS && rh.base != nullptr) {
+    const float sr = r_scale(d, scal, z) * inv;
+    uint16_t* dh = rh.base + (int64_t)z * rh.stride;
+    float rmax = 0.f;
+#pragma unroll
+    for (int fm = 0; fm < 2; ++fm)
+#pragma unroll
+      for (int fn = 0; fn < FN; ++fn)
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const int row = tm * MT + wm * 64 + fm * 32 + acc_row(v, lane);
+          const int col = tn * NT + wn * (NT / 4) + fn * 32 + acc_col(lane);
+          if (row < Mdim && col < d.r) {
+            const float x = acc[fm][fn][v] * sr;
+            rmax = fmaxf(rmax, fabsf(x));
+            dh[(int64_t)row * d.r + col] = __builtin_bit_cast(uint16_t, (_Float16)__builtin_amdgcn_fmed3f(x, -65504.f, 65504.f));
+          }
+        }
+    if (!(rmax <= 65504.f)) atomicOr(&info[z * kInfoPerMat + kWarnSlot], kWarnRClipped);
+  }
 }
 
 // ====================================================================================
@@ -1625,14 +1648,15 @@ static hipError_t proj_g(const ClassDims& d, const MatPtrs& ptrs, Prec prec, con
   return proj_t<TileWide, NumF16, GSrc>(d, ptrs, scal, part, splits, qht, st);
 }
 template <bool TRANS, int NT>
-static hipError_t stream_d_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr part, int splits, HalfArr fh, hipStream_t st) {
+static hipError_t stream_d_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, WsArr part, int splits, HalfArr fh, hipStream_t st,
+                             HalfArr rh = HalfArr{nullptr, 0}, int* info = nullptr) {
   constexpr int SB = NT == 512 ? 2 : 3;
   constexpr int lds = SB * NT * 64 + 3 * (128 * 32 * 6) + 2 * (TRANS ? 32 * 320 : 128 * 64);
   hipError_t e = allow_lds(k_stream_d<TRANS, NT, SB>, lds);
   if (e != hipSuccess) return e;
   const int Mdim = TRANS ? d.n : d.m;
   dim3 grid(((Mdim + 127) / 128) * ((d.r + NT - 1) / NT), splits, d.nb);
-  launch_timed(k_stream_d<TRANS, NT, SB>, grid, dim3(512), lds, st, d, ptrs, scal, part, splits, fh);
+  launch_timed(k_stream_d<TRANS, NT, SB>, grid, dim3(512), lds, st, d, ptrs, scal, part, splits, fh, rh, info);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -1674,10 +1698,16 @@ static hipError_t back_g(const ClassDims& d, const MatPtrs& ptrs, Prec prec, con
   if (d.r > 256) return back_t<TileHuge, NumF16, GSrc, 2>(d, ptrs, scal, p, part, splits, pht, st);
   return back_t<TileWide, NumF16, GSrc>(d, ptrs, scal, p, part, splits, pht, st);
 }
-hipError_t launch_back(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p, WsArr part, int splits, HalfArr pht, hipStream_t st) {
-  if (prec == PREC_F16 && stream_kernel_eligible(d))
-    return stream_tile_cols(d.r) == 256 ? stream_d_t<true, 256>(d, ptrs, scal, part, splits, pht, st)
-                                        : stream_d_t<true, 512>(d, ptrs, scal, part, splits, pht, st);
+bool back_writes_fp16_copy(const ClassDims& d, Prec prec, int splits) { return prec == PREC_F16 && splits == 1 && stream_kernel_eligible(d); }
+
+hipError_t launch_back(const ClassDims& d, const MatPtrs& ptrs, Prec prec, const float* scal, WsArr p, WsArr part, int splits, HalfArr pht, hipStream_t st,
+                       HalfArr rh, int* info) {
+  if (prec == PREC_F16 && stream_kernel_eligible(d)) {
+    const HalfArr none{nullptr, 0};
+    const bool copy = back_writes_fp16_copy(d, prec, splits) && rh.base != nullptr && info != nullptr;
+    return stream_tile_cols(d.r) == 256 ? stream_d_t<true, 256>(d, ptrs, scal, part, splits, pht, st, copy ? rh : none, info)
+                                        : stream_d_t<true, 512>(d, ptrs, scal, part, splits, pht, st, copy ? rh : none, info);
+  }
   return d.g_bf16 ? back_g<SrcBF16>(d, ptrs, prec, scal, p, part, splits, pht, st) : back_g<SrcF32>(d, ptrs, prec, scal, p, part, splits, pht, st);
 }
 
