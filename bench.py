@@ -57,6 +57,7 @@ def parse_args():
     ap.add_argument("--precision", default="auto", choices=["auto", "fast", "exact"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-sweep", action="store_true")
+    ap.add_argument("--groups", type=int, default=0, choices=[0, 1, 2], help="0: the library chooses")
     ap.add_argument("--pool", type=int, default=4, help="distinct gradients per matrix cycled through")
     return ap.parse_args()
 
@@ -171,7 +172,7 @@ def cpu_baseline(w, variant):
                       f"its multiplicity: " + "; ".join(parts)}
 
 
-def measure(torch, binding, synth, dev, name, variant, precision, steps, warmup, pool):
+def measure(torch, binding, synth, dev, name, variant, precision, steps, warmup, pool, groups=0):
     """Times `steps` steps of one workload; returns the fields of its bench record."""
     from paper_2605_16341_amd.device_inputs import device_gradients, device_state, to_device
     w = synth.WORKLOADS[name]
@@ -193,7 +194,7 @@ def measure(torch, binding, synth, dev, name, variant, precision, steps, warmup,
         data = "synthetic (seeded, generated on device; Gaussian stand-ins for the singular-vector factors)"
     torch.cuda.synchronize()
 
-    opt = binding.OrthDion(w.shapes, w.r, x_dtype=w.x_dtype, variant=variant, precision=precision, mu=w.mu, lr=w.lr)
+    opt = binding.OrthDion(w.shapes, w.r, x_dtype=w.x_dtype, variant=variant, precision=precision, mu=w.mu, lr=w.lr, groups=groups)
     sh = torch.cuda.current_stream().cuda_stream
     xs = [t.data_ptr() for t in X]; ms = [t.data_ptr() for t in M]; qs = [t.data_ptr() for t in Q]
     gs = [[Gpool[i][p].data_ptr() for i in range(nmat)] for p in range(pool)]
@@ -307,7 +308,7 @@ def main():
     binding.load()
     dev = torch.device("cuda:0")
     try:
-        head = measure(torch, binding, synth, dev, args.workload, args.variant, args.precision, args.steps, args.warmup, args.pool)
+        head = measure(torch, binding, synth, dev, args.workload, args.variant, args.precision, args.steps, args.warmup, args.pool, args.groups)
     except RuntimeError as exc:
         print(f"bench.py: {exc}", file=sys.stderr)
         sys.exit(3)
@@ -350,7 +351,7 @@ def main():
             if name == args.workload:
                 continue
             try:
-                rec = measure(torch, binding, synth, dev, name, args.variant, args.precision, k, 2, 2)
+                rec = measure(torch, binding, synth, dev, name, args.variant, args.precision, k, 2, 2, args.groups)
             except RuntimeError as exc:
                 sweep.append({"workload": name, "error": str(exc)})
                 continue

@@ -22,11 +22,14 @@
  * (HBM) pointers owned by the caller; pointer *arrays* are host arrays.  The library never
  * allocates or frees device memory and never synchronises the device or a stream, except
  * orthdion_get_info / orthdion_get_warnings / orthdion_get_diagnostics, which wait for the
- * stream they are given.  For ranks above 256 in fast precision orthdion_step creates, at its
- * first call that is not under stream capture, one more stream and two events (runtime
- * objects of the handle, released by orthdion_destroy): the guard of the second CholeskyQR
- * pass forks onto it and joins the caller's stream again before the step's remaining kernels,
- * so the caller sees a single stream; under capture both branches are part of the graph.
+ * stream they are given.  orthdion_step creates, at its first call that is not under stream
+ * capture and only when it has a use for them, two more streams and four events (runtime
+ * objects of the handle, released by orthdion_destroy).  Ranks above 256 in fast precision
+ * fork the guard of the second CholeskyQR pass onto one of them; a handle with two groups
+ * (orthdion_config.groups) runs the second group's step on the other.  Every fork is joined
+ * to the caller's stream again before the kernels that need it, at the latest before the call
+ * returns, so the caller sees a single stream; under capture all branches are part of the
+ * graph.
  *
  * Errors: every function returns ORTHDION_OK (0) or a negative orthdion_status; nothing
  * throws or aborts.  Numerical breakdown found on the device (a rank-deficient or
@@ -97,6 +100,12 @@ typedef struct {
   orthdion_precision precision;
   float mu;     /* momentum / error-feedback coefficient, 0 <= mu <= 1                  */
   float lr;     /* step size eta; any scale factor or schedule is folded in by the caller */
+  int32_t groups; /* 0 = chosen by the library (two for a set of several matrices with 2^26 to
+                   * 2^29 elements in all, else one), 1, or 2.  With two groups the launch
+                   * batches are dealt to two sets of about equal work whose steps run side
+                   * by side, one on the caller's stream and one on a stream of the handle:
+                   * what one set leaves idle (its Cholesky chains, short launches) the other
+                   * one uses.  No result depends on it, bit for bit.                        */
 } orthdion_config;
 
 /* Builds a handle for a fixed set of nmat matrices (host-side planning only; the handle

@@ -47,7 +47,7 @@ class orthdion_matdesc(ctypes.Structure):
 class orthdion_config(ctypes.Structure):
     _fields_ = [("x_dtype", ctypes.c_int), ("g_dtype", ctypes.c_int), ("variant", ctypes.c_int),
                 ("ef", ctypes.c_int), ("precision", ctypes.c_int), ("mu", ctypes.c_float),
-                ("lr", ctypes.c_float)]
+                ("lr", ctypes.c_float), ("groups", ctypes.c_int32)]
 
 
 _lib: Optional[ctypes.CDLL] = None
@@ -145,9 +145,10 @@ def _check(status: int) -> None:
 
 def orthdion_create(shapes: Sequence[Sequence[int]], r, x_dtype: int, g_dtype: int, variant: int = ORTHDION_QR,
                     ef: int = ORTHDION_EF_DION, precision: int = ORTHDION_PREC_AUTO, mu: float = 0.95,
-                    lr: float = 0.01, lds: Optional[Sequence[Sequence[int]]] = None) -> int:
+                    lr: float = 0.01, lds: Optional[Sequence[Sequence[int]]] = None, groups: int = 0) -> int:
     """`shapes` is a list of (m, n); `r` one rank or one per matrix; `lds` optional
-    (ldx, ldg, ldm) per matrix (default n).  Returns the opaque handle as an int."""
+    (ldx, ldg, ldm) per matrix (default n); `groups` 0 (the library chooses), 1 or 2.  Returns
+    the opaque handle as an int."""
     lib = load()
     nmat = len(shapes)
     ranks = [int(r)] * nmat if isinstance(r, int) else [int(v) for v in r]
@@ -155,7 +156,7 @@ def orthdion_create(shapes: Sequence[Sequence[int]], r, x_dtype: int, g_dtype: i
     for i, (m, n) in enumerate(shapes):
         ld = lds[i] if lds is not None else (n, n, n)
         descs[i] = orthdion_matdesc(int(m), int(n), ranks[i], int(ld[0]), int(ld[1]), int(ld[2]))
-    cfg = orthdion_config(int(x_dtype), int(g_dtype), int(variant), int(ef), int(precision), float(mu), float(lr))
+    cfg = orthdion_config(int(x_dtype), int(g_dtype), int(variant), int(ef), int(precision), float(mu), float(lr), int(groups))
     handle = ctypes.c_void_p()
     _check(lib.orthdion_create(ctypes.byref(handle), descs, nmat, ctypes.byref(cfg)))
     return handle.value
@@ -270,7 +271,7 @@ class OrthDion:
     (device memory and the current stream come from torch; nothing else does)."""
 
     def __init__(self, shapes, r, x_dtype="bf16", g_dtype=None, variant="qr", ef="dion", precision="auto",
-                 mu=0.95, lr=0.01, device="cuda:0"):
+                 mu=0.95, lr=0.01, device="cuda:0", groups=0):
         import torch
         g_dtype = g_dtype or x_dtype
         dt = {"f32": ORTHDION_F32, "bf16": ORTHDION_BF16}
@@ -283,7 +284,7 @@ class OrthDion:
                                       {"qr": ORTHDION_QR, "colnorm": ORTHDION_COLNORM}[variant],
                                       {"dion": ORTHDION_EF_DION, "paper": ORTHDION_EF_PAPER, "polyak": ORTHDION_EF_POLYAK}[ef],
                                       {"auto": ORTHDION_PREC_AUTO, "fast": ORTHDION_PREC_FAST,
-                                       "exact": ORTHDION_PREC_EXACT}[precision], mu, lr)
+                                       "exact": ORTHDION_PREC_EXACT}[precision], mu, lr, groups=groups)
         self.workspace_bytes = orthdion_workspace_bytes(self.handle)
         self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=device)
         self._torch = torch

@@ -3,6 +3,7 @@
 // in the caller's workspace.
 #include "../../include/orthdion.h"
 
+#include <algorithm>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -20,6 +21,14 @@ using od::WsArr;
 using od::HalfArr;
 
 constexpr size_t kAlign = 256;
+// Two groups by default between these numbers of matrix elements.  A set below is a chain of
+// short launches, where the fork and join of the second stream cost more than the overlap
+// returns.  A set above comes in launch batches of many matrices, whose kernels fill the chip
+// by themselves: side by side they mostly compete (measured on 96 matrices of rank 512: 2 % less
+// time per step, and no kernel's time stamps mean anything any more), whereas a few matrices of
+// large rank gain 13 %: there the Cholesky chains and the one-matrix launches leave room.
+constexpr double kGroupMinElements = 64.0 * 1024 * 1024;
+constexpr double kGroupMaxElements = 512.0 * 1024 * 1024;
 
 size_t align_up(size_t v) { return (v + kAlign - 1) / kAlign * kAlign; }
 
@@ -42,6 +51,7 @@ struct Batch {
 // matrices: the class owns the r x r arrays, every batch a contiguous range of slices.
 struct RankClass {
   int r, count, slot_base;
+  int group;                         // which of the two groups a large set of one rank is dealt into
   int64_t st_rr;
   std::vector<int> batches;
   size_t off_gram, off_tp1, off_tp2, off_tq1, off_tq2, off_w, off_tmp;
@@ -96,6 +106,12 @@ struct orthdion_ctx {
   hipStream_t side = nullptr;
   hipEvent_t ev_fork = nullptr, ev_join = nullptr;
   bool side_tried = false;
+  // Two groups: the batches are dealt to two sets of about equal work, each with rank classes
+  // of its own, and the two sets run side by side on the caller's stream and on `group_stream`
+  // (see orthdion_step_impl).
+  bool two_groups = false;
+  hipStream_t group_stream = nullptr;
+  hipEvent_t ev_group_fork = nullptr, ev_group_join = nullptr;
 };
 
 static bool ensure_side_stream(orthdion_ctx* h, hipStream_t st) {
@@ -106,12 +122,18 @@ static bool ensure_side_stream(orthdion_ctx* h, hipStream_t st) {
   if (cs != hipStreamCaptureStatusNone) return false;        // nothing is created under capture; a later call may
   h->side_tried = true;
   if (hipStreamCreateWithFlags(&h->side, hipStreamNonBlocking) != hipSuccess) { h->side = nullptr; (void)hipGetLastError(); return false; }
-  if (hipEventCreateWithFlags(&h->ev_fork, hipEventDisableTiming) != hipSuccess ||
-      hipEventCreateWithFlags(&h->ev_join, hipEventDisableTiming) != hipSuccess) {
-    if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
-    if (h->ev_join) (void)hipEventDestroy(h->ev_join);
+  bool ok = hipStreamCreateWithFlags(&h->group_stream, hipStreamNonBlocking) == hipSuccess;
+  if (!ok) h->group_stream = nullptr;
+  hipEvent_t* const events[4] = {&h->ev_fork, &h->ev_join, &h->ev_group_fork, &h->ev_group_join};
+  for (hipEvent_t* e : events) ok = ok && hipEventCreateWithFlags(e, hipEventDisableTiming) == hipSuccess;
+  if (!ok) {
+    for (hipEvent_t* e : events) {
+      if (*e) (void)hipEventDestroy(*e);
+      *e = nullptr;
+    }
+    if (h->group_stream) (void)hipStreamDestroy(h->group_stream);
     (void)hipStreamDestroy(h->side);
-    h->side = nullptr; h->ev_fork = nullptr; h->ev_join = nullptr;
+    h->side = nullptr; h->group_stream = nullptr;
     (void)hipGetLastError();
     return false;
   }
@@ -141,6 +163,7 @@ static int check_config(const orthdion_config* c) {
     return ORTHDION_E_INVALID_ARG;
   if (!std::isfinite(c->mu) || c->mu < 0.f || c->mu > 1.f) return ORTHDION_E_INVALID_ARG;
   if (!std::isfinite(c->lr)) return ORTHDION_E_INVALID_ARG;
+  if (c->groups < 0 || c->groups > 2) return ORTHDION_E_INVALID_ARG;
   return ORTHDION_OK;
 }
 
@@ -201,14 +224,18 @@ static int create_impl(orthdion_handle* out, const orthdion_matdesc* mats, int32
   h->slot_of.assign(nmat, -1);
 
   // shape classes, in order of first appearance, cut into batches
+  auto same_shape = [](const ClassDims& d, const orthdion_matdesc& a) {
+    return d.m == a.m && d.n == a.n && d.r == a.r && d.ldx == a.ldx && d.ldg == a.ldg && d.ldm == a.ldm;
+  };
+  double total_elems = 0.0;
+  for (int i = 0; i < nmat; ++i) total_elems += (double)mats[i].m * (double)mats[i].n;
+  int groups = cfg->groups;
+  if (groups == 0) groups = (nmat >= 2 && total_elems >= kGroupMinElements && total_elems < kGroupMaxElements) ? 2 : 1;
   for (int i = 0; i < nmat; ++i) {
     const orthdion_matdesc& a = mats[i];
     int found = -1;
     for (size_t b = 0; b < h->batches.size(); ++b) {
-      const ClassDims& d = h->batches[b].d;
-      if (d.m == a.m && d.n == a.n && d.r == a.r && d.ldx == a.ldx && d.ldg == a.ldg && d.ldm == a.ldm &&
-          (int)h->batches[b].members.size() < od::kMaxBatchHost)
-        found = (int)b;
+      if (same_shape(h->batches[b].d, a) && (int)h->batches[b].members.size() < od::kMaxBatchHost) found = (int)b;
     }
     if (found < 0) {
       Batch nb = {};
@@ -231,16 +258,34 @@ static int create_impl(orthdion_handle* out, const orthdion_matdesc* mats, int32
   h->off_diag = off; off = align_up(off + (size_t)nmat * od::kDiagPerMat * sizeof(float));
   h->off_dacc = off; off = align_up(off + (size_t)nmat * od::kDaccPerMat * sizeof(double));
   h->off_dpart = off; off = align_up(off + (size_t)nmat * od::kDiagBlocks * 4 * sizeof(double));
-  // rank classes in order of first appearance; table rows (slots) run class by class
+  // Groups: the heaviest batch first, each to the group with less work so far (m n per matrix
+  // measures a batch's step).  A set with a single batch stays one group.
+  std::vector<int> group_of(h->batches.size(), 0);
+  for (Batch& b : h->batches) b.d.nb = (int)b.members.size();
+  if (groups == 2 && h->batches.size() >= 2) {
+    std::vector<int> order(h->batches.size());
+    for (size_t k = 0; k < order.size(); ++k) order[k] = (int)k;
+    auto weight = [&](int k) { const ClassDims& d = h->batches[k].d; return (double)d.m * d.n * d.nb; };
+    std::stable_sort(order.begin(), order.end(), [&](int x, int y) { return weight(x) > weight(y); });
+    double load[2] = {0.0, 0.0};
+    for (int k : order) {
+      const int g = load[1] < load[0] ? 1 : 0;
+      group_of[k] = g;
+      load[g] += weight(k);
+    }
+    h->two_groups = true;
+  }
+  // rank classes in order of first appearance (one per rank and group); table rows (slots) run
+  // class by class
   for (size_t bi = 0; bi < h->batches.size(); ++bi) {
     Batch& b = h->batches[bi];
-    b.d.nb = (int)b.members.size();
     int found = -1;
     for (size_t c = 0; c < h->classes.size(); ++c)
-      if (h->classes[c].r == b.d.r) found = (int)c;
+      if (h->classes[c].r == b.d.r && h->classes[c].group == group_of[bi]) found = (int)c;
     if (found < 0) {
       RankClass rc = {};
       rc.r = b.d.r;
+      rc.group = group_of[bi];
       rc.st_rr = ((int64_t)b.d.r * b.d.r + 63) / 64 * 64;
       h->classes.push_back(rc);
       found = (int)h->classes.size() - 1;
@@ -706,23 +751,37 @@ extern "C" int orthdion_step_impl(orthdion_handle h, void* const* X, const void*
   };
 
   // Rank class by rank class; inside a class the batches run piece by piece, so that each of
-  // the two Cholesky steps is one launch sequence over all matrices of the rank.  Its time is
+  // the two Cholesky steps is one launch sequence over all matrices of the class.  Its time is
   // booked on the first batch of the class.
-  for (const RankClass& c : h->classes) {
+  const hipStream_t caller_st = st;
+  // pieces of a class between its two Cholesky steps
+  auto class_head = [&](const RankClass& c) -> int {
+    int rc;
+    for (int b2 : c.batches)
+      if ((rc = left_head(b2)) != ORTHDION_OK) return rc;
+    return ORTHDION_OK;
+  };
+  auto class_chol = [&](const RankClass& c, int side, hipStream_t on) -> int {
+    const int bi = c.batches[0];
+    st = on;
+    OD_PHASE_BEGIN(side == 0 ? ORTHDION_PHASE_CHOL_LEFT : ORTHDION_PHASE_CHOL_RIGHT);
+    int rc = class_cholinv(c, ws, side == 0 ? c.off_tp1 : c.off_tq1, side, info_all, on);
+    if (rc != ORTHDION_OK) return rc;
+    OD_PHASE_END(side == 0 ? ORTHDION_PHASE_CHOL_LEFT : ORTHDION_PHASE_CHOL_RIGHT);
+    st = caller_st;
+    return ORTHDION_OK;
+  };
+  // Ranks above 256 in fast precision: the guard (a launch chain over the class that returns at
+  // once for every well-conditioned matrix, then the full product of the flagged ones) runs on
+  // the second stream beside the first-order result of the others; the streams join before
+  // anything reads a factor.  (With two groups side by side the guard stays on its group's
+  // stream: the other group fills the chip meanwhile.)
+  auto class_middle = [&](const RankClass& c, bool fork_guard) -> int {
     int rc;
     const int bi = c.batches[0];
     for (int b2 : c.batches)
-      if ((rc = left_head(b2)) != ORTHDION_OK) return rc;
-    OD_PHASE_BEGIN(ORTHDION_PHASE_CHOL_LEFT);
-    if ((rc = class_cholinv(c, ws, c.off_tp1, 0, info_all, st)) != ORTHDION_OK) return rc;
-    OD_PHASE_END(ORTHDION_PHASE_CHOL_LEFT);
-    for (int b2 : c.batches)
       if ((rc = left_second(b2)) != ORTHDION_OK) return rc;
-    // Ranks above 256 in fast precision: the guard (a launch chain over the class that returns at
-    // once for every well-conditioned matrix, then the full product of the flagged ones) runs on
-    // the second stream beside the first-order result of the others; the streams join before
-    // anything reads a factor.
-    const bool forked = allow_second_stream && fast && guard_is_class_wide(c.r) && ensure_side_stream(h, st);
+    const bool forked = fork_guard && allow_second_stream && fast && guard_is_class_wide(c.r) && ensure_side_stream(h, st);
     if (forked) {
       OD_TRY(hipEventRecord(h->ev_fork, st));
       OD_TRY(hipStreamWaitEvent(h->side, h->ev_fork, 0));
@@ -742,13 +801,16 @@ extern "C" int orthdion_step_impl(orthdion_handle h, void* const* X, const void*
       for (int b2 : c.batches)
         if ((rc = middle(b2, 0)) != ORTHDION_OK) return rc;
     }
-    const bool forked_right = forked && h->cfg.variant == ORTHDION_QR;
+    return ORTHDION_OK;
+  };
+  auto class_tail = [&](const RankClass& c, bool fork_guard) -> int {
+    int rc;
+    const int bi = c.batches[0];
+    bool forked_right = false;
     if (h->cfg.variant == ORTHDION_QR) {
-      OD_PHASE_BEGIN(ORTHDION_PHASE_CHOL_RIGHT);
-      if ((rc = class_cholinv(c, ws, c.off_tq1, 1, info_all, st)) != ORTHDION_OK) return rc;
-      OD_PHASE_END(ORTHDION_PHASE_CHOL_RIGHT);
       for (int b2 : c.batches)
         if ((rc = right_second(b2)) != ORTHDION_OK) return rc;
+      forked_right = fork_guard && allow_second_stream && fast && guard_is_class_wide(c.r) && ensure_side_stream(h, st);
       if (forked_right) {
         OD_TRY(hipEventRecord(h->ev_fork, st));
         OD_TRY(hipStreamWaitEvent(h->side, h->ev_fork, 0));
@@ -767,6 +829,36 @@ extern "C" int orthdion_step_impl(orthdion_handle h, void* const* X, const void*
     }
     for (int b2 : c.batches)
       if ((rc = tail(b2, forked_right ? 3 : 0)) != ORTHDION_OK) return rc;
+    return ORTHDION_OK;
+  };
+
+  // Two groups: the classes of group 1 go to the handle's group stream, which starts after
+  // everything enqueued on the caller's stream so far and is joined before the call returns, so
+  // the caller sees a single stream.  The groups share no matrix and no workspace slice;
+  // whatever one group cannot fill the chip with (its Cholesky chains, the small reductions and
+  // corrections, the last round of every launch) the other group's kernels run beside.
+  const bool side_by_side = h->two_groups && allow_second_stream && ensure_side_stream(h, caller_st);
+  if (side_by_side) {
+    OD_TRY(hipEventRecord(h->ev_group_fork, caller_st));
+    OD_TRY(hipStreamWaitEvent(h->group_stream, h->ev_group_fork, 0));
+  }
+  const bool right_chol = h->cfg.variant == ORTHDION_QR;
+  for (const RankClass& c : h->classes) {
+    int rc;
+    const hipStream_t on = (side_by_side && c.group == 1) ? h->group_stream : caller_st;
+    st = on;
+    if ((rc = class_head(c)) != ORTHDION_OK) return rc;
+    if ((rc = class_chol(c, 0, on)) != ORTHDION_OK) return rc;
+    st = on;
+    if ((rc = class_middle(c, !side_by_side)) != ORTHDION_OK) return rc;
+    if (right_chol && (rc = class_chol(c, 1, on)) != ORTHDION_OK) return rc;
+    st = on;
+    if ((rc = class_tail(c, !side_by_side)) != ORTHDION_OK) return rc;
+  }
+  st = caller_st;
+  if (side_by_side) {
+    OD_TRY(hipEventRecord(h->ev_group_join, h->group_stream));
+    OD_TRY(hipStreamWaitEvent(caller_st, h->ev_group_join, 0));
   }
   if (h->prof_on && h->prof_steps < h->prof_max_steps) h->prof_steps++;
   return ORTHDION_OK;
@@ -962,7 +1054,10 @@ extern "C" int orthdion_destroy(orthdion_handle h) {
     if (e) (void)hipEventDestroy(e);
   if (h->ev_fork) (void)hipEventDestroy(h->ev_fork);
   if (h->ev_join) (void)hipEventDestroy(h->ev_join);
+  if (h->ev_group_fork) (void)hipEventDestroy(h->ev_group_fork);
+  if (h->ev_group_join) (void)hipEventDestroy(h->ev_group_join);
   if (h->side) (void)hipStreamDestroy(h->side);
+  if (h->group_stream) (void)hipStreamDestroy(h->group_stream);
   delete h;
   return ORTHDION_OK;
 }

@@ -15,11 +15,11 @@ class GpuRun:
     """State of a set of matrices on the GPU, stepped by the library."""
 
     def __init__(self, shapes, r, x_dtype, states: Sequence[synth.MatrixState], variant="qr", ef="dion",
-                 precision="auto", mu=0.95, lr=0.01):
+                 precision="auto", mu=0.95, lr=0.01, groups=0):
         import torch
         self.torch = torch
         self.opt = binding.OrthDion(shapes, r, x_dtype=x_dtype, variant=variant, ef=ef, precision=precision,
-                                    mu=mu, lr=lr)
+                                    mu=mu, lr=lr, groups=groups)
         self.X = [to_device(s.X, torch) for s in states]
         self.M = [to_device(s.M, torch) for s in states]
         self.Q = [to_device(s.Q, torch) for s in states]

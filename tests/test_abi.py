@@ -42,7 +42,7 @@ def test_create_validates_shapes_and_config():
             b.orthdion_create([(64, 128)], 16, 1, 1, lds=lds)
         assert e.value.status == b.ORTHDION_E_BAD_SHAPE
     for kw in (dict(mu=1.5), dict(mu=-0.1), dict(mu=float("nan")), dict(lr=float("inf")), dict(variant=7),
-               dict(ef=3), dict(precision=9)):
+               dict(ef=3), dict(precision=9), dict(groups=3), dict(groups=-1)):
         with pytest.raises(b.OrthDionError) as e:
             b.orthdion_create([(64, 64)], 8, 1, 1, **kw)
         assert e.value.status == b.ORTHDION_E_INVALID_ARG, kw

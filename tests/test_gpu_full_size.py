@@ -151,24 +151,56 @@ def test_config5_rank2048_qr_properties_and_sampled_rows():
     assert np.mean(dist != 0) < 0.02 and np.mean(dist > 1) < 1e-3
 
 
-def test_whole_config3_set_runs_in_one_call():
-    """All 96 matrices (4 shape classes, 3 launch batches each) in one handle: every matrix
-    gets orthonormal factors and a finite state."""
+def _whole_set_against_oracle(w, probes):
+    """The whole matrix set in one handle, as bench.py runs it (its launch batches, splits,
+    class-wide factorisations and, where the library chooses them, its two groups): one warm-up
+    step, then a second step that the oracle repeats, from the copied state, for the matrices
+    `probes`; every matrix must come out unflagged, finite and with an orthonormal right factor."""
     import torch
     dev = torch.device("cuda:0")
-    w = synth.WORKLOADS["C3"]
-    X, M, Q, G = [], [], [], []
+    X, M, Q, G0, G1 = [], [], [], [], []
     for i in range(len(w.shapes)):
         x, mom, q = device_state(torch, w, i, dev)
         X.append(x); M.append(mom); Q.append(q)
-        G.append(device_gradients(torch, w, i, 1, dev)[0])
+        g0, g1 = device_gradients(torch, w, i, 2, dev)
+        G0.append(g0); G1.append(g1)
     opt = binding.OrthDion(w.shapes, w.r, x_dtype="bf16", mu=w.mu, lr=w.lr)
-    opt.step(X, G, M, Q)
+    opt.step(X, G0, M, Q)
+    torch.cuda.synchronize()
+    assert opt.info() == [0] * len(w.shapes)
+    before = {i: {"X": to_host(X[i], torch), "M": to_host(M[i], torch), "Q": to_host(Q[i], torch),
+                  "G": to_host(G1[i], torch)} for i in probes}
+    opt.step(X, G1, M, Q)
     torch.cuda.synchronize()
     assert opt.info() == [0] * len(w.shapes)
     eye = torch.eye(w.r, device=dev)
-    for i in range(0, len(w.shapes), 7):
-        assert float((Q[i].T @ Q[i] - eye).abs().max()) < 1e-4
-        assert bool(torch.isfinite(M[i]).all())
-        p = opt.debug_factors(i)["P"]
-        assert float((p.T @ p - eye).abs().max()) < 1e-4
+    for i in range(len(w.shapes)):
+        assert float((Q[i].T @ Q[i] - eye).abs().max()) < 1e-4, i
+        assert bool(torch.isfinite(M[i]).all()), i
+    orc = OrthDionOracle(mu=w.mu, lr=w.lr, variant="qr", x_bf16=True, qr="library" if w.r >= 1024 else "householder")
+    for i in probes:
+        f = opt.debug_factors(i)
+        after = {"X": to_host(X[i], torch), "M": to_host(M[i], torch), "Q": to_host(Q[i], torch),
+                 "P": f["P"].cpu().numpy(), "R": f["R"].cpu().numpy()}
+        b = before[i]
+        o = orc.step(b["X"], b["G"], b["M"].astype(np.float64), b["Q"].astype(np.float64))
+        for key in ("P", "R", "Q", "M"):
+            fro = rel_fro(after[key], o[key])
+            worst = float(np.abs(after[key].astype(np.float64) - o[key]).max() / np.abs(o[key]).max())
+            assert fro <= FRO_SEEN and worst <= MAXABS_TOL[key], (w.name, i, key, fro, worst)
+        mism = float(np.mean(after["X"] != o["X_bits"]))
+        beyond = bf16_gap_beyond(after["X"], o["X_bits"], 1.0, FRO_TOL * w.lr * float(np.abs(o["D"]).max()))
+        assert mism <= 0.01 and beyond == 0.0, (w.name, i, mism, beyond)
+    opt.close()
+
+
+def test_whole_config3_set_in_one_call_against_the_oracle():
+    """All 96 matrices (four launch batches of 24): the oracle repeats the step of the second
+    matrix of one batch and of the last matrix of another."""
+    _whole_set_against_oracle(synth.WORKLOADS["C3"], probes=(5, 95))
+
+
+def test_whole_config4_set_in_one_call_against_the_oracle():
+    """The five matrices of rank 1024 in one handle: four launch batches dealt to two groups
+    that step side by side; the oracle repeats the step of one matrix of either group."""
+    _whole_set_against_oracle(synth.WORKLOADS["C4"], probes=(1, 3))

@@ -348,21 +348,46 @@ def test_orthonormality_and_qr_uniqueness_from_the_debug_factors():
     assert abs(np.sum(b * (p @ q.T)) / np.trace(t_q) - 1.0) < 1e-4
 
 
-@pytest.mark.parametrize("shapes,r", [(((256, 192), (128, 320)), 32), (((640, 384), (384, 512)), 320),
-                                      (((1024, 640), (640, 1024)), 512)])
-def test_step_replayed_from_a_hip_graph_matches_eager_bit_for_bit(shapes, r):
+@pytest.mark.parametrize("r,variant", [(16, "qr"), (64, "qr"), (320, "qr"), (64, "colnorm")])
+def test_two_groups_side_by_side_leave_the_bits_of_one_group(r, variant):
+    """A handle with two groups deals its launch batches to two sets that step side by side on
+    two streams.  The batches themselves are the same, so every output must be bit-identical
+    to the one-group run (seven matrices of four shapes: both groups hold several batches; at
+    r = 320 each group also runs the class-wide guard of the second CholeskyQR pass)."""
+    m = 384 if r >= 320 else 264
+    shapes = ((m, 392), (520, m), (m, 392), (m, m), (520, m), (m, 392), (648, 392))
+    w = synth.Workload("groups", shapes, r=r, x_dtype="bf16", steps=3)
+    nmat = len(shapes)
+    streams = [synth.make_stream(w, i) for i in range(nmat)]
+    states = [synth.make_state(w, i) for i in range(nmat)]
+    runs = []
+    for groups in (1, 2):
+        gpu = GpuRun(w.shapes, w.r, "bf16", states, variant=variant, mu=w.mu, lr=w.lr, groups=groups)
+        for t in range(w.steps):
+            assert gpu.step([s.gradient(t) for s in streams]) == [0] * nmat
+        runs.append([gpu.fetch(i) for i in range(nmat)])
+    for a, b in zip(*runs):
+        for key in ("X", "M", "Q", "P", "R"):
+            assert a[key].tobytes() == b[key].tobytes(), key
+
+
+@pytest.mark.parametrize("shapes,r,groups", [(((256, 192), (128, 320)), 32, 0), (((640, 384), (384, 512)), 320, 0),
+                                             (((1024, 640), (640, 1024)), 512, 0),
+                                             (((640, 384), (384, 512), (640, 384)), 320, 2)])
+def test_step_replayed_from_a_hip_graph_matches_eager_bit_for_bit(shapes, r, groups):
     """orthdion_step only enqueues kernels (no allocation, no synchronisation, no memset), so
     it can be captured once and replayed.  Every replay, with eager work and synchronisation
     in between, must leave exactly the bits an eager twin computes from the same inputs.
     The ranks above 256 fork the guard of the second CholeskyQR pass onto the library's second
-    stream and join it again: the capture must hold both branches."""
+    stream and join it again, and a handle with two groups runs one of them on a third stream:
+    the capture must hold all branches."""
     import torch
     w = synth.Workload("graph", shapes, r=r, x_dtype="bf16", steps=4)
     nmat = len(w.shapes)
     streams = [synth.make_stream(w, i) for i in range(nmat)]
     states = [synth.make_state(w, i) for i in range(nmat)]
-    eager = GpuRun(w.shapes, w.r, w.x_dtype, states, mu=w.mu, lr=w.lr)
-    twin = GpuRun(w.shapes, w.r, w.x_dtype, states, mu=w.mu, lr=w.lr)
+    eager = GpuRun(w.shapes, w.r, w.x_dtype, states, mu=w.mu, lr=w.lr, groups=groups)
+    twin = GpuRun(w.shapes, w.r, w.x_dtype, states, mu=w.mu, lr=w.lr, groups=groups)
     gbuf = [to_device(st.gradient(0), torch) for st in streams]       # static gradient buffers of the graph
     side = torch.cuda.Stream()
     # one eager step on the capture stream first (lazy one-time set-up must not be captured)
