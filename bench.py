@@ -263,7 +263,7 @@ def measure(torch, binding, synth, dev, name, variant, precision, steps, warmup,
     per_launch_ms = dom_ms / max(dom_launches, 1)
     step_bytes, step_flops, step_flops_qr = step_work(w, variant)
     rec = {
-        "workload": w.name, "variant": variant, "steps": steps, "ms_per_step": ms_per_step, "steps_per_s": steps / elapsed,
+        "workload": w.name, "groups_used": opt.groups, "variant": variant, "steps": steps, "ms_per_step": ms_per_step, "steps_per_s": steps / elapsed,
         "ms_per_step_without_events": ms_per_step_plain,
         "data": data, "nmat": nmat, "r": w.r, "elements": w.elements, "x_dtype": w.x_dtype, "mu": w.mu, "lr": w.lr,
         "shapes": sorted({f"{m}x{n}" for m, n in w.shapes}), "fast_path": fast_path,
@@ -340,7 +340,7 @@ def main():
         "data": head["data"],
         "config": {"workload": head["workload"], "matrices": head["nmat"], "shapes": head["shapes"], "r": head["r"],
                    "x_g_dtype": head["x_dtype"], "state_dtype": "f32", "variant": args.variant, "ef": "dion",
-                   "mu": head["mu"], "lr": head["lr"], "precision": args.precision, "elements": head["elements"]},
+                   "mu": head["mu"], "lr": head["lr"], "precision": args.precision, "groups": head["groups_used"], "elements": head["elements"]},
         "roofline": head["roofline"], "whole_step": head["whole_step"],
         "kernel_group_ms_per_step_warmup": head["kernel_group_ms_per_step_warmup"],
         "phase_ms_per_step_warmup": head["phase_ms_per_step_warmup"],
@@ -356,7 +356,7 @@ def main():
                 sweep.append({"workload": name, "error": str(exc)})
                 continue
             rf, ws = rec["roofline"], rec["whole_step"]
-            sweep.append({"workload": name, "r": rec["r"], "steps": k, "ms_per_step": rec["ms_per_step"],
+            sweep.append({"workload": name, "r": rec["r"], "groups": rec["groups_used"], "steps": k, "ms_per_step": rec["ms_per_step"],
                           "ms_per_step_without_events": rec["ms_per_step_without_events"],
                           "steps_per_s": rec["steps_per_s"], "dominant_kernel": rf["kernel"], "bound": rf["bound"],
                           "kernel_frac": rf["frac"], "kernel_hbm_frac": rf["hbm_frac"], "kernel_mfma_frac": rf["mfma_frac"],

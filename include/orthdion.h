@@ -118,6 +118,10 @@ int orthdion_create(orthdion_handle* out, const orthdion_matdesc* mats, int32_t 
  * Its contents are meaningless between steps except for the debug layout below. */
 size_t orthdion_workspace_bytes(orthdion_handle h);
 
+/* 1 or 2: the number of groups the handle's matrices were dealt into (orthdion_config.groups;
+ * 2 only when the set has at least two launch batches); 0 for a NULL handle. */
+int32_t orthdion_get_groups(orthdion_handle h);
+
 int orthdion_set_lr(orthdion_handle h, float lr);
 int orthdion_set_mu(orthdion_handle h, float mu);
 int orthdion_set_variant(orthdion_handle h, orthdion_variant v);

@@ -29,7 +29,8 @@ EXPORTS = ["orthdion_create", "orthdion_workspace_bytes", "orthdion_set_lr", "or
            "orthdion_set_variant", "orthdion_step", "orthdion_get_info", "orthdion_workspace_layout",
            "orthdion_profile_begin", "orthdion_profile_end", "orthdion_set_diagnostics",
            "orthdion_get_diagnostics", "orthdion_rank_policy", "orthdion_resize_q", "orthdion_strerror",
-           "orthdion_destroy", "orthdion_step_static", "orthdion_static_scratch_bytes", "orthdion_get_warnings"]
+           "orthdion_destroy", "orthdion_step_static", "orthdion_static_scratch_bytes", "orthdion_get_warnings",
+           "orthdion_get_groups"]
 
 DIAG = ["b_norm", "r_norm", "tracking_error", "residual_ratio", "inner", "nu", "erank", "g_norm"]
 ORTHDION_NDIAG = len(DIAG)
@@ -86,6 +87,8 @@ def load() -> ctypes.CDLL:
     lib.orthdion_create.restype = ctypes.c_int
     lib.orthdion_workspace_bytes.argtypes = [vp]
     lib.orthdion_workspace_bytes.restype = sz
+    lib.orthdion_get_groups.argtypes = [vp]
+    lib.orthdion_get_groups.restype = ctypes.c_int32
     lib.orthdion_set_lr.argtypes = [vp, ctypes.c_float]
     lib.orthdion_set_lr.restype = ctypes.c_int
     lib.orthdion_set_mu.argtypes = [vp, ctypes.c_float]
@@ -164,6 +167,10 @@ def orthdion_create(shapes: Sequence[Sequence[int]], r, x_dtype: int, g_dtype: i
 
 def orthdion_workspace_bytes(handle: int) -> int:
     return int(load().orthdion_workspace_bytes(handle))
+
+
+def orthdion_get_groups(handle: int) -> int:
+    return int(load().orthdion_get_groups(handle))
 
 
 def orthdion_set_lr(handle: int, lr: float) -> None:
@@ -286,6 +293,7 @@ class OrthDion:
                                       {"auto": ORTHDION_PREC_AUTO, "fast": ORTHDION_PREC_FAST,
                                        "exact": ORTHDION_PREC_EXACT}[precision], mu, lr, groups=groups)
         self.workspace_bytes = orthdion_workspace_bytes(self.handle)
+        self.groups = orthdion_get_groups(self.handle)
         self.workspace = torch.empty(self.workspace_bytes, dtype=torch.uint8, device=device)
         self._torch = torch
 

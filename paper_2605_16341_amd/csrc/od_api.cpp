@@ -372,6 +372,8 @@ static int create_impl(orthdion_handle* out, const orthdion_matdesc* mats, int32
 
 extern "C" size_t orthdion_workspace_bytes(orthdion_handle h) { return h ? h->ws_bytes : 0; }
 
+extern "C" int32_t orthdion_get_groups(orthdion_handle h) { return h ? (h->two_groups ? 2 : 1) : 0; }
+
 extern "C" int orthdion_set_lr(orthdion_handle h, float lr) {
   if (!h) return ORTHDION_E_NULL_PTR;
   if (!std::isfinite(lr)) return ORTHDION_E_INVALID_ARG;
