@@ -494,8 +494,11 @@ OD_DEV void chol256_block(const CholArgs& a, int z, char* lds_raw) {
   }
   lds_barrier();
   bool expired = false;
-  for (int J = 0; J < nt; ++J) {
-    if (diag_wave) {
+  // One loop per role (the branch is wave-uniform and both loops pass the same nt barriers): in
+  // the diagonal wave's loop the workers' accumulators are dead, so its serial chain keeps its
+  // operands in registers.
+  if (diag_wave) {
+    for (int J = 0; J < nt; ++J) {
       // ---- the serial chain stays in this wave: T(J, J+1) = W_JJ^T S(J, J+1) from the stash,
       // tile (J+1, J+1) -= T^T T (both fp32 products with the accumulator as k-side operand,
       // see panel_tile), then its factorisation.  The workers form T(J, J+1) again for the panel.
@@ -523,7 +526,11 @@ OD_DEV void chol256_block(const CholArgs& a, int z, char* lds_raw) {
         for (int v = 0; v < 16; ++v) dn = mfma_f32_k2(-t1[v], t1[v], dn);
         do_diag(J + 1, dn);
       }
-    } else {
+      // the next step rewrites the panels and the other Wt buffer
+      lds_barrier();
+    }
+  } else {
+    for (int J = 0; J < nt; ++J) {
       // ---- (b) row J of T and row J of V; the tile the diagonal wave waits for goes first
       const float* wt = Wt + (J & 1) * kCTileF;
       f32x4 mrow[4];
@@ -556,9 +563,8 @@ OD_DEV void chol256_block(const CholArgs& a, int z, char* lds_raw) {
           }
         }
       }
+      lds_barrier();
     }
-    // the next step rewrites the panels and the other Wt buffer
-    lds_barrier();
   }
   // a wait that ran out means a tile was used before its producer finished: the factors of this
   // matrix are wrong, which the breakdown word says (the warning bit says why)
