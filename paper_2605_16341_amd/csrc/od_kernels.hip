@@ -557,28 +557,37 @@ __global__ __launch_bounds__(kSmallRows) void k_small_first_pass(int rows, int r
   for (int base = kbeg; base < kend; base += kSmallRows) {
     const int row = base + tid;
     const bool valid = row < kend;
-    float x[32];
+    // this thread's row of A waits in its own row of S (which takes the row of a1 further down)
+    float* xs = S + tid * kSmallPitch;
 #pragma unroll
     for (int j4 = 0; j4 < 8; ++j4) {
       f32x4 v4 = {0.f, 0.f, 0.f, 0.f};
       if (valid && 4 * j4 < r) v4 = *reinterpret_cast<const f32x4*>(A + (int64_t)row * r + 4 * j4);
-#pragma unroll
-      for (int e = 0; e < 4; ++e) x[4 * j4 + e] = v4[e];
+      *reinterpret_cast<f32x4*>(xs + 4 * j4) = v4;
     }
     // the first rows are requested before the wait for the factorisation
     if (first) { __syncthreads(); first = false; }
-    // o = x W, W upper triangular: column block jb takes k <= 4 jb + 3
+    // o = x W, W upper triangular: column block jb takes k <= 4 jb + 3.  Four k per turn of a
+    // loop that stays rolled: unrolled, all 144 reads of W were issued ahead of the arithmetic
+    // and a quarter of them spilled to scratch memory.
     f32x4 o[8];
 #pragma unroll
     for (int jb = 0; jb < 8; ++jb) o[jb] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll 1
+    for (int kb = 0; kb < 8; ++kb) {
+      const f32x4 x4 = *reinterpret_cast<const f32x4*>(xs + 4 * kb);
 #pragma unroll
-    for (int k = 0; k < 32; ++k)
+      for (int jb = 0; jb < 8; ++jb) {
+        if (jb >= kb) {
 #pragma unroll
-      for (int jb = k / 4; jb < 8; ++jb) {
-        const f32x4 w4 = *reinterpret_cast<const f32x4*>(Wl + k * kSmallPitch + 4 * jb);
+          for (int i = 0; i < 4; ++i) {
+            const f32x4 w4 = *reinterpret_cast<const f32x4*>(Wl + (4 * kb + i) * kSmallPitch + 4 * jb);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) o[jb][e] = fmaf(x[k], w4[e], o[jb][e]);
+            for (int e = 0; e < 4; ++e) o[jb][e] = fmaf(x4[i], w4[e], o[jb][e]);
+          }
+        }
       }
+    }
 #pragma unroll
     for (int jb = 0; jb < 8; ++jb) {
       if (valid && 4 * jb < r) *reinterpret_cast<f32x4*>(O + (int64_t)row * r + 4 * jb) = o[jb];
