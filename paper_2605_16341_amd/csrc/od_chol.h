@@ -4,8 +4,8 @@
 // Used by the CholeskyQR orthogonalisation (orth() of Alg. 1 lines 2 and 4): T is the
 // triangular factor of the thin QR, W turns the triangular solve into a product.
 //
-// Layout of the computation (7 waves: wave 3 runs the serial chain of diagonal tiles alone
-// on its SIMD, the other six are workers)
+// Layout of the computation (8 waves: wave 3 runs the serial chain of diagonal tiles, the
+// other seven are workers)
 //   * The block is cut into 32 x 32 tiles; the tiles (I, K) with I < K are kept as
 //     matrix-core accumulators (16 registers per lane: register v of lane l is row
 //     8 (v / 4) + 4 (l / 32) + v % 4, column l % 32), spread over the workers so that every
@@ -43,9 +43,10 @@ constexpr int kCholMax = 256;          // largest block one workgroup factors
 constexpr int kCT = 32;                // tile size
 constexpr int kCNT = kCholMax / kCT;   // 8 tiles per side
 constexpr int kCTiles = kCNT * (kCNT + 1) / 2;   // 36
-constexpr int kCholThreads = 448;      // 7 waves
-constexpr int kCholDiagWave = 3;       // alone on its SIMD (waves 0..2 and 4..6 pair up on the other three)
-constexpr int kCSlots = 6;             // off-diagonal tiles per worker (28 over 6 workers: 4 to 6)
+constexpr int kCholThreads = 512;      // 8 waves: two per SIMD
+constexpr int kCholDiagWave = 3;       // the serial chain; the other seven are workers
+constexpr int kCWorkers = 7;
+constexpr int kCSlots = 4;             // off-diagonal tiles per worker: 28 over 7 workers, four each
 constexpr int kCPitch = 36;            // floats per row of an fp32 LDS tile (16-byte aligned, conflict free)
 constexpr int kCTileF = kCT * kCPitch; // floats per fp32 LDS tile
 constexpr int kPPitch = 80;            // bytes per row of a pre-split operand tile (32 bf16 + pad)
@@ -73,12 +74,16 @@ struct CholArgs {
 
 // tile (I, K), I < K, of slot s of worker u, four bits per slot, 15 = no tile (kept in scalar
 // registers: a table in memory would cost a dependent load per use).  Tile (I, K) belongs
-// to worker (I + K) mod 6.
+// to worker (I + K) mod 7: four tiles each, and in every step the panel tiles (one row and one
+// column of tiles, sums I + K that span eight consecutive values) go to seven different
+// workers but for one pair.
 OD_DEV uint64_t own_rows(int u) {
-  return u == 0 ? 0xff5210ull : u == 1 ? 0x632100ull : u == 2 ? 0xff3210ull : u == 3 ? 0xf43210ull : u == 4 ? 0xff4310ull : u == 5 ? 0xf54210ull : 0xffffffull;
+  return u == 0 ? 0x3210ull : u == 1 ? 0x3210ull : u == 2 ? 0x4320ull : u == 3 ? 0x4310ull : u == 4 ? 0x5410ull : u == 5 ? 0x5210ull
+       : u == 6 ? 0x6210ull : 0xffffull;
 }
 OD_DEV uint64_t own_cols(int u) {
-  return u == 0 ? 0xff7456ull : u == 1 ? 0x745671ull : u == 2 ? 0xff5672ull : u == 3 ? 0xf56723ull : u == 4 ? 0xff6734ull : u == 5 ? 0xf67345ull : 0xffffffull;
+  return u == 0 ? 0x4567ull : u == 1 ? 0x5671ull : u == 2 ? 0x5672ull : u == 3 ? 0x6723ull : u == 4 ? 0x6734ull : u == 5 ? 0x7345ull
+       : u == 6 ? 0x7456ull : 0xffffull;
 }
 
 // A diagonal tile waiting in LDS in accumulator layout: plane q holds registers 4q .. 4q+3
@@ -316,7 +321,7 @@ OD_DEV void chol256_block(const CholArgs& a, int z, char* lds_raw) {
   if (a.pred.scal != nullptr && (a.pred.scal[z * kScalPerMat + a.pred.slot] > a.pred.thr) != (a.pred.want != 0)) return;
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const bool diag_wave = wave == kCholDiagWave;
-  const int worker = diag_wave ? 6 : (wave < kCholDiagWave ? wave : wave - 1);
+  const int worker = diag_wave ? kCWorkers : (wave < kCholDiagWave ? wave : wave - 1);
   const uint64_t ownI = own_rows(worker), ownK = own_cols(worker);
   const int r = a.r;
   const int o = a.blk * kCholMax;
