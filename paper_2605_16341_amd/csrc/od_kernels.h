@@ -25,6 +25,7 @@ struct ClassDims {
   int m, n, r, nb;
   int64_t ldx, ldg, ldm;
   int x_bf16, g_bf16;
+  int col_fast;        // error-feedback pass: consecutive workgroups walk along a row of tiles (set by its launcher)
 };
 
 // A workspace array with one slice per matrix of the class.

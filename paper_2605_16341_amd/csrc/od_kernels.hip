@@ -1015,6 +1015,11 @@ __global__ __launch_bounds__(512, 4) void k_efx_h(ClassDims d, MatPtrs ptrs, con
   extern __shared__ __align__(16) char lds[];
   const int tiles_i = (d.m + TI - 1) / TI;
   int ti = blockIdx.x % tiles_i, tj = blockIdx.x / tiles_i;
+  if (d.col_fast) {
+    const int tiles_jj = (d.n + TJ - 1) / TJ;
+    tj = blockIdx.x % tiles_jj;
+    ti = blockIdx.x / tiles_jj;
+  }
   if (d.r > 256) {
     // Long K loops re-read the panels of P, R and Q often enough to matter: bands of eight tile
     // columns, row-major inside a band, one contiguous range of that order per XCD, so that the
@@ -1163,6 +1168,11 @@ __global__ __launch_bounds__(128 * WI, (WI == 2 ? 2 : 1)) void k_efx_d(ClassDims
   extern __shared__ __align__(16) char lds[];
   const int tiles_i = (d.m + TI - 1) / TI;
   int ti = blockIdx.x % tiles_i, tj = blockIdx.x / tiles_i;
+  if (d.col_fast) {
+    const int tiles_jj = (d.n + TJ - 1) / TJ;
+    tj = blockIdx.x % tiles_jj;
+    ti = blockIdx.x / tiles_jj;
+  }
   if (d.r > 256) {
     // bands of eight tile columns, one contiguous range of that order per XCD (see k_efx_h)
     const int tiles_j = (d.n + TJ - 1) / TJ;
@@ -1336,7 +1346,7 @@ __global__ __launch_bounds__(128 * WI, (WI == 2 ? 2 : 1)) void k_efx_d(ClassDims
 // ------------------------------------------------------------------------------------
 template <bool TRANS, int NT, int SB>
 __global__ __launch_bounds__(512, 1) void k_stream_d(ClassDims d, MatPtrs ptrs, const float* scal, WsArr part, int splits, HalfArr fh, HalfArr rh,
-                                                  int* info) {
+                                                  int* info, int rotate) {
   constexpr int MT = 128, KT = 32, ROWB = 64, SR = 3;
   constexpr int FN = NT / 128;                                // 32-column accumulator blocks per wave
   constexpr int B_STAGE = NT * ROWB, RAW_M = MT * KT * 4, RAW_G = MT * KT * 2, RAW_STAGE = RAW_M + RAW_G;
@@ -1362,6 +1372,15 @@ __global__ __launch_bounds__(512, 1) void k_stream_d(ClassDims d, MatPtrs ptrs, 
   int kend;
   const int kbeg = split_begin(Kdim, splits, KT, split, &kend);
   const int nsteps = kend > kbeg ? (kend - kbeg + KT - 1) / KT : 0;
+  // rotated k order (the projection of one matrix whose rows lie a multiple of 32 KB apart):
+  // every row panel starts its k range `rotate` steps after the panel before it, otherwise all
+  // panels would read the same columns - the same memory channels - in lockstep
+  const int rot = (rotate > 0 && nsteps > 0) ? (int)(((int64_t)tm * rotate) % nsteps) : 0;
+  auto k_of = [&](int step) {
+    int s2 = step + rot;
+    if (s2 >= nsteps) s2 -= nsteps;
+    return kbeg + s2 * KT;
+  };
   const float sa = b_scale(d, scal, z);
   const uint32_t lds0 = lds_offset_of(lds);
   const float* Mz = ptrs.M[z];
@@ -1403,13 +1422,13 @@ __global__ __launch_bounds__(512, 1) void k_stream_d(ClassDims d, MatPtrs ptrs, 
   }
   auto issue_f = [&](int step) {
     const uint32_t boff = (uint32_t)(step % SB) * B_STAGE;
-    const int k0 = min(kbeg + step * KT, Kdim - KT);          // a clamped step only meets zeros of the other operand
+    const int k0 = min(k_of(step), Kdim - KT);                // a clamped step only meets zeros of the other operand
 #pragma unroll
     for (int q = 0; q < kCB; ++q) dma16(fp[q] + k0, foff[q] + boff);
   };
   auto issue_raw = [&](int step) {
     const uint32_t boff = (uint32_t)(step % SR) * RAW_STAGE;
-    const int k0 = kbeg + step * KT;
+    const int k0 = k_of(step);
 #pragma unroll
     for (int q = 0; q < kNR; ++q) {
       const bool isg = q == 2;
@@ -1425,7 +1444,7 @@ __global__ __launch_bounds__(512, 1) void k_stream_d(ClassDims d, MatPtrs ptrs, 
   auto convert = [&](int step) {
     const char* raw = lds + OFF_RAW + (step % SR) * RAW_STAGE;
     char* abuf = lds + OFF_A + (step & 1) * A_BYTES;
-    const int k0 = kbeg + step * KT;
+    const int k0 = k_of(step);
     const int kld = TRANS ? min(k0, d.m - KT) : min(k0, d.n - KT);       // where the loaded tile really starts
 #pragma unroll
     for (int h = 0; h < 2; ++h) {
@@ -1665,7 +1684,11 @@ static hipError_t stream_d_t(const ClassDims& d, const MatPtrs& ptrs, const floa
   if (e != hipSuccess) return e;
   const int Mdim = TRANS ? d.n : d.m;
   dim3 grid(((Mdim + 127) / 128) * ((d.r + NT - 1) / NT), splits, d.nb);
-  launch_timed(k_stream_d<TRANS, NT, SB>, grid, dim3(512), lds, st, d, ptrs, scal, part, splits, fh, rh, info);
+  // rotated k order for the projection of a single matrix at 8192 columns (see the kernel): 120 ->
+  // 102 us at r = 256.  With several matrices in flight the order does not matter, and the
+  // 512-column tiles of the larger ranks are not waiting for memory (no gain measured there).
+  const int rotate = (!TRANS && NT == 256 && d.nb == 1 && (d.ldm * (int64_t)sizeof(float)) % 32768 == 0) ? 1 : 0;
+  launch_timed(k_stream_d<TRANS, NT, SB>, grid, dim3(512), lds, st, d, ptrs, scal, part, splits, fh, rh, info, rotate);
   OD_CHECK_LAUNCH();
   return hipSuccess;
 }
@@ -2014,8 +2037,14 @@ static hipError_t efx_n(const ClassDims& d, const MatPtrs& ptrs, const float* sc
                   : efx_t<Num, false, false>(d, ptrs, scal, info, p, rr, a_coef, b_coef, lr, st);
 }
 template <bool XBF, bool GBF>
-static hipError_t efx_h_t(const ClassDims& d, const MatPtrs& ptrs, const float* scal, int* info, HalfArr ph, HalfArr rh, HalfArr qh,
+static hipError_t efx_h_t(const ClassDims& d_in, const MatPtrs& ptrs, const float* scal, int* info, HalfArr ph, HalfArr rh, HalfArr qh,
                           float a_coef, float b_coef, float lr, hipStream_t st) {
+  ClassDims d = d_in;
+  // up to r = 256 (above, the XCD-aware band order takes over) consecutive workgroups walk along a
+  // row of tiles, i.e. through consecutive addresses of M, G, X, instead of down a column of tiles
+  // whose rows lie a whole leading dimension apart: 8192 x 8192: 172 -> 156 us at r = 16, 233 ->
+  // 224 us at r = 256; no difference at 4096 x 4096
+  d.col_fast = d.r <= 256 ? 1 : 0;
   dim3 grid(((d.m + 127) / 128) * ((d.n + 127) / 128), 1, d.nb);
   const bool stream = d.r > 256 || (int64_t)d.m * d.n * d.nb >= ((int64_t)48 << 20);
   // ranks that are whole 32-deep steps take the direct-to-LDS kernel
