@@ -136,3 +136,26 @@ def test_binding_phase_and_diagnostic_names_follow_the_header():
     assert [int(v) for _, v in phases] == list(range(len(phases)))
     assert int(re.search(r"ORTHDION_NPHASE\s*=\s*(\d+)", text).group(1)) == len(binding.PHASES)
     assert int(re.search(r"ORTHDION_NDIAG\s*=\s*(\d+)", text).group(1)) == len(binding.DIAG)
+
+
+def test_groups_follow_the_size_of_the_set():
+    """Host-side planning of orthdion_config.groups: the library takes two groups for several
+    matrices of 2^26 to 2^29 elements in all, one otherwise; a caller's 2 needs at least two launch
+    batches; the workspace never shrinks with the choice."""
+    from paper_2605_16341_amd import synth
+
+    def groups(shapes, r, asked):
+        h = b.orthdion_create(shapes, r, b.ORTHDION_BF16, b.ORTHDION_BF16, groups=asked)
+        got, ws = b.orthdion_get_groups(h), b.orthdion_workspace_bytes(h)
+        b.orthdion_destroy(h)
+        return got, ws
+
+    c3, c4 = synth.WORKLOADS["C3"], synth.WORKLOADS["C4"]
+    assert groups(c4.shapes, c4.r, 0)[0] == 2 and groups(c4.shapes, c4.r, 1)[0] == 1
+    assert groups(c3.shapes, c3.r, 0)[0] == 1 and groups(c3.shapes, c3.r, 2)[0] == 2
+    assert groups([(8192, 8192)], 256, 0)[0] == 1 and groups([(8192, 8192)], 256, 2)[0] == 1      # one batch
+    assert groups([(8192, 8192)] * 3, 256, 2)[0] == 1                                             # still one batch
+    small = [(256, 128), (128, 512), (96, 96)]
+    assert groups(small, 32, 0)[0] == 1 and groups(small, 32, 2)[0] == 2
+    assert groups(small, 32, 2)[1] >= groups(small, 32, 1)[1]
+    assert b.load().orthdion_get_groups(None) == 0
