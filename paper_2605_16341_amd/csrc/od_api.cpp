@@ -24,9 +24,9 @@ constexpr size_t kAlign = 256;
 // Two groups by default between these numbers of matrix elements.  A set below is a chain of
 // short launches, where the fork and join of the second stream cost more than the overlap
 // returns.  A set above comes in launch batches of many matrices, whose kernels fill the chip
-// by themselves: side by side they mostly compete (measured on 96 matrices of rank 512: 2 % less
-// time per step, and no kernel's time stamps mean anything any more), whereas a few matrices of
-// large rank gain 13 %: there the Cholesky chains and the one-matrix launches leave room.
+// by themselves: side by side they mostly compete (measured on 96 matrices of rank 512: 2 to 4 %
+// less time per step, and no kernel's time stamps mean anything any more), whereas a few matrices
+// of large rank gain 13 %: there the Cholesky chains and the one-matrix launches leave room.
 constexpr double kGroupMinElements = 64.0 * 1024 * 1024;
 constexpr double kGroupMaxElements = 512.0 * 1024 * 1024;
 
