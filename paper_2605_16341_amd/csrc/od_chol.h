@@ -1,5 +1,5 @@
 // Cholesky factorisation and triangular inverse of one SPD block of up to 256 x 256 in a
-// single workgroup (4 waves):  G = T^T T with T upper triangular, W = T^-1.
+// single workgroup (8 waves):  G = T^T T with T upper triangular, W = T^-1.
 //
 // Used by the CholeskyQR orthogonalisation (orth() of Alg. 1 lines 2 and 4): T is the
 // triangular factor of the thin QR, W turns the triangular solve into a product.
